@@ -1,0 +1,6 @@
+"""fp64 CPU oracle (test infrastructure only; never imported by the product path)."""
+from .uniprefill_oracle import *  # noqa: F401,F403
+from .uniprefill_oracle import (  # noqa: F401
+    SCORE_FLOOR, importance_scores, quantise_scores, phi, packed_keys, forced_mask, kept_count,
+    block_kept_counts, plan, select_tokens, compact, scatter, sparsify, block_mass, select_blocks_top_p,
+)

@@ -1,0 +1,243 @@
+"""CPU oracle for the UniPrefill block-wise token-sparsification operator.
+
+TEST INFRASTRUCTURE ONLY.  This is a plain, slow, fp64 numpy statement of what
+the operator computes.  Only the test-suite, the smoke check and the benchmark's
+``cpu_baseline`` leg may import it; the product path never does, and it shares
+no code with the HIP kernels.
+
+What is computed, step by step (paper section / equation in brackets):
+
+1. token importance [Token Importance Estimation, Eq. 2-3; kernel-design
+   paragraph of "Fused Kernel and vLLM Integration"]: for every sequence of the
+   packed batch, every query head and each of the last n query rows, the
+   causal softmax over the *whole* visible key sequence of q.k/sqrt(d_k);
+   the per-token score is the mean of those attention weights over the n rows
+   and over the heads.
+2. quantisation: the score is carried as a 32-bit float (the key encoding of
+   Eq. 14 acts on float bits); means below 2**-64 are floored to +0 so that
+   fp32 underflow is a *defined* tie rather than an accident.
+3. block partition [Token Importance Estimation: non-overlapping blocks of G
+   tokens per sequence, ragged tail] and forced retention of the first A
+   tokens and the last n tokens [Top-p Token Selection, last sentence; expansion
+   kernel in the kernel-design paragraph].
+4. block-local top-k by keep ratio (the selection rule of this build's target;
+   the paper's own block-level top-p rule is ``select_blocks_top_p`` below),
+   ordered with the packed integer key of Eq. 14, index complemented so that a
+   descending order prefers the lower index among equal scores.
+5. compaction of hidden states / position ids onto the kept rows [Sparsity
+   Propagation, Eq. 7] and the inverse scatter [Eq. 8].
+
+Pins (see tests/test_oracle_*.py): softmax row sums, harmonic closed form for
+Q = 0, a library attention routine with V = I, shift/permutation invariances,
+exact kept counts, brute-force subset enumeration, identity at ratio 1,
+gather/scatter round trips, varlen == concatenation, monotonicity of phi.
+End-to-end model accuracy (RULER) is **parity unpinned**: it needs the dataset
+and model weights, which are not available.
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+
+SCORE_FLOOR = 2.0 ** -64
+
+
+# --------------------------------------------------------------------------- #
+# 1. token importance  (Eq. 2, Eq. 3; causal mask per the kernel-design text)
+# --------------------------------------------------------------------------- #
+def importance_scores(q, k, cu_seqlens, *, n_obs, scale=None):
+    """Per-token importance o_i in float64 (not yet quantised).
+
+    q : [T, Hq, D] float array (only the last min(n_obs, N_r) rows of each
+        sequence are read), k : [T, Hkv, D] float array, cu_seqlens : [R+1].
+    Query head h reads kv head h // (Hq // Hkv).
+    """
+    q = np.asarray(q)
+    k = np.asarray(k)
+    cu = np.asarray(cu_seqlens, dtype=np.int64)
+    T, Hq, D = q.shape
+    Hkv = k.shape[1]
+    assert k.shape[0] == T and k.shape[2] == D and Hq % Hkv == 0
+    group = Hq // Hkv
+    if scale is None:
+        scale = 1.0 / math.sqrt(D)          # Eq. 2: logits divided by sqrt(d_k)
+    o = np.zeros(T, dtype=np.float64)
+    for r in range(len(cu) - 1):
+        c0, c1 = int(cu[r]), int(cu[r + 1])
+        N = c1 - c0
+        if N == 0:
+            continue
+        n_eff = min(int(n_obs), N)
+        Kr = k[c0:c1].astype(np.float64)                 # [N, Hkv, D]
+        Qw = q[c1 - n_eff:c1].astype(np.float64)         # [n_eff, Hq, D]
+        qpos = np.arange(N - n_eff, N)                   # local position of each query row
+        visible = np.arange(N)[None, :] <= qpos[:, None]  # key i visible to row j iff i <= j
+        colsum = np.zeros(N, dtype=np.float64)
+        for h in range(Hq):
+            S = scale * (Qw[:, h, :] @ Kr[:, h // group, :].T)   # partial GEMM, [n_eff, N]
+            S[~visible] = -np.inf
+            S -= S.max(axis=1, keepdims=True)
+            P = np.exp(S)
+            P /= P.sum(axis=1, keepdims=True)            # softmax over the complete key sequence
+            colsum += P.sum(axis=0)
+        o[c0:c1] = colsum / (n_eff * Hq)                 # Eq. 3 mean over rows; mean over heads
+    return o
+
+
+def quantise_scores(o):
+    """fp64 score -> the fp32 value selection sees; values below 2**-64 become +0."""
+    o = np.asarray(o, dtype=np.float64)
+    out = o.astype(np.float32)
+    out[o < SCORE_FLOOR] = np.float32(0.0)
+    return out
+
+
+# --------------------------------------------------------------------------- #
+# 2. order-preserving key encoding  (Eq. 14)
+# --------------------------------------------------------------------------- #
+def phi(x):
+    """Monotone map from float32 to uint32: flip the sign bit of non-negative
+    floats, flip all bits of negative floats (sign taken from the sign bit)."""
+    bits = np.asarray(x, dtype=np.float32).view(np.uint32)
+    neg = (bits >> np.uint32(31)) == 1
+    return np.where(neg, bits ^ np.uint32(0xFFFFFFFF), bits ^ np.uint32(0x80000000)).astype(np.uint32)
+
+
+def packed_keys(scores_f32, forced, block_size):
+    """(phi(score) << 32) | (G-1-local_index) for the tokens of one block.
+
+    Forced tokens take the all-ones upper word, above every finite score.  The
+    paper packs the plain index; the index is complemented here so that the
+    descending sort breaks score ties toward the lower index."""
+    s = np.asarray(scores_f32, dtype=np.float32)
+    L = s.shape[0]
+    hi = phi(s).astype(np.uint64)
+    hi = np.where(np.asarray(forced, dtype=bool), np.uint64(0xFFFFFFFF), hi)
+    lo = (np.uint64(block_size - 1) - np.arange(L, dtype=np.uint64))
+    return (hi << np.uint64(32)) | lo
+
+
+# --------------------------------------------------------------------------- #
+# 3. block partition, forced tokens, kept counts
+# --------------------------------------------------------------------------- #
+def forced_mask(N, n_obs, n_sink):
+    """True for the first A tokens and the last n tokens of a length-N sequence."""
+    i = np.arange(N)
+    return (i < n_sink) | (i >= N - n_obs)
+
+
+def kept_count(L, F, rho):
+    """Tokens kept in a block of L tokens, F of them forced, at keep ratio rho.
+
+    rho is a float32 widened to double; rho*L is then exact, so the ceiling is
+    unambiguous."""
+    want = math.ceil(float(np.float32(rho)) * L)
+    want = min(L, max(1, want))
+    return max(want, F)
+
+
+def block_kept_counts(N, block_size, n_obs, n_sink, rho):
+    """k_g for every block of one sequence."""
+    f = forced_mask(N, n_obs, n_sink)
+    out = []
+    for lo in range(0, N, block_size):
+        hi = min(N, lo + block_size)
+        out.append(kept_count(hi - lo, int(f[lo:hi].sum()), rho))
+    return out
+
+
+def plan(cu_seqlens, keep_ratio, *, block_size, n_obs, n_sink):
+    """Closed-form output layout: new_cu_seqlens (int32 [R+1])."""
+    cu = np.asarray(cu_seqlens, dtype=np.int64)
+    new_cu = np.zeros(len(cu), dtype=np.int32)
+    for r in range(len(cu) - 1):
+        N = int(cu[r + 1] - cu[r])
+        new_cu[r + 1] = new_cu[r] + sum(block_kept_counts(N, block_size, n_obs, n_sink, keep_ratio[r]))
+    return new_cu
+
+
+# --------------------------------------------------------------------------- #
+# 4. block-local top-k selection
+# --------------------------------------------------------------------------- #
+def select_tokens(scores_f32, cu_seqlens, keep_ratio, *, block_size, n_obs, n_sink):
+    """kept_idx (int32, ascending global packed row ids) and new_cu_seqlens."""
+    s = np.asarray(scores_f32, dtype=np.float32)
+    cu = np.asarray(cu_seqlens, dtype=np.int64)
+    kept = []
+    new_cu = np.zeros(len(cu), dtype=np.int32)
+    for r in range(len(cu) - 1):
+        c0, c1 = int(cu[r]), int(cu[r + 1])
+        N = c1 - c0
+        f = forced_mask(N, n_obs, n_sink)
+        count = 0
+        for lo in range(0, N, block_size):
+            hi = min(N, lo + block_size)
+            fb = f[lo:hi]
+            kg = kept_count(hi - lo, int(fb.sum()), keep_ratio[r])
+            keys = packed_keys(s[c0 + lo:c0 + hi], fb, block_size)
+            order = np.argsort(keys, kind="stable")[::-1]          # descending, keys are unique
+            chosen = np.sort(order[:kg])
+            kept.append((c0 + lo + chosen).astype(np.int32))
+            count += kg
+        new_cu[r + 1] = new_cu[r] + count
+    kept_idx = np.concatenate(kept) if kept else np.zeros(0, dtype=np.int32)
+    return kept_idx.astype(np.int32), new_cu
+
+
+# --------------------------------------------------------------------------- #
+# 5. compaction and its inverse  (Eq. 7, Eq. 8)
+# --------------------------------------------------------------------------- #
+def compact(hidden, pos, kept_idx):
+    """Rows of hidden / entries of pos at kept_idx (bit copies)."""
+    idx = np.asarray(kept_idx, dtype=np.int64)
+    return np.asarray(hidden)[idx].copy(), np.asarray(pos)[idx].copy()
+
+
+def scatter(hidden_compact, kept_idx, hidden_full):
+    """Write compact rows back at kept_idx; every other row keeps its old state."""
+    out = np.array(hidden_full, copy=True)
+    out[np.asarray(kept_idx, dtype=np.int64)] = np.asarray(hidden_compact)
+    return out
+
+
+# --------------------------------------------------------------------------- #
+# whole path
+# --------------------------------------------------------------------------- #
+def sparsify(q, k, hidden, pos, cu_seqlens, keep_ratio, *, block_size, n_obs, n_sink, scale=None):
+    """score -> quantise -> select -> compact.  Returns a dict of all products."""
+    o = importance_scores(q, k, cu_seqlens, n_obs=n_obs, scale=scale)
+    s32 = quantise_scores(o)
+    kept_idx, new_cu = select_tokens(s32, cu_seqlens, keep_ratio,
+                                     block_size=block_size, n_obs=n_obs, n_sink=n_sink)
+    h_out, p_out = compact(hidden, pos, kept_idx)
+    return {"scores64": o, "scores": s32, "kept_idx": kept_idx, "new_cu_seqlens": new_cu,
+            "hidden_out": h_out, "pos_out": p_out}
+
+
+# --------------------------------------------------------------------------- #
+# the paper's own selection rule (block-level top-p, Eq. 4-5) -- next row
+# --------------------------------------------------------------------------- #
+def block_mass(o, N, block_size):
+    """Attention mass captured by each block (sum of token scores; a constant
+    1/G factor would cancel in the ratio of Eq. 5)."""
+    return np.array([o[lo:min(N, lo + block_size)].sum() for lo in range(0, N, block_size)],
+                    dtype=np.float64)
+
+
+def select_blocks_top_p(o_seq, p, *, block_size, n_obs, n_sink):
+    """Token keep-mask of one sequence under Eq. 5: the minimal prefix of
+    score-sorted blocks whose cumulative mass reaches p of the total, lifted to
+    tokens, with sinks and the query window always kept."""
+    o_seq = np.asarray(o_seq, dtype=np.float64)
+    N = o_seq.shape[0]
+    b = block_mass(o_seq, N, block_size)
+    order = np.argsort(-b, kind="stable")                # descending, ties to the lower block
+    csum = np.cumsum(b[order])
+    total = csum[-1]
+    kstar = int(np.searchsorted(csum, p * total, side="left")) + 1
+    kstar = min(kstar, len(b))
+    keep_block = np.zeros(len(b), dtype=bool)
+    keep_block[order[:kstar]] = True
+    mask = np.repeat(keep_block, block_size)[:N]
+    return mask | forced_mask(N, n_obs, n_sink)

@@ -1,0 +1,217 @@
+"""Pins for the oracle's token-importance scores (Eq. 2-3 of the paper).
+
+None of these re-types the oracle's formula: they are closed forms, invariants,
+hand-worked rationals, and a library attention routine."""
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "hand_worked_scores.txt")
+
+
+def _rand(rng, T, Hq, Hkv, D):
+    return rng.standard_normal((T, Hq, D)), rng.standard_normal((T, Hkv, D))
+
+
+def _parse_num(tok):
+    if tok.startswith("ln"):
+        return math.log(float(tok[2:]))
+    return float(Fraction(tok))
+
+
+def test_golden_hand_worked_examples():
+    """tests/golden/hand_worked_scores.txt: exact rationals worked out by hand."""
+    n_cases = 0
+    for line in open(GOLDEN):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        head, ks, exp = [p.strip() for p in line.split("|")]
+        _, N, n, qv = head.split()
+        N, n, qv = int(N), int(n), float(qv)
+        k = np.array([_parse_num(t) for t in ks.split()]).reshape(N, 1, 1)
+        q = np.full((N, 1, 1), qv)
+        want = np.array([_parse_num(t) for t in exp.split()])
+        got = oracle.importance_scores(q, k, [0, N], n_obs=n, scale=1.0)
+        np.testing.assert_allclose(got, want, rtol=1e-14, atol=0)
+        n_cases += 1
+    assert n_cases == 4
+
+
+@pytest.mark.parametrize("N,n", [(1, 128), (5, 2), (200, 128), (1000, 128), (300, 7)])
+def test_harmonic_closed_form_zero_queries(N, n):
+    """Q = 0 makes every visible logit equal, so row j gives 1/(j+1) to keys 0..j and
+    o_i = (1/n_eff) * sum_{j >= max(i, N-n_eff)} 1/(j+1)."""
+    rng = np.random.default_rng(1)
+    Hq, Hkv, D = 4, 2, 8
+    q = np.zeros((N, Hq, D))
+    k = rng.standard_normal((N, Hkv, D))
+    got = oracle.importance_scores(q, k, [0, N], n_obs=n)
+    n_eff = min(n, N)
+    want = np.array([sum(Fraction(1, j + 1) for j in range(max(i, N - n_eff), N)) / n_eff
+                     for i in range(N)], dtype=object)
+    np.testing.assert_allclose(got, np.array([float(w) for w in want]), rtol=1e-13)
+
+
+def test_equal_keys_give_harmonic_form_too():
+    """All key rows identical: logits within a row are equal whatever q is."""
+    rng = np.random.default_rng(2)
+    N, n = 77, 16
+    q = rng.standard_normal((N, 2, 4))
+    k = np.broadcast_to(rng.standard_normal((1, 1, 4)), (N, 1, 4)).copy()
+    got = oracle.importance_scores(q, k, [0, N], n_obs=n)
+    want = [sum(1.0 / (j + 1) for j in range(max(i, N - n), N)) / n for i in range(N)]
+    np.testing.assert_allclose(got, want, rtol=1e-13)
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(1, 1), (4, 4), (8, 2), (5, 1)])
+def test_against_library_attention_with_identity_values(Hq, Hkv):
+    """A library attention routine with V = I returns the attention weights
+    themselves; their mean over the window rows and heads is the score."""
+    rng = np.random.default_rng(3)
+    N, n, D = 150, 32, 16
+    q, k = _rand(rng, N, Hq, Hkv, D)
+    scale = 0.37
+    got = oracle.importance_scores(q, k, [0, N], n_obs=n, scale=scale)
+
+    tq = torch.from_numpy(q[N - n:]).permute(1, 0, 2)[None]                      # [1,Hq,n,D]
+    tk = torch.from_numpy(k).permute(1, 0, 2).repeat_interleave(Hq // Hkv, 0)[None]  # [1,Hq,N,D]
+    eye = torch.eye(N, dtype=torch.float64).expand(1, Hq, N, N)
+    rows = torch.arange(N - n, N)[:, None]
+    mask = torch.arange(N)[None, :] <= rows                                      # [n,N] True = attend
+    w = torch.nn.functional.scaled_dot_product_attention(tq, tk, eye, attn_mask=mask, scale=scale)
+    want = w.mean(dim=(0, 1, 2)).numpy()
+    np.testing.assert_allclose(got, want, rtol=1e-10, atol=1e-300)
+
+
+def test_single_row_single_head_is_plain_softmax():
+    from scipy.special import softmax
+    rng = np.random.default_rng(4)
+    N, D = 64, 8
+    q, k = _rand(rng, N, 1, 1, D)
+    got = oracle.importance_scores(q, k, [0, N], n_obs=1)
+    want = softmax((k[:, 0, :] @ q[N - 1, 0, :]) / math.sqrt(D))
+    np.testing.assert_allclose(got, want, rtol=1e-12)
+
+
+def test_scores_are_a_distribution_per_sequence():
+    rng = np.random.default_rng(5)
+    cu = [0, 40, 40, 41, 300, 500]
+    q, k = _rand(rng, 500, 4, 2, 8)
+    o = oracle.importance_scores(q, k, cu, n_obs=64)
+    assert (o >= 0).all()
+    for r in range(5):
+        if cu[r + 1] > cu[r]:
+            assert abs(o[cu[r]:cu[r + 1]].sum() - 1.0) < 1e-12
+    assert o[40] == 1.0  # a length-1 request holds all of its own mass
+
+
+def test_key_shift_invariance():
+    """Adding one vector to every key shifts each row's logits by a constant."""
+    rng = np.random.default_rng(6)
+    q, k = _rand(rng, 120, 4, 2, 8)
+    a = oracle.importance_scores(q, k, [0, 120], n_obs=20)
+    b = oracle.importance_scores(q, k + rng.standard_normal((1, 2, 8)), [0, 120], n_obs=20)
+    np.testing.assert_allclose(a, b, rtol=1e-9)
+
+
+def test_head_permutation_within_groups_is_invisible():
+    rng = np.random.default_rng(7)
+    q, k = _rand(rng, 90, 6, 2, 8)          # groups {0,1,2} and {3,4,5}
+    a = oracle.importance_scores(q, k, [0, 90], n_obs=30)
+    b = oracle.importance_scores(q[:, [2, 0, 1, 5, 4, 3], :], k, [0, 90], n_obs=30)
+    np.testing.assert_allclose(a, b, rtol=1e-12)
+
+
+def test_gqa_mapping_is_contiguous_groups():
+    """Swapping two query heads ACROSS kv groups must change the result unless
+    the kv heads are swapped as well."""
+    rng = np.random.default_rng(8)
+    q, k = _rand(rng, 60, 4, 2, 8)
+    a = oracle.importance_scores(q, k, [0, 60], n_obs=10)
+    swapped = oracle.importance_scores(q[:, [2, 3, 0, 1], :], k[:, [1, 0], :], [0, 60], n_obs=10)
+    np.testing.assert_allclose(a, swapped, rtol=1e-12)
+    wrong = oracle.importance_scores(q[:, [2, 1, 0, 3], :], k, [0, 60], n_obs=10)
+    assert np.abs(wrong - a).max() > 1e-6
+
+
+def test_last_key_gets_one_rows_weight():
+    """Only the last query row sees the last key: its score is the mean over heads of
+    that single softmax entry divided by n_eff."""
+    rng = np.random.default_rng(9)
+    N, n, D = 50, 8, 4
+    q, k = _rand(rng, N, 2, 1, D)
+    o = oracle.importance_scores(q, k, [0, N], n_obs=n)
+    w = []
+    for h in range(2):
+        logits = (k[:, 0, :] @ q[N - 1, h, :]) / math.sqrt(D)
+        e = np.exp(logits - logits.max())
+        w.append(e[-1] / e.sum())
+    assert abs(o[-1] - sum(w) / (2 * n)) < 1e-15
+
+
+def test_causal_mask_hides_later_keys():
+    """Changing a key can only change scores through rows at or after it: a change to
+    the LAST key leaves the ratio structure of earlier rows intact, and keys are never
+    influenced by queries outside the window."""
+    rng = np.random.default_rng(10)
+    N, n = 40, 5
+    q, k = _rand(rng, N, 2, 2, 4)
+    q2 = q.copy()
+    q2[:N - n] = np.nan                      # rows outside the window are never read
+    a = oracle.importance_scores(q, k, [0, N], n_obs=n)
+    b = oracle.importance_scores(q2, k, [0, N], n_obs=n)
+    np.testing.assert_array_equal(a, b)
+    # with n = 1 at position N-1 ... and n rows: row j = N-n never sees keys > N-n
+    k3 = k.copy()
+    k3[N - 1] += 5.0
+    c = oracle.importance_scores(q, k3, [0, N], n_obs=n)
+    # contribution of the first window row (j = N-n) to key 0 is unchanged: isolate it with n_obs via prefix
+    first = oracle.importance_scores(q[:N - n + 1], k[:N - n + 1], [0, N - n + 1], n_obs=1)
+    first3 = oracle.importance_scores(q[:N - n + 1], k3[:N - n + 1], [0, N - n + 1], n_obs=1)
+    np.testing.assert_array_equal(first, first3)
+    assert np.abs(c - a).max() > 1e-6
+
+
+def test_prefix_rows_decompose_the_window():
+    """The n-row score is the mean of n single-row scores, each a causal prefix problem."""
+    rng = np.random.default_rng(11)
+    N, n = 33, 6
+    q, k = _rand(rng, N, 3, 1, 4)
+    o = oracle.importance_scores(q, k, [0, N], n_obs=n)
+    acc = np.zeros(N)
+    for j in range(N - n, N):
+        acc[:j + 1] += oracle.importance_scores(q[:j + 1], k[:j + 1], [0, j + 1], n_obs=1)
+    np.testing.assert_allclose(o, acc / n, rtol=1e-12)
+
+
+def test_varlen_scores_equal_per_sequence_runs():
+    rng = np.random.default_rng(12)
+    cu = np.array([0, 1, 130, 130, 400, 657])
+    q, k = _rand(rng, 657, 4, 2, 8)
+    o = oracle.importance_scores(q, k, cu, n_obs=128)
+    for r in range(5):
+        a, b = cu[r], cu[r + 1]
+        if b > a:
+            np.testing.assert_array_equal(o[a:b], oracle.importance_scores(q[a:b], k[a:b], [0, b - a], n_obs=128))
+
+
+def test_default_scale_is_inverse_sqrt_head_dim():
+    rng = np.random.default_rng(13)
+    q, k = _rand(rng, 30, 2, 2, 16)
+    np.testing.assert_array_equal(oracle.importance_scores(q, k, [0, 30], n_obs=4),
+                                  oracle.importance_scores(q, k, [0, 30], n_obs=4, scale=0.25))
+
+
+def test_quantise_floor_and_rounding():
+    o = np.array([1.0, 2.0 ** -64, 2.0 ** -64 * (1 - 1e-12), 0.0, 1e-300, 1 / 3])
+    s = oracle.quantise_scores(o)
+    assert s.dtype == np.float32
+    np.testing.assert_array_equal(s, np.array([1.0, 2.0 ** -64, 0.0, 0.0, 0.0, np.float32(1 / 3)], dtype=np.float32))
+    assert not np.signbit(s).any()

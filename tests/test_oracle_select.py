@@ -1,0 +1,270 @@
+"""Pins for the oracle's block partition, forced keeps, key encoding, block-local
+top-k, compaction/scatter, and the paper's block-level top-p rule."""
+import itertools
+import math
+import struct
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+
+
+# ----------------------------------------------------------------------------- phi (Eq. 14)
+def test_phi_is_monotone_on_special_and_random_floats():
+    rng = np.random.default_rng(0)
+    specials = np.array([-np.inf, -3.4028235e38, -1.0, -1e-38, -1e-45, -0.0, 0.0, 1e-45, 1e-38,
+                         2.0 ** -64, 1.0, 3.4028235e38, np.inf], dtype=np.float32)
+    rnd = rng.standard_normal(4096).astype(np.float32) * np.float32(10.0) ** rng.integers(-30, 30, 4096).astype(np.float32)
+    x = np.unique(np.concatenate([specials, rnd]))          # sorted ascending, -0.0/+0.0 collapse
+    p = oracle.phi(x).astype(np.int64)
+    assert (np.diff(p) > 0).all()
+    # -0.0 sorts directly below +0.0 (sign taken from the sign bit)
+    assert oracle.phi(np.float32(-0.0)) + 1 == oracle.phi(np.float32(0.0))
+
+
+def test_phi_matches_bit_definition():
+    for v in [0.0, 1.0, 0.5, 1e-20, -1.0, -2.5]:
+        bits = struct.unpack("<I", struct.pack("<f", v))[0]
+        want = bits ^ (0xFFFFFFFF if v < 0 else 0x80000000)
+        assert int(oracle.phi(np.float32(v))) == want
+
+
+def test_packed_key_order_is_forced_then_score_then_lower_index():
+    s = np.array([0.5, 0.5, 0.9, 0.0, 0.9, 0.1], dtype=np.float32)
+    forced = np.array([0, 0, 0, 1, 0, 0], dtype=bool)
+    keys = oracle.packed_keys(s, forced, 8)
+    order = list(np.argsort(keys)[::-1])
+    assert order == [3, 2, 4, 0, 1, 5]
+
+
+# ----------------------------------------------------------------------------- counts
+def test_kept_count_values_of_the_five_configs():
+    assert oracle.kept_count(64, 0, np.float32(0.5)) == 32
+    assert oracle.kept_count(128, 0, np.float32(0.3)) == 39      # 0.3f * 128 = 38.400002 -> 39
+    assert oracle.kept_count(128, 0, np.float32(0.25)) == 32
+    assert oracle.kept_count(64, 0, np.float32(0.4)) == 26       # 0.4f * 64 = 25.600000381 -> 26
+    assert oracle.kept_count(64, 0, np.float32(1.0)) == 64
+    assert oracle.kept_count(7, 0, np.float32(1e-6)) == 1        # never zero
+    assert oracle.kept_count(64, 50, np.float32(0.5)) == 50      # forced tokens fill the quota first
+    assert oracle.kept_count(5, 5, np.float32(0.2)) == 5
+
+
+def test_total_kept_of_full_size_configs_closed_form():
+    """Config 1: 64 blocks of 64: 2 sink blocks + 2 window blocks fully kept, 60 x 32.
+    Config 2: 256 blocks of 128: 1 + 1 fully kept, 254 x 39.  Config 4: 1024 blocks: 2 x 128 + 1022 x 32."""
+    assert oracle.plan([0, 4096], [0.5], block_size=64, n_obs=128, n_sink=128)[-1] == 4 * 64 + 60 * 32 == 2176
+    assert oracle.plan([0, 32768], [0.3], block_size=128, n_obs=128, n_sink=128)[-1] == 2 * 128 + 254 * 39 == 10162
+    assert oracle.plan([0, 131072], [0.25], block_size=128, n_obs=128, n_sink=128)[-1] == 2 * 128 + 1022 * 32 == 32960
+
+
+def test_forced_mask():
+    m = oracle.forced_mask(10, 3, 2)
+    assert list(np.nonzero(m)[0]) == [0, 1, 7, 8, 9]
+    assert oracle.forced_mask(5, 128, 128).all()
+    assert oracle.forced_mask(256, 128, 128).all()
+    assert not oracle.forced_mask(257, 128, 128).all()
+
+
+# ----------------------------------------------------------------------------- brute force
+def _brute_force_block(scores, forced, k):
+    """All k-subsets; best = most forced tokens, then largest score sum under exact
+    rational arithmetic, then lexicographically smallest index tuple."""
+    from fractions import Fraction
+    best, best_key = None, None
+    for sub in itertools.combinations(range(len(scores)), k):
+        key = (-sum(int(forced[i]) for i in sub), -sum(Fraction(float(scores[i])) for i in sub), sub)
+        if best_key is None or key < best_key:
+            best, best_key = sub, key
+    return list(best)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_selection_against_subset_enumeration(seed):
+    rng = np.random.default_rng(seed)
+    G = 8
+    N = int(rng.integers(1, 40))
+    n_obs, n_sink = int(rng.integers(0, 5)), int(rng.integers(0, 5))
+    rho = np.float32(rng.uniform(0.05, 1.0))
+    kind = seed % 4
+    if kind == 0:
+        s = rng.random(N).astype(np.float32)
+    elif kind == 1:
+        s = rng.integers(0, 3, N).astype(np.float32) / 4          # many exact ties
+    elif kind == 2:
+        s = np.zeros(N, dtype=np.float32)                         # all-zero block
+    else:
+        s = np.full(N, 0.25, dtype=np.float32)                    # all-equal block
+    kept, new_cu = oracle.select_tokens(s, [0, N], [rho], block_size=G, n_obs=n_obs, n_sink=n_sink)
+    f = oracle.forced_mask(N, n_obs, n_sink)
+    want = []
+    for lo in range(0, N, G):
+        hi = min(N, lo + G)
+        kg = oracle.kept_count(hi - lo, int(f[lo:hi].sum()), rho)
+        want += [lo + i for i in _brute_force_block(s[lo:hi], f[lo:hi], kg)]
+    assert list(kept) == want
+    assert new_cu[-1] == len(want)
+
+
+def test_selection_equals_tuple_sort_on_random_blocks():
+    rng = np.random.default_rng(100)
+    for _ in range(30):
+        G = int(rng.choice([32, 64, 128]))
+        N = int(rng.integers(1, 700))
+        s = (rng.random(N) ** 8).astype(np.float32)
+        s[rng.random(N) < 0.3] = 0.0
+        rho = np.float32(rng.uniform(0.1, 1.0))
+        kept, _ = oracle.select_tokens(s, [0, N], [rho], block_size=G, n_obs=100, n_sink=50)
+        f = oracle.forced_mask(N, 100, 50)
+        want = []
+        for lo in range(0, N, G):
+            hi = min(N, lo + G)
+            kg = oracle.kept_count(hi - lo, int(f[lo:hi].sum()), rho)
+            order = sorted(range(lo, hi), key=lambda i: (not f[i], -float(s[i]), i))
+            want += sorted(order[:kg])
+        assert list(kept) == want
+
+
+# ----------------------------------------------------------------------------- invariants
+def _random_batch(rng, R=6, maxlen=500):
+    lengths = rng.integers(0, maxlen, R)
+    lengths[rng.integers(0, R)] = 1
+    cu = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int32)
+    T = int(cu[-1])
+    s = (rng.random(T) ** 6).astype(np.float32)
+    ratio = rng.uniform(0.1, 1.0, R).astype(np.float32)
+    return cu, s, ratio
+
+
+@pytest.mark.parametrize("G", [32, 64, 128])
+def test_kept_idx_shape_counts_and_forced(G):
+    rng = np.random.default_rng(G)
+    cu, s, ratio = _random_batch(rng)
+    kept, new_cu = oracle.select_tokens(s, cu, ratio, block_size=G, n_obs=128, n_sink=128)
+    assert (np.diff(kept) > 0).all() and kept.dtype == np.int32
+    assert kept.min() >= 0 and kept.max() < cu[-1]
+    np.testing.assert_array_equal(new_cu, oracle.plan(cu, ratio, block_size=G, n_obs=128, n_sink=128))
+    keptset = set(kept.tolist())
+    for r in range(len(cu) - 1):
+        N = cu[r + 1] - cu[r]
+        inside = kept[(kept >= cu[r]) & (kept < cu[r + 1])]
+        assert len(inside) == new_cu[r + 1] - new_cu[r]
+        counts = oracle.block_kept_counts(int(N), G, 128, 128, ratio[r])
+        for g, kg in enumerate(counts):
+            lo = cu[r] + g * G
+            assert ((inside >= lo) & (inside < lo + G)).sum() == kg
+        for i in np.nonzero(oracle.forced_mask(int(N), 128, 128))[0]:
+            assert int(cu[r] + i) in keptset
+        if N <= 256:
+            assert len(inside) == N
+
+
+def test_identity_at_keep_ratio_one():
+    rng = np.random.default_rng(3)
+    cu, s, _ = _random_batch(rng)
+    kept, new_cu = oracle.select_tokens(s, cu, np.ones(len(cu) - 1, np.float32), block_size=64, n_obs=128, n_sink=128)
+    np.testing.assert_array_equal(kept, np.arange(cu[-1], dtype=np.int32))
+    np.testing.assert_array_equal(new_cu, cu)
+    h = rng.integers(0, 65536, (cu[-1], 16)).astype(np.uint16)
+    p = rng.integers(0, 1 << 30, cu[-1]).astype(np.int32)
+    ho, po = oracle.compact(h, p, kept)
+    np.testing.assert_array_equal(ho, h)
+    np.testing.assert_array_equal(po, p)
+
+
+def test_gather_scatter_round_trips():
+    rng = np.random.default_rng(4)
+    cu, s, ratio = _random_batch(rng)
+    T = int(cu[-1])
+    kept, _ = oracle.select_tokens(s, cu, ratio, block_size=32, n_obs=16, n_sink=8)
+    h = rng.integers(0, 65536, (T, 24)).astype(np.uint16)
+    hc, _ = oracle.compact(h, np.arange(T, dtype=np.int32), kept)
+    np.testing.assert_array_equal(oracle.scatter(hc, kept, h), h)
+    mask = np.zeros(T, bool)
+    mask[kept] = True
+    np.testing.assert_array_equal(oracle.scatter(hc, kept, np.zeros_like(h)), h * mask[:, None])
+    x = rng.integers(0, 65536, hc.shape).astype(np.uint16)
+    back, _ = oracle.compact(oracle.scatter(x, kept, h), np.arange(T, dtype=np.int32), kept)
+    np.testing.assert_array_equal(back, x)
+    # rows that were dropped keep their old state (Eq. 8)
+    out = oracle.scatter(x, kept, h)
+    np.testing.assert_array_equal(out[~mask], h[~mask])
+
+
+def test_varlen_batch_equals_concatenated_single_runs():
+    rng = np.random.default_rng(5)
+    cu, s, ratio = _random_batch(rng, R=7)
+    kept, new_cu = oracle.select_tokens(s, cu, ratio, block_size=64, n_obs=128, n_sink=128)
+    parts = []
+    for r in range(len(cu) - 1):
+        a, b = int(cu[r]), int(cu[r + 1])
+        kr, nc = oracle.select_tokens(s[a:b], [0, b - a], ratio[r:r + 1], block_size=64, n_obs=128, n_sink=128)
+        parts.append(kr + a)
+        assert nc[-1] == new_cu[r + 1] - new_cu[r]
+    np.testing.assert_array_equal(kept, np.concatenate(parts))
+
+
+def test_end_to_end_small_shrunk_configs_are_consistent():
+    """sparsify() on shrunk versions of the five workloads: structure invariants hold together."""
+    for idx, shrink in [(1, 8), (2, 64), (3, 64), (4, 256), (5, 16)]:
+        w = workloads.make_config(idx, shrink=shrink, hidden_dim=32)
+        q = workloads.bf16_bits_to_f32(w.q)
+        k = workloads.bf16_bits_to_f32(w.k)
+        out = oracle.sparsify(q, k, w.hidden, w.pos, w.cu_seqlens, w.keep_ratio,
+                              block_size=w.block_size, n_obs=w.n_obs, n_sink=w.n_sink)
+        assert (np.diff(out["kept_idx"]) > 0).all()
+        np.testing.assert_array_equal(out["new_cu_seqlens"],
+                                      oracle.plan(w.cu_seqlens, w.keep_ratio, block_size=w.block_size,
+                                                  n_obs=w.n_obs, n_sink=w.n_sink))
+        np.testing.assert_array_equal(out["hidden_out"], w.hidden[out["kept_idx"]])
+        np.testing.assert_array_equal(out["pos_out"], w.pos[out["kept_idx"]])
+        for r in range(w.num_seqs):
+            a, b = w.cu_seqlens[r], w.cu_seqlens[r + 1]
+            assert abs(out["scores64"][a:b].sum() - 1.0) < 1e-10
+
+
+def test_higher_score_never_loses_to_lower_score_in_same_block():
+    rng = np.random.default_rng(6)
+    N, G = 1000, 64
+    s = rng.random(N).astype(np.float32)
+    kept, _ = oracle.select_tokens(s, [0, N], [np.float32(0.3)], block_size=G, n_obs=0, n_sink=0)
+    mask = np.zeros(N, bool)
+    mask[kept] = True
+    for lo in range(0, N, G):
+        blk = slice(lo, min(N, lo + G))
+        if (~mask[blk]).any():
+            assert s[blk][mask[blk]].min() >= s[blk][~mask[blk]].max()
+
+
+# ----------------------------------------------------------------------------- paper's top-p rule (Eq. 5-6)
+def test_top_p_keeps_minimal_prefix_with_mass_at_least_p():
+    rng = np.random.default_rng(7)
+    N, G = 1000, 64
+    o = rng.random(N) ** 10
+    o /= o.sum()
+    for p in [0.5, 0.9, 0.99]:
+        mask = oracle.select_blocks_top_p(o, p, block_size=G, n_obs=0, n_sink=0)
+        b = oracle.block_mass(o, N, G)
+        kb = np.array([mask[lo] for lo in range(0, N, G)])
+        assert b[kb].sum() >= p * b.sum() - 1e-15            # Eq. 6: dropped mass <= 1 - p
+        # minimal: dropping the smallest kept block falls below p
+        assert b[kb].sum() - b[kb].min() < p * b.sum()
+        # greedy: every kept block outweighs every dropped block
+        if (~kb).any():
+            assert b[kb].min() >= b[~kb].max()
+
+
+def test_top_p_forces_sinks_and_window_and_p1_keeps_all_positive_mass():
+    rng = np.random.default_rng(8)
+    N, G = 700, 32
+    o = rng.random(N)
+    o[100:400] = 0.0
+    o /= o.sum()
+    m = oracle.select_blocks_top_p(o, 0.3, block_size=G, n_obs=50, n_sink=20)
+    assert m[:20].all() and m[-50:].all()
+    m1 = oracle.select_blocks_top_p(o, 1.0, block_size=G, n_obs=0, n_sink=0)
+    b = oracle.block_mass(o, N, G)
+    for g, lo in enumerate(range(0, N, G)):
+        if b[g] > 0:
+            assert m1[lo]
