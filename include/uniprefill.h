@@ -1,0 +1,162 @@
+/*
+ * uniprefill.h -- C ABI of the UniPrefill block-wise token-sparsification operator
+ * for AMD MI355X (gfx950).
+ *
+ * The operator works on a packed continuous-batching batch: R sequences stored
+ * back to back ("variable-length packed token representation indexed by
+ * cu_seqlens", section "Fused Kernel and vLLM Integration", kernel-design
+ * paragraph).  Sequence r owns packed rows [cu_seqlens[r], cu_seqlens[r+1]).
+ *
+ * Conventions shared by every entry point
+ *   - "dev"  pointers are device (HBM) addresses, "host" pointers are host
+ *     addresses.  Unmarked data pointers (q, k, hidden, pos, scores, kept_idx,
+ *     workspace, outputs) are device addresses.
+ *   - Ownership: the caller owns every buffer.  The library never allocates or
+ *     frees device memory, keeps no state between calls, and only enqueues work
+ *     on `stream` (a hipStream_t passed as void*, NULL = the null stream).  It
+ *     never synchronises and never copies device->host; the host copies of
+ *     cu_seqlens / keep_ratio that serving engines already hold are passed in.
+ *   - Errors: every entry point returns an up_status.  All argument errors are
+ *     found on the host before anything is launched, so an error return means
+ *     no kernel ran.  Nothing throws or aborts.
+ *       UP_ERR_NULL        a required pointer is NULL
+ *       UP_ERR_SHAPE       cu_seqlens[0] != 0, cu_seqlens decreasing, or
+ *                          cu_seqlens[R] != total_tokens; negative sizes
+ *       UP_ERR_RANGE       keep ratio not in (0,1] or NaN; block_size not in
+ *                          {32,64,128}; n_obs < 1 or > 1024; n_sink < 0;
+ *                          total_kept inconsistent with the plan
+ *       UP_ERR_UNSUPPORTED head_dim != 128; num_q_heads % num_kv_heads != 0;
+ *                          more than 64 query heads per kv head; unknown dtype
+ *       UP_ERR_ALIGN       a base pointer is not 16-byte aligned or a row stride
+ *                          in bytes is not a multiple of 16
+ *       UP_ERR_WORKSPACE   workspace is NULL or smaller than uniprefill_plan says
+ *       UP_ERR_HIP         a launch failed (hipGetLastError after the launch)
+ *   - Zero-length sequences are legal and produce nothing; total_tokens == 0 is
+ *     legal and launches nothing.
+ *   - Layouts: q is [T, num_q_heads, head_dim] with row stride q_row_stride
+ *     elements between tokens (heads contiguous inside a row); k likewise with
+ *     num_kv_heads and k_row_stride; hidden is [T, hidden_dim] with row stride
+ *     hidden_row_stride; compacted outputs are dense with the same row stride
+ *     convention (hidden_out uses hidden_row_stride as well).
+ *     Query head h reads kv head h / (num_q_heads / num_kv_heads).
+ */
+#ifndef UNIPREFILL_H
+#define UNIPREFILL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  UP_OK = 0,
+  UP_ERR_NULL = 1,
+  UP_ERR_SHAPE = 2,
+  UP_ERR_RANGE = 3,
+  UP_ERR_UNSUPPORTED = 4,
+  UP_ERR_ALIGN = 5,
+  UP_ERR_WORKSPACE = 6,
+  UP_ERR_HIP = 7
+} up_status;
+
+typedef enum { UP_BF16 = 0, UP_F32 = 1 } up_dtype;
+
+/* Problem description.  Hyper-parameters follow the paper's notation:
+ * G = block_size, n = n_obs (observation window: the last n query positions of
+ * each sequence), A = n_sink (attention-sink tokens always retained).  The
+ * paper's defaults are G = 64, n = 128, A = 128 (Experimental Setup). */
+typedef struct {
+  int32_t num_seqs;          /* R */
+  int32_t total_tokens;      /* T = cu_seqlens[R] */
+  int32_t block_size;        /* G in {32, 64, 128} */
+  int32_t n_obs;             /* n >= 1 */
+  int32_t n_sink;            /* A >= 0 */
+  int32_t num_q_heads;
+  int32_t num_kv_heads;
+  int32_t head_dim;          /* 128 */
+  int32_t hidden_dim;        /* d */
+  int64_t q_row_stride;      /* elements between consecutive tokens of q */
+  int64_t k_row_stride;      /* elements between consecutive tokens of k */
+  int64_t hidden_row_stride; /* elements between consecutive rows of hidden */
+  float softmax_scale;       /* 0 => 1/sqrt(head_dim)  (Eq. 2) */
+  int32_t qk_dtype;          /* up_dtype of q and k */
+  int32_t hidden_dtype;      /* up_dtype of hidden (bit-copied, never computed on) */
+} up_params;
+
+/* Host-only, pure, needs no GPU.  Closed-form output layout of the block-local
+ * selection: inside every block of G consecutive tokens of a sequence (ragged
+ * last block allowed; block partition of "Token Importance Estimation") the
+ * operator keeps k_g = max(min(L_g, max(1, ceil(ratio * L_g))), F_g) tokens,
+ * L_g the block length and F_g the number of tokens in it that are always
+ * retained: the first A and the last n of the sequence ("Top-p Token
+ * Selection", last sentence).  ratio is a float widened to double, so the
+ * product and the ceiling are exact.
+ *   new_cu_seqlens_host [R+1] out (may be NULL): prefix sums of kept counts
+ *   total_kept          out (may be NULL)
+ *   workspace_bytes     out (may be NULL): bytes the scoring entries need */
+int uniprefill_plan(const up_params* p, const int32_t* cu_seqlens_host,
+                    const float* keep_ratio_host, int32_t* new_cu_seqlens_host,
+                    int64_t* total_kept, size_t* workspace_bytes);
+
+/* Token importance (Eq. 2-3; kernels K1/K2 and the head contraction of K3 in
+ * the kernel-design paragraph): for each sequence, query head and each of the
+ * last n_eff = min(n, N) query rows, the causal softmax over the whole visible
+ * key sequence of scale * <q_j, k_i>; score_i = mean over those rows and over
+ * all query heads.  Written as float; means below 2^-64 are written as +0.
+ *   q, k           device, qk_dtype; only the last n_eff rows of q per sequence
+ *                  are read
+ *   scores_out     device float [T]
+ *   workspace      device scratch of at least workspace_bytes (from the plan),
+ *                  256-byte aligned; contents undefined afterwards */
+int uniprefill_score(const up_params* p, const void* q, const void* k,
+                     const int32_t* cu_seqlens_dev, const int32_t* cu_seqlens_host,
+                     float* scores_out, void* workspace, size_t workspace_bytes,
+                     void* stream);
+
+/* Block-local top-k with forced retention (block partition and retained
+ * sinks/window as above; integer ordering key of Eq. 14 with the index word
+ * complemented so that equal scores resolve to the lower index).  Emits the
+ * kept packed row ids in ascending order and the patched sequence offsets
+ * (the compacted stream's query_start_loc, "vLLM scheduler integration").
+ *   scores              device float [T]
+ *   keep_ratio_dev/host [R] each, same values
+ *   kept_idx            device int32 [total_kept]   out
+ *   new_cu_seqlens_dev  device int32 [R+1]          out */
+int uniprefill_select(const up_params* p, const float* scores,
+                      const int32_t* cu_seqlens_dev, const int32_t* cu_seqlens_host,
+                      const float* keep_ratio_dev, const float* keep_ratio_host,
+                      int32_t* kept_idx, int32_t* new_cu_seqlens_dev, void* stream);
+
+/* Compaction (Eq. 7: later sublayers run on the retained set only):
+ * hidden_out[t] = hidden[kept_idx[t]], pos_out[t] = pos[kept_idx[t]].
+ * pos / pos_out may both be NULL.  kept_idx values must lie in [0, T). */
+int uniprefill_compact(const up_params* p, const void* hidden, const int32_t* pos,
+                       const int32_t* kept_idx, int64_t total_kept, void* hidden_out,
+                       int32_t* pos_out, void* stream);
+
+/* Reconstitution (Eq. 8): hidden_full[kept_idx[t]] = hidden_compact[t]; rows not
+ * named by kept_idx keep their old state.  kept_idx must not repeat a row. */
+int uniprefill_scatter(const up_params* p, const void* hidden_compact,
+                       const int32_t* kept_idx, int64_t total_kept,
+                       void* hidden_full_inout, void* stream);
+
+/* The whole path in one call: score -> select -> compact, enqueued back to back
+ * on `stream` with no host synchronisation ("sequence of fused kernels ...
+ * without CPU round-trips").  Outputs as in the single entries; scores_out may
+ * be NULL.  hidden_out needs room for the plan's total_kept rows. */
+int uniprefill_fused(const up_params* p, const void* q, const void* k, const void* hidden,
+                     const int32_t* pos, const int32_t* cu_seqlens_dev,
+                     const int32_t* cu_seqlens_host, const float* keep_ratio_dev,
+                     const float* keep_ratio_host, void* hidden_out, int32_t* pos_out,
+                     int32_t* kept_idx, int32_t* new_cu_seqlens_dev, float* scores_out,
+                     void* workspace, size_t workspace_bytes, void* stream);
+
+/* Static, never NULL. */
+const char* uniprefill_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* UNIPREFILL_H */

@@ -53,8 +53,7 @@ def importance_scores(q, k, cu_seqlens, *, n_obs, scale=None):
         sequence are read), k : [T, Hkv, D] float array, cu_seqlens : [R+1].
     Query head h reads kv head h // (Hq // Hkv).
     """
-    q = np.asarray(q)
-    k = np.asarray(k)
+    k = np.asarray(k)                       # q is only sliced (window rows), never read whole
     cu = np.asarray(cu_seqlens, dtype=np.int64)
     T, Hq, D = q.shape
     Hkv = k.shape[1]
@@ -70,7 +69,7 @@ def importance_scores(q, k, cu_seqlens, *, n_obs, scale=None):
             continue
         n_eff = min(int(n_obs), N)
         Kr = k[c0:c1].astype(np.float64)                 # [N, Hkv, D]
-        Qw = q[c1 - n_eff:c1].astype(np.float64)         # [n_eff, Hq, D]
+        Qw = np.asarray(q[c1 - n_eff:c1], dtype=np.float64)   # [n_eff, Hq, D]
         qpos = np.arange(N - n_eff, N)                   # local position of each query row
         visible = np.arange(N)[None, :] <= qpos[:, None]  # key i visible to row j iff i <= j
         colsum = np.zeros(N, dtype=np.float64)

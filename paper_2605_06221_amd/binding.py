@@ -1,0 +1,160 @@
+"""ctypes binding of libuniprefill.so: argument marshalling only.
+
+Every function has the name and argument order of its C entry point
+(include/uniprefill.h).  Tensors are torch tensors on the GPU (device pointers)
+or numpy arrays (host pointers); nothing is computed here and there is no
+fallback: if the library is missing the import fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libuniprefill.so")
+
+UP_OK, UP_ERR_NULL, UP_ERR_SHAPE, UP_ERR_RANGE, UP_ERR_UNSUPPORTED, UP_ERR_ALIGN, UP_ERR_WORKSPACE, UP_ERR_HIP = range(8)
+UP_BF16, UP_F32 = 0, 1
+
+EXPORTS = ["uniprefill_plan", "uniprefill_score", "uniprefill_select", "uniprefill_compact",
+           "uniprefill_scatter", "uniprefill_fused", "uniprefill_status_string"]
+
+
+class up_params(ctypes.Structure):
+    _fields_ = [
+        ("num_seqs", ctypes.c_int32), ("total_tokens", ctypes.c_int32),
+        ("block_size", ctypes.c_int32), ("n_obs", ctypes.c_int32), ("n_sink", ctypes.c_int32),
+        ("num_q_heads", ctypes.c_int32), ("num_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32), ("hidden_dim", ctypes.c_int32),
+        ("q_row_stride", ctypes.c_int64), ("k_row_stride", ctypes.c_int64),
+        ("hidden_row_stride", ctypes.c_int64),
+        ("softmax_scale", ctypes.c_float),
+        ("qk_dtype", ctypes.c_int32), ("hidden_dtype", ctypes.c_int32),
+    ]
+
+
+class UniPrefillError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()'). "
+            "There is no fallback path.")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32p, f32p = ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p
+    P = ctypes.POINTER(up_params)
+    lib.uniprefill_plan.argtypes = [P, i32p, f32p, i32p, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_size_t)]
+    lib.uniprefill_score.argtypes = [P, vp, vp, i32p, i32p, f32p, vp, ctypes.c_size_t, vp]
+    lib.uniprefill_select.argtypes = [P, f32p, i32p, i32p, f32p, f32p, i32p, i32p, vp]
+    lib.uniprefill_compact.argtypes = [P, vp, i32p, i32p, ctypes.c_int64, vp, i32p, vp]
+    lib.uniprefill_scatter.argtypes = [P, vp, i32p, ctypes.c_int64, vp, vp]
+    lib.uniprefill_fused.argtypes = [P, vp, vp, vp, i32p, i32p, i32p, f32p, f32p, vp, i32p, i32p, i32p, f32p, vp, ctypes.c_size_t, vp]
+    for name in EXPORTS[:-1]:
+        getattr(lib, name).restype = ctypes.c_int
+    lib.uniprefill_status_string.argtypes = [ctypes.c_int]
+    lib.uniprefill_status_string.restype = ctypes.c_char_p
+    return lib
+
+
+_lib = _load()
+
+
+def lib():
+    """The loaded ctypes library (for tests that poke the raw C ABI)."""
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return _lib.uniprefill_status_string(int(status)).decode()
+
+
+def ptr(x):
+    """Address of a torch tensor / numpy array / int / None as a void*."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return ctypes.c_void_p(x)
+    if isinstance(x, np.ndarray):
+        return ctypes.c_void_p(x.ctypes.data)
+    return ctypes.c_void_p(x.data_ptr())      # torch tensor
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    if isinstance(stream, int):
+        return ctypes.c_void_p(stream)
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _check(status: int, where: str, check: bool):
+    if check and status != UP_OK:
+        raise UniPrefillError(status, where)
+    return status
+
+
+def make_params(*, num_seqs, total_tokens, block_size, n_obs=128, n_sink=128, num_q_heads=0,
+                num_kv_heads=0, head_dim=128, hidden_dim=0, q_row_stride=None, k_row_stride=None,
+                hidden_row_stride=None, softmax_scale=0.0, qk_dtype=UP_BF16, hidden_dtype=UP_BF16) -> up_params:
+    return up_params(
+        num_seqs, total_tokens, block_size, n_obs, n_sink, num_q_heads, num_kv_heads, head_dim, hidden_dim,
+        num_q_heads * head_dim if q_row_stride is None else q_row_stride,
+        num_kv_heads * head_dim if k_row_stride is None else k_row_stride,
+        hidden_dim if hidden_row_stride is None else hidden_row_stride,
+        softmax_scale, qk_dtype, hidden_dtype)
+
+
+def uniprefill_plan(p: up_params, cu_seqlens_host: np.ndarray, keep_ratio_host: np.ndarray, *,
+                    want_workspace: bool = True, check: bool = True):
+    """Returns (status, new_cu_seqlens_host, total_kept, workspace_bytes)."""
+    new_cu = np.zeros(p.num_seqs + 1, dtype=np.int32)
+    total = ctypes.c_int64(0)
+    ws = ctypes.c_size_t(0)
+    st = _lib.uniprefill_plan(ctypes.byref(p), ptr(cu_seqlens_host), ptr(keep_ratio_host), ptr(new_cu),
+                              ctypes.byref(total), ctypes.byref(ws) if want_workspace else None)
+    _check(st, "uniprefill_plan", check)
+    return st, new_cu, int(total.value), int(ws.value)
+
+
+def uniprefill_score(p, q, k, cu_seqlens_dev, cu_seqlens_host, scores_out, workspace, workspace_bytes,
+                     stream=None, check=True):
+    st = _lib.uniprefill_score(ctypes.byref(p), ptr(q), ptr(k), ptr(cu_seqlens_dev), ptr(cu_seqlens_host),
+                               ptr(scores_out), ptr(workspace), workspace_bytes, _stream(stream))
+    return _check(st, "uniprefill_score", check)
+
+
+def uniprefill_select(p, scores, cu_seqlens_dev, cu_seqlens_host, keep_ratio_dev, keep_ratio_host,
+                      kept_idx, new_cu_seqlens_dev, stream=None, check=True):
+    st = _lib.uniprefill_select(ctypes.byref(p), ptr(scores), ptr(cu_seqlens_dev), ptr(cu_seqlens_host),
+                                ptr(keep_ratio_dev), ptr(keep_ratio_host), ptr(kept_idx),
+                                ptr(new_cu_seqlens_dev), _stream(stream))
+    return _check(st, "uniprefill_select", check)
+
+
+def uniprefill_compact(p, hidden, pos, kept_idx, total_kept, hidden_out, pos_out, stream=None, check=True):
+    st = _lib.uniprefill_compact(ctypes.byref(p), ptr(hidden), ptr(pos), ptr(kept_idx), int(total_kept),
+                                 ptr(hidden_out), ptr(pos_out), _stream(stream))
+    return _check(st, "uniprefill_compact", check)
+
+
+def uniprefill_scatter(p, hidden_compact, kept_idx, total_kept, hidden_full_inout, stream=None, check=True):
+    st = _lib.uniprefill_scatter(ctypes.byref(p), ptr(hidden_compact), ptr(kept_idx), int(total_kept),
+                                 ptr(hidden_full_inout), _stream(stream))
+    return _check(st, "uniprefill_scatter", check)
+
+
+def uniprefill_fused(p, q, k, hidden, pos, cu_seqlens_dev, cu_seqlens_host, keep_ratio_dev, keep_ratio_host,
+                     hidden_out, pos_out, kept_idx, new_cu_seqlens_dev, scores_out, workspace,
+                     workspace_bytes, stream=None, check=True):
+    st = _lib.uniprefill_fused(ctypes.byref(p), ptr(q), ptr(k), ptr(hidden), ptr(pos), ptr(cu_seqlens_dev),
+                               ptr(cu_seqlens_host), ptr(keep_ratio_dev), ptr(keep_ratio_host),
+                               ptr(hidden_out), ptr(pos_out), ptr(kept_idx), ptr(new_cu_seqlens_dev),
+                               ptr(scores_out), ptr(workspace), workspace_bytes, _stream(stream))
+    return _check(st, "uniprefill_fused", check)

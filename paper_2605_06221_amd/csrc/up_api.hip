@@ -1,0 +1,231 @@
+// C ABI of the UniPrefill operator library: argument validation, closed-form
+// planning, and kernel sequencing.  Every check happens on the host before the
+// first launch; nothing here allocates, synchronises or copies.
+#include "../../include/uniprefill.h"
+
+#include <math.h>
+
+#include "up_common.h"
+#include "up_kernels.h"
+
+using namespace up;
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int elem_bytes(int dt) { return dt == UP_BF16 ? 2 : 4; }
+
+// Checks that need only the parameter block.
+int check_params(const up_params* p, bool need_qk, bool need_hidden, Problem* pb) {
+  if (p == nullptr) return UP_ERR_NULL;
+  if (p->num_seqs < 0 || p->total_tokens < 0) return UP_ERR_SHAPE;
+  if (p->block_size != 32 && p->block_size != 64 && p->block_size != 128) return UP_ERR_RANGE;
+  if (p->n_obs < 1 || p->n_obs > kMaxNObs || p->n_sink < 0) return UP_ERR_RANGE;
+  Problem q{};
+  q.R = p->num_seqs; q.T = p->total_tokens;
+  q.G = p->block_size; q.n_obs = p->n_obs; q.n_sink = p->n_sink;
+  q.Hq = p->num_q_heads; q.Hkv = p->num_kv_heads; q.d = p->hidden_dim;
+  q.q_stride = p->q_row_stride; q.k_stride = p->k_row_stride; q.h_stride = p->hidden_row_stride;
+  q.Gq = 1; q.CK = 128; q.tpw = 1; q.n_slab = 1;
+  if (need_qk) {
+    if (p->head_dim != 128) return UP_ERR_UNSUPPORTED;
+    if (p->num_q_heads < 1 || p->num_kv_heads < 1) return UP_ERR_SHAPE;
+    if (p->num_q_heads % p->num_kv_heads != 0) return UP_ERR_UNSUPPORTED;
+    if (p->num_q_heads / p->num_kv_heads > 64) return UP_ERR_UNSUPPORTED;
+    if (p->qk_dtype != UP_BF16) return UP_ERR_UNSUPPORTED;   // fp32 q/k: not built yet
+    if (!(p->softmax_scale >= 0.0f) || isinf(p->softmax_scale)) return UP_ERR_RANGE;
+    if (p->q_row_stride < (int64_t)p->num_q_heads * p->head_dim ||
+        p->k_row_stride < (int64_t)p->num_kv_heads * p->head_dim)
+      return UP_ERR_SHAPE;
+    const int eb = elem_bytes(p->qk_dtype);
+    if ((p->q_row_stride * eb) % 16 != 0 || (p->k_row_stride * eb) % 16 != 0) return UP_ERR_ALIGN;
+    q.Gq = p->num_q_heads / p->num_kv_heads;
+    q.qk_is_f32 = p->qk_dtype == UP_F32;
+    q.scale = p->softmax_scale > 0.0f ? p->softmax_scale : 1.0f / sqrtf((float)p->head_dim);
+    // launch shape of the scoring passes
+    const int tiles = ceil_div(q.n_obs * q.Gq, 16);
+    q.tpw = imin(8, ceil_div(tiles, 8));
+    q.n_slab = ceil_div(tiles, 8 * q.tpw);
+    long long ck = ((long long)q.T * q.Hkv * q.n_slab / 1024) / 64 * 64;
+    if (ck < 128) ck = 128;
+    if (ck > 1024) ck = 1024;
+    q.CK = (int)ck;
+  }
+  if (need_hidden) {
+    if (p->hidden_dim < 1) return UP_ERR_SHAPE;
+    if (p->hidden_dtype != UP_BF16 && p->hidden_dtype != UP_F32) return UP_ERR_UNSUPPORTED;
+    if (p->hidden_row_stride < p->hidden_dim) return UP_ERR_SHAPE;
+    q.hidden_elem_bytes = elem_bytes(p->hidden_dtype);
+    if (((int64_t)p->hidden_dim * q.hidden_elem_bytes) % 16 != 0 ||
+        (p->hidden_row_stride * q.hidden_elem_bytes) % 16 != 0)
+      return UP_ERR_ALIGN;
+  }
+  q.chunk_slots = q.T / q.CK + q.R;
+  const long long rs = (long long)q.R * q.n_obs;
+  q.row_slots = rs < q.T ? (int)rs : q.T;
+  *pb = q;
+  return UP_OK;
+}
+
+int check_cu(const up_params* p, const int32_t* cu_host) {
+  if (cu_host == nullptr) return UP_ERR_NULL;
+  if (cu_host[0] != 0) return UP_ERR_SHAPE;
+  for (int r = 0; r < p->num_seqs; ++r)
+    if (cu_host[r + 1] < cu_host[r]) return UP_ERR_SHAPE;
+  if (cu_host[p->num_seqs] != p->total_tokens) return UP_ERR_SHAPE;
+  return UP_OK;
+}
+
+int check_ratio(const up_params* p, const float* ratio_host) {
+  if (ratio_host == nullptr) return UP_ERR_NULL;
+  for (int r = 0; r < p->num_seqs; ++r)
+    if (!(ratio_host[r] > 0.0f && ratio_host[r] <= 1.0f)) return UP_ERR_RANGE;
+  return UP_OK;
+}
+
+long long host_total_kept(const Problem& pb, const int32_t* cu, const float* ratio,
+                          int32_t* new_cu_out) {
+  long long total = 0;
+  if (new_cu_out) new_cu_out[0] = 0;
+  for (int r = 0; r < pb.R; ++r) {
+    SeqGeom sg{cu[r + 1] - cu[r], pb.G, pb.n_obs, pb.n_sink, (double)ratio[r]};
+    total += seq_kept(sg);
+    if (new_cu_out) new_cu_out[r + 1] = (int32_t)total;
+  }
+  return total;
+}
+
+}  // namespace
+
+extern "C" {
+
+int uniprefill_plan(const up_params* p, const int32_t* cu_seqlens_host, const float* keep_ratio_host,
+                    int32_t* new_cu_seqlens_host, int64_t* total_kept, size_t* workspace_bytes) {
+  Problem pb;
+  const bool want_ws = workspace_bytes != nullptr;
+  int st = check_params(p, want_ws, false, &pb);
+  if (st != UP_OK) return st;
+  if ((st = check_cu(p, cu_seqlens_host)) != UP_OK) return st;
+  if ((st = check_ratio(p, keep_ratio_host)) != UP_OK) return st;
+  const long long total = host_total_kept(pb, cu_seqlens_host, keep_ratio_host, new_cu_seqlens_host);
+  if (total_kept) *total_kept = total;
+  if (want_ws) *workspace_bytes = workspace_layout(pb).total;
+  return UP_OK;
+}
+
+int uniprefill_score(const up_params* p, const void* q, const void* k, const int32_t* cu_seqlens_dev,
+                     const int32_t* cu_seqlens_host, float* scores_out, void* workspace,
+                     size_t workspace_bytes, void* stream) {
+  Problem pb;
+  int st = check_params(p, true, false, &pb);
+  if (st != UP_OK) return st;
+  if (!q || !k || !cu_seqlens_dev || !scores_out) return UP_ERR_NULL;
+  if ((st = check_cu(p, cu_seqlens_host)) != UP_OK) return st;
+  if (!aligned16(q) || !aligned16(k)) return UP_ERR_ALIGN;
+  if (workspace == nullptr || workspace_bytes < workspace_layout(pb).total) return UP_ERR_WORKSPACE;
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return UP_ERR_ALIGN;
+  hipStream_t s = (hipStream_t)stream;
+  if (launch_score_passes(pb, q, k, cu_seqlens_dev, workspace, s) != hipSuccess) return UP_ERR_HIP;
+  if (launch_finalise_scores(pb, cu_seqlens_dev, workspace, scores_out, s) != hipSuccess)
+    return UP_ERR_HIP;
+  return UP_OK;
+}
+
+int uniprefill_select(const up_params* p, const float* scores, const int32_t* cu_seqlens_dev,
+                      const int32_t* cu_seqlens_host, const float* keep_ratio_dev,
+                      const float* keep_ratio_host, int32_t* kept_idx, int32_t* new_cu_seqlens_dev,
+                      void* stream) {
+  Problem pb;
+  int st = check_params(p, false, false, &pb);
+  if (st != UP_OK) return st;
+  if (!scores || !cu_seqlens_dev || !keep_ratio_dev || !kept_idx || !new_cu_seqlens_dev)
+    return UP_ERR_NULL;
+  if ((st = check_cu(p, cu_seqlens_host)) != UP_OK) return st;
+  if ((st = check_ratio(p, keep_ratio_host)) != UP_OK) return st;
+  hipStream_t s = (hipStream_t)stream;
+  if (launch_plan(pb, cu_seqlens_dev, keep_ratio_dev, new_cu_seqlens_dev, s) != hipSuccess)
+    return UP_ERR_HIP;
+  if (launch_select(pb, scores, nullptr, 0, cu_seqlens_dev, keep_ratio_dev, new_cu_seqlens_dev,
+                    kept_idx, nullptr, nullptr, nullptr, nullptr, nullptr, s) != hipSuccess)
+    return UP_ERR_HIP;
+  return UP_OK;
+}
+
+int uniprefill_compact(const up_params* p, const void* hidden, const int32_t* pos,
+                       const int32_t* kept_idx, int64_t total_kept, void* hidden_out,
+                       int32_t* pos_out, void* stream) {
+  Problem pb;
+  int st = check_params(p, false, true, &pb);
+  if (st != UP_OK) return st;
+  if (total_kept < 0 || total_kept > p->total_tokens) return UP_ERR_RANGE;
+  if (!hidden || !kept_idx || !hidden_out) return UP_ERR_NULL;
+  if ((pos == nullptr) != (pos_out == nullptr)) return UP_ERR_NULL;
+  if (!aligned16(hidden) || !aligned16(hidden_out)) return UP_ERR_ALIGN;
+  if (launch_compact(pb, hidden, pos, kept_idx, total_kept, hidden_out, pos_out,
+                     (hipStream_t)stream) != hipSuccess)
+    return UP_ERR_HIP;
+  return UP_OK;
+}
+
+int uniprefill_scatter(const up_params* p, const void* hidden_compact, const int32_t* kept_idx,
+                       int64_t total_kept, void* hidden_full_inout, void* stream) {
+  Problem pb;
+  int st = check_params(p, false, true, &pb);
+  if (st != UP_OK) return st;
+  if (total_kept < 0 || total_kept > p->total_tokens) return UP_ERR_RANGE;
+  if (!hidden_compact || !kept_idx || !hidden_full_inout) return UP_ERR_NULL;
+  if (!aligned16(hidden_compact) || !aligned16(hidden_full_inout)) return UP_ERR_ALIGN;
+  if (launch_scatter(pb, hidden_compact, kept_idx, total_kept, hidden_full_inout,
+                     (hipStream_t)stream) != hipSuccess)
+    return UP_ERR_HIP;
+  return UP_OK;
+}
+
+int uniprefill_fused(const up_params* p, const void* q, const void* k, const void* hidden,
+                     const int32_t* pos, const int32_t* cu_seqlens_dev,
+                     const int32_t* cu_seqlens_host, const float* keep_ratio_dev,
+                     const float* keep_ratio_host, void* hidden_out, int32_t* pos_out,
+                     int32_t* kept_idx, int32_t* new_cu_seqlens_dev, float* scores_out,
+                     void* workspace, size_t workspace_bytes, void* stream) {
+  Problem pb;
+  int st = check_params(p, true, true, &pb);
+  if (st != UP_OK) return st;
+  if (!q || !k || !hidden || !cu_seqlens_dev || !keep_ratio_dev || !hidden_out || !kept_idx ||
+      !new_cu_seqlens_dev)
+    return UP_ERR_NULL;
+  if ((pos == nullptr) != (pos_out == nullptr)) return UP_ERR_NULL;
+  if ((st = check_cu(p, cu_seqlens_host)) != UP_OK) return st;
+  if ((st = check_ratio(p, keep_ratio_host)) != UP_OK) return st;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(hidden) || !aligned16(hidden_out))
+    return UP_ERR_ALIGN;
+  const Workspace w = workspace_layout(pb);
+  if (workspace == nullptr || workspace_bytes < w.total) return UP_ERR_WORKSPACE;
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return UP_ERR_ALIGN;
+  hipStream_t s = (hipStream_t)stream;
+  if (launch_plan(pb, cu_seqlens_dev, keep_ratio_dev, new_cu_seqlens_dev, s) != hipSuccess)
+    return UP_ERR_HIP;
+  if (launch_score_passes(pb, q, k, cu_seqlens_dev, workspace, s) != hipSuccess) return UP_ERR_HIP;
+  const double* parts = (const double*)((const char*)workspace + w.part_o_off);
+  if (launch_select(pb, nullptr, parts, pb.Hkv * pb.n_slab, cu_seqlens_dev, keep_ratio_dev,
+                    new_cu_seqlens_dev, kept_idx, scores_out, hidden, pos, hidden_out, pos_out,
+                    s) != hipSuccess)
+    return UP_ERR_HIP;
+  return UP_OK;
+}
+
+const char* uniprefill_status_string(int status) {
+  switch (status) {
+    case UP_OK: return "ok";
+    case UP_ERR_NULL: return "required pointer is NULL";
+    case UP_ERR_SHAPE: return "inconsistent shape or cu_seqlens";
+    case UP_ERR_RANGE: return "parameter out of range";
+    case UP_ERR_UNSUPPORTED: return "unsupported configuration";
+    case UP_ERR_ALIGN: return "pointer or row stride not 16-byte aligned";
+    case UP_ERR_WORKSPACE: return "workspace missing or too small";
+    case UP_ERR_HIP: return "kernel launch failed";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

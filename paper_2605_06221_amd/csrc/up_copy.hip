@@ -1,0 +1,71 @@
+// Ragged row gather / scatter (Eq. 7 compaction, Eq. 8 reconstitution).
+//
+// Pure HBM traffic: one wavefront moves one row with 128-bit loads and stores,
+// four loads in flight per lane; rows are multiples of 16 bytes (checked on the
+// host).  Streaming data is marked non-temporal so that it does not evict the
+// key tensor from the last-level cache between the two scoring passes.
+#include "up_common.h"
+#include "up_kernels.h"
+
+namespace up {
+
+__device__ __forceinline__ void copy_row_wave(const char* __restrict__ src, char* __restrict__ dst,
+                                              long long row_bytes, int lane) {
+  constexpr int U = 4;
+  long long off = (long long)lane * 16;
+  for (; off + (U - 1) * 1024 < row_bytes; off += U * 1024) {
+    u32x4 v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) v[u] = __builtin_nontemporal_load((const u32x4*)(src + off + u * 1024));
+#pragma unroll
+    for (int u = 0; u < U; ++u) __builtin_nontemporal_store(v[u], (u32x4*)(dst + off + u * 1024));
+  }
+  for (; off < row_bytes; off += 1024) {
+    u32x4 v = __builtin_nontemporal_load((const u32x4*)(src + off));
+    __builtin_nontemporal_store(v, (u32x4*)(dst + off));
+  }
+}
+
+template <bool SCATTER>
+__global__ __launch_bounds__(256) void k_rows(const char* __restrict__ src, char* __restrict__ dst,
+                                              const int32_t* __restrict__ idx, long long total_kept,
+                                              long long row_bytes, long long stride_bytes,
+                                              const int32_t* __restrict__ pos,
+                                              int32_t* __restrict__ pos_out) {
+  const int lane = threadIdx.x & 63;
+  const long long t = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= total_kept) return;
+  const long long row = idx[t];
+  if (SCATTER) {
+    copy_row_wave(src + t * stride_bytes, dst + row * stride_bytes, row_bytes, lane);
+  } else {
+    copy_row_wave(src + row * stride_bytes, dst + t * stride_bytes, row_bytes, lane);
+    if (pos != nullptr && lane == 0) pos_out[t] = pos[row];
+  }
+}
+
+hipError_t launch_compact(const Problem& pb, const void* hidden, const int32_t* pos,
+                          const int32_t* kept_idx, long long total_kept, void* hidden_out,
+                          int32_t* pos_out, hipStream_t s) {
+  if (total_kept == 0) return hipSuccess;
+  const long long row_bytes = (long long)pb.d * pb.hidden_elem_bytes;
+  const long long stride_bytes = pb.h_stride * pb.hidden_elem_bytes;
+  const unsigned grid = (unsigned)((total_kept + 3) / 4);
+  hipLaunchKernelGGL(k_rows<false>, dim3(grid), dim3(256), 0, s, (const char*)hidden,
+                     (char*)hidden_out, kept_idx, total_kept, row_bytes, stride_bytes, pos, pos_out);
+  return hipGetLastError();
+}
+
+hipError_t launch_scatter(const Problem& pb, const void* hidden_compact, const int32_t* kept_idx,
+                          long long total_kept, void* hidden_full, hipStream_t s) {
+  if (total_kept == 0) return hipSuccess;
+  const long long row_bytes = (long long)pb.d * pb.hidden_elem_bytes;
+  const long long stride_bytes = pb.h_stride * pb.hidden_elem_bytes;
+  const unsigned grid = (unsigned)((total_kept + 3) / 4);
+  hipLaunchKernelGGL(k_rows<true>, dim3(grid), dim3(256), 0, s, (const char*)hidden_compact,
+                     (char*)hidden_full, kept_idx, total_kept, row_bytes, stride_bytes,
+                     (const int32_t*)nullptr, (int32_t*)nullptr);
+  return hipGetLastError();
+}
+
+}  // namespace up

@@ -1,0 +1,295 @@
+"""GPU parity: every C-ABI entry point against the fp64 CPU oracle on the same
+seeded inputs.  Integer, index and byte outputs must be bit-exact; scores agree
+within 1e-2 relative (bf16 inputs) plus the 2^-64 floor."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2605_06221_amd as up
+import workloads
+from gpu_util import DeviceBatch, dev_bf16, host_bits, oracle_run, score_margin_report
+
+pytestmark = pytest.mark.gpu
+
+SCORE_RTOL = 1e-2          # bf16 inputs (tolerance stated for this build)
+SCORE_ATOL = 2.0 ** -64    # the floor
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+# ----------------------------------------------------------------------------- compact / scatter
+@pytest.mark.parametrize("d,dtype", [(8, "bf16"), (24, "bf16"), (1024, "bf16"), (4096, "bf16"), (5120, "bf16"),
+                                      (520, "bf16"), (4, "f32"), (1000, "f32")])
+def test_compact_and_scatter_are_bit_exact(d, dtype):
+    _say("compact/scatter d", d, dtype)
+    rng = np.random.default_rng(d)
+    T = 3000
+    mask = rng.random(T) < 0.37
+    mask[[0, T - 1]] = True
+    kept = np.nonzero(mask)[0].astype(np.int32)
+    K = len(kept)
+    pos = rng.integers(0, 1 << 30, T).astype(np.int32)
+    if dtype == "bf16":
+        h = rng.integers(0, 65536, (T, d)).astype(np.uint16)
+        hd = dev_bf16(h)
+        out = torch.zeros((K + 8, d), dtype=torch.bfloat16, device="cuda")
+        hdt = up.UP_BF16
+        to_host = host_bits
+    else:
+        h = rng.integers(0, 1 << 32, (T, d), dtype=np.uint64).astype(np.uint32)
+        hd = torch.from_numpy(h.view(np.int32)).cuda()
+        out = torch.zeros((K + 8, d), dtype=torch.int32, device="cuda")
+        hdt = up.UP_F32
+        to_host = lambda t: t.cpu().numpy().view(np.uint32)
+    p = up.make_params(num_seqs=1, total_tokens=T, block_size=64, hidden_dim=d, hidden_dtype=hdt)
+    kd = torch.from_numpy(kept).cuda()
+    pd = torch.from_numpy(pos).cuda()
+    po = torch.full((K + 8,), -5, dtype=torch.int32, device="cuda")
+    up.uniprefill_compact(p, hd, pd, kd, K, out, po)
+    torch.cuda.synchronize()
+    want_h, want_p = oracle.compact(h, pos, kept)
+    np.testing.assert_array_equal(to_host(out[:K]), want_h)
+    np.testing.assert_array_equal(po[:K].cpu().numpy(), want_p)
+    assert (po[K:] == -5).all() and (out[K:] == 0).all()
+    # scatter into a different full tensor: kept rows replaced, others untouched
+    full = rng.integers(0, 60000, (T, d)).astype(h.dtype)
+    fd = dev_bf16(full) if dtype == "bf16" else torch.from_numpy(full.view(np.int32)).cuda()
+    up.uniprefill_scatter(p, out, kd, K, fd)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(to_host(fd), oracle.scatter(want_h, kept, full))
+    # no position ids: both NULL is legal
+    up.uniprefill_compact(p, hd, None, kd, K, out, None)
+    torch.cuda.synchronize()
+
+
+def test_compact_with_padded_row_stride_and_empty_selection():
+    rng = np.random.default_rng(0)
+    T, d, stride = 500, 64, 96
+    h = rng.integers(0, 65536, (T, stride)).astype(np.uint16)
+    kept = np.arange(0, T, 3, dtype=np.int32)
+    p = up.make_params(num_seqs=1, total_tokens=T, block_size=32, hidden_dim=d, hidden_row_stride=stride)
+    out = torch.zeros((len(kept), stride), dtype=torch.bfloat16, device="cuda")
+    up.uniprefill_compact(p, dev_bf16(h), None, torch.from_numpy(kept).cuda(), len(kept), out, None)
+    got = host_bits(out)
+    np.testing.assert_array_equal(got[:, :d], h[kept, :d])
+    assert (got[:, d:] == 0).all()          # bytes beyond hidden_dim are never written
+    up.uniprefill_compact(p, dev_bf16(h), None, torch.from_numpy(kept).cuda(), 0, out, None)
+    torch.cuda.synchronize()
+
+
+# ----------------------------------------------------------------------------- select
+def _select_case(rng, G, n_obs, n_sink, R, maxlen, kind):
+    lengths = rng.integers(0, maxlen, R)
+    lengths[rng.integers(0, R)] = 1
+    lengths[rng.integers(0, R)] = 0
+    cu = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int32)
+    T = int(cu[-1])
+    if kind == "random":
+        s = (rng.random(T) ** 6).astype(np.float32)
+    elif kind == "ties":
+        s = (rng.integers(0, 4, T) / 8).astype(np.float32)
+    elif kind == "zeros":
+        s = np.zeros(T, np.float32)
+    else:  # heavy tail with floored zeros and denormal-range values
+        s = np.exp(rng.standard_normal(T) * 30 - 40).astype(np.float32)
+        s[rng.random(T) < 0.5] = 0.0
+    ratio = rng.uniform(0.05, 1.0, R).astype(np.float32)
+    ratio[0] = 1.0
+    return cu, s, ratio
+
+
+@pytest.mark.parametrize("G", [32, 64, 128])
+@pytest.mark.parametrize("kind", ["random", "ties", "zeros", "heavy"])
+def test_select_is_bit_exact_on_given_scores(G, kind):
+    _say("select", G, kind)
+    rng = np.random.default_rng(G * 7 + len(kind))
+    for n_obs, n_sink, R, maxlen in [(128, 128, 9, 2000), (16, 8, 30, 300), (1, 0, 5, 700), (512, 200, 6, 3000)]:
+        cu, s, ratio = _select_case(rng, G, n_obs, n_sink, R, maxlen, kind)
+        T = int(cu[-1])
+        p = up.make_params(num_seqs=R, total_tokens=T, block_size=G, n_obs=n_obs, n_sink=n_sink)
+        want_idx, want_cu = oracle.select_tokens(s, cu, ratio, block_size=G, n_obs=n_obs, n_sink=n_sink)
+        K = len(want_idx)
+        kept = torch.full((K + 16,), -3, dtype=torch.int32, device="cuda")
+        new_cu = torch.full((R + 1 + 16,), -3, dtype=torch.int32, device="cuda")
+        up.uniprefill_select(p, torch.from_numpy(s).cuda(), torch.from_numpy(cu).cuda(), cu,
+                             torch.from_numpy(ratio).cuda(), ratio, kept, new_cu)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(new_cu[:R + 1].cpu().numpy(), want_cu)
+        np.testing.assert_array_equal(kept[:K].cpu().numpy(), want_idx)
+        assert (kept[K:] == -3).all() and (new_cu[R + 1:] == -3).all()
+
+
+def test_select_many_sequences_prefix_scan():
+    """More than 1024 sequences: the device-side offsets scan in several rounds."""
+    rng = np.random.default_rng(5)
+    R = 2500
+    lengths = rng.integers(0, 70, R)
+    cu = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int32)
+    T = int(cu[-1])
+    s = rng.random(T).astype(np.float32)
+    ratio = rng.uniform(0.1, 1.0, R).astype(np.float32)
+    p = up.make_params(num_seqs=R, total_tokens=T, block_size=32, n_obs=4, n_sink=2)
+    want_idx, want_cu = oracle.select_tokens(s, cu, ratio, block_size=32, n_obs=4, n_sink=2)
+    kept = torch.zeros(len(want_idx), dtype=torch.int32, device="cuda")
+    new_cu = torch.zeros(R + 1, dtype=torch.int32, device="cuda")
+    up.uniprefill_select(p, torch.from_numpy(s).cuda(), torch.from_numpy(cu).cuda(), cu,
+                         torch.from_numpy(ratio).cuda(), ratio, kept, new_cu)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(new_cu.cpu().numpy(), want_cu)
+    np.testing.assert_array_equal(kept.cpu().numpy(), want_idx)
+
+
+# ----------------------------------------------------------------------------- score
+def _q_f32(w):
+    """q as the oracle reads it: only window rows are upcast (the rest is NaN filler)."""
+    from gpu_util import _LazyQ
+    return _LazyQ(w.q)
+
+
+def _score_close(got, want32):
+    want = want32.astype(np.float64)
+    err = np.abs(got.astype(np.float64) - want)
+    ok = err <= SCORE_RTOL * want + SCORE_ATOL
+    return ok.all(), (err / np.maximum(want, 1e-300))[want > 0].max() if (want > 0).any() else 0.0
+
+
+@pytest.mark.parametrize("case", [
+    dict(lengths=[700], Hq=8, Hkv=8, n_obs=128),
+    dict(lengths=[1, 5, 130, 0, 257, 1000, 64], Hq=8, Hkv=2, n_obs=128),
+    dict(lengths=[3000, 2], Hq=32, Hkv=8, n_obs=128),
+    dict(lengths=[1500], Hq=40, Hkv=8, n_obs=128),
+    dict(lengths=[900, 77], Hq=4, Hkv=4, n_obs=32),
+    dict(lengths=[600], Hq=2, Hkv=1, n_obs=512),
+    dict(lengths=[2100], Hq=16, Hkv=2, n_obs=200),
+])
+def test_scores_match_oracle(case):
+    _say("score", case)
+    w = workloads.make_custom(name="score", seed=11, lengths=case["lengths"], keep_ratio=[0.5] * len(case["lengths"]),
+                              hidden_dim=8, num_q_heads=case["Hq"], num_kv_heads=case["Hkv"], block_size=64,
+                              n_obs=case["n_obs"])
+    b = DeviceBatch(w)
+    b.score()
+    got = b.results()["scores"]
+    want = oracle.quantise_scores(oracle.importance_scores(
+        _q_f32(w), workloads.bf16_bits_to_f32(w.k), w.cu_seqlens, n_obs=w.n_obs))
+    ok, worst = _score_close(got, want)
+    _say("  worst relative score error", worst)
+    assert ok
+    assert b.canaries_intact()
+    for r in range(w.num_seqs):
+        a, e = w.cu_seqlens[r], w.cu_seqlens[r + 1]
+        if e > a:
+            assert abs(float(got[a:e].astype(np.float64).sum()) - 1.0) < 1e-4
+
+
+def test_scores_custom_scale_and_heavy_tail():
+    _say("score heavy tail")
+    w = workloads.make_custom(name="ht", seed=3, lengths=[4000], keep_ratio=[0.25], hidden_dim=8,
+                              num_q_heads=8, num_kv_heads=2, block_size=128, k_row_lognormal=True)
+    for scale in [0.0, 0.03]:
+        b = DeviceBatch(w, softmax_scale=scale)
+        b.score()
+        got = b.results()["scores"]
+        want = oracle.quantise_scores(oracle.importance_scores(
+            _q_f32(w), workloads.bf16_bits_to_f32(w.k), w.cu_seqlens, n_obs=w.n_obs, scale=scale or None))
+        ok, worst = _score_close(got, want)
+        _say("  scale", scale, "worst relative score error", worst, "zeros", int((want == 0).sum()))
+        assert ok
+        # the floor is applied identically except within rounding of the floor itself
+        assert ((got == 0) != (want == 0)).sum() <= 2
+
+
+# ----------------------------------------------------------------------------- fused, small
+def _assert_fused_exact(w, b, ref):
+    res = b.results()
+    np.testing.assert_array_equal(res["new_cu_seqlens"], ref["new_cu_seqlens"])
+    ok, worst = _score_close(res["scores"], ref["scores"])
+    margin = score_margin_report(ref, w)
+    _say(f"  {w.name}: T={w.total_tokens} kept={len(ref['kept_idx'])} worst score rel err {worst:.3e} "
+         f"min selection margin {margin:.3e}")
+    assert ok
+    diff = np.nonzero(res["kept_idx"] != ref["kept_idx"])[0]
+    assert len(diff) == 0, f"{len(diff)} kept indices differ (first at {diff[:5]})"
+    np.testing.assert_array_equal(res["pos_out"], ref["pos_out"])
+    np.testing.assert_array_equal(res["hidden_out"], ref["hidden_out"])
+    assert b.canaries_intact()
+
+
+@pytest.mark.parametrize("idx,shrink", [(1, 4), (2, 16), (3, 16), (4, 32), (5, 8)])
+def test_fused_shrunk_configs_bit_exact(idx, shrink):
+    _say("fused shrunk", idx, shrink)
+    w = workloads.make_config(idx, shrink=shrink, hidden_dim=256)
+    b = DeviceBatch(w)
+    b.fused()
+    _assert_fused_exact(w, b, oracle_run(w))
+
+
+def test_fused_without_scores_and_repeatability():
+    _say("fused determinism")
+    w = workloads.make_config(3, shrink=32, hidden_dim=128)
+    b = DeviceBatch(w)
+    b.fused(want_scores=False)
+    first = b.results()
+    assert (first["scores"] == -7.0).all()        # scores_out = NULL: never written
+    ref = oracle_run(w)
+    np.testing.assert_array_equal(first["kept_idx"], ref["kept_idx"])
+    np.testing.assert_array_equal(first["hidden_out"], ref["hidden_out"])
+    for _ in range(5):
+        b.fused(want_scores=True)
+        again = b.results()
+        np.testing.assert_array_equal(again["kept_idx"], first["kept_idx"])
+        np.testing.assert_array_equal(again["hidden_out"], first["hidden_out"])
+    s1 = again["scores"].copy()
+    b.fused(want_scores=True)
+    np.testing.assert_array_equal(b.results()["scores"], s1)    # bitwise repeatable, no float atomics
+
+
+def test_fused_identity_at_ratio_one_and_varlen_concat():
+    _say("fused identity / concat")
+    rng = np.random.default_rng(9)
+    lengths = [300, 1, 0, 1029, 257]
+    w = workloads.make_custom(name="id", seed=9, lengths=lengths, keep_ratio=[1.0] * 5, hidden_dim=64,
+                              num_q_heads=8, num_kv_heads=2, block_size=64)
+    b = DeviceBatch(w)
+    b.fused()
+    res = b.results()
+    np.testing.assert_array_equal(res["kept_idx"], np.arange(w.total_tokens, dtype=np.int32))
+    np.testing.assert_array_equal(res["hidden_out"], w.hidden)
+    np.testing.assert_array_equal(res["new_cu_seqlens"], w.cu_seqlens)
+    # varlen batch == concatenation of single-sequence runs
+    w2 = workloads.make_custom(name="cat", seed=10, lengths=lengths, keep_ratio=[0.3, 0.5, 0.5, 0.2, 0.6],
+                               hidden_dim=64, num_q_heads=8, num_kv_heads=2, block_size=64)
+    b2 = DeviceBatch(w2)
+    b2.fused()
+    whole = b2.results()
+    parts = []
+    for r in range(5):
+        a, e = int(w2.cu_seqlens[r]), int(w2.cu_seqlens[r + 1])
+        if e == a:
+            continue
+        w1 = workloads.Workload(name="one", block_size=64, n_obs=128, n_sink=128, num_q_heads=8, num_kv_heads=2,
+                                head_dim=128, hidden_dim=64, cu_seqlens=np.array([0, e - a], np.int32),
+                                keep_ratio=w2.keep_ratio[r:r + 1], hidden=w2.hidden[a:e], q=w2.q[a:e],
+                                k=w2.k[a:e], pos=w2.pos[a:e])
+        b1 = DeviceBatch(w1)
+        b1.fused()
+        parts.append(b1.results()["kept_idx"] + a)
+    np.testing.assert_array_equal(whole["kept_idx"], np.concatenate(parts))
+
+
+# ----------------------------------------------------------------------------- fused, full size
+@pytest.mark.parametrize("idx", [1, 2, 5, 3, 4])
+def test_fused_full_size_configs_bit_exact(idx):
+    """The five workloads at full size, in the launch configuration the benchmark times."""
+    _say("fused full", idx)
+    w = workloads.make_config(idx)
+    _say("  generated", w.name, "T =", w.total_tokens)
+    b = DeviceBatch(w)
+    b.fused()
+    torch.cuda.synchronize()
+    _say("  gpu done; running oracle")
+    ref = oracle_run(w)
+    _assert_fused_exact(w, b, ref)
