@@ -1,0 +1,209 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused UniPrefill score+select+compact operator on one MI355X.
+
+One "step" is one uniprefill_fused call (plan, two scoring passes, merge,
+select+compact) over one synthetic batch that is already resident in HBM.
+Prints ONE JSON line: whole-operator tokens/s, the roofline figures of the
+dominant kernel (per-kernel times measured with events on the launch stream),
+and the CPU oracle timed on the host cores of the same machine.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+
+
+def algorithmic_bytes(w, total_kept):
+    """Bytes the method must move: K once, a score per token, the kept rows in and out,
+    index/position words, and the query window."""
+    per_token = w.num_kv_heads * w.head_dim * 2 + 4
+    per_kept = 2 * w.hidden_dim * 2 + 12
+    q_bytes = sum(min(w.n_obs, int(w.cu_seqlens[r + 1] - w.cu_seqlens[r])) for r in range(w.num_seqs)) \
+        * w.num_q_heads * w.head_dim * 2
+    return w.total_tokens * per_token + total_kept * per_kept + q_bytes
+
+
+def product_flops(w):
+    """Flops of one Q.K^T pass: 2 * n_eff * N * D * Hq per sequence."""
+    f = 0
+    for r in range(w.num_seqs):
+        N = int(w.cu_seqlens[r + 1] - w.cu_seqlens[r])
+        f += 2 * min(w.n_obs, N) * N * w.head_dim * w.num_q_heads
+    return f
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=4, help="workload 1..5 (default: the 128k-token one)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-phases", action="store_true", help="skip the per-kernel timing loop")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (no sharding or collectives are built)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2605_06221_amd as up      # fails loudly if the HIP library is missing
+    import workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+
+    t0 = time.time()
+    w = workloads.make_config(args.config)
+    print(f"[bench] generated {w.name}: T={w.total_tokens} R={w.num_seqs} in {time.time() - t0:.1f}s",
+          file=sys.stderr, flush=True)
+
+    cu_host = np.ascontiguousarray(w.cu_seqlens, dtype=np.int32)
+    ratio_host = np.ascontiguousarray(w.keep_ratio, dtype=np.float32)
+    p = up.make_params(num_seqs=w.num_seqs, total_tokens=w.total_tokens, block_size=w.block_size,
+                       n_obs=w.n_obs, n_sink=w.n_sink, num_q_heads=w.num_q_heads,
+                       num_kv_heads=w.num_kv_heads, head_dim=w.head_dim, hidden_dim=w.hidden_dim)
+    _, new_cu_plan, total_kept, ws_bytes = up.uniprefill_plan(p, cu_host, ratio_host)
+
+    def dev_bf16(bits):
+        return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+
+    q, k, hidden = dev_bf16(w.q), dev_bf16(w.k), dev_bf16(w.hidden)
+    pos = torch.from_numpy(w.pos).cuda()
+    cu = torch.from_numpy(cu_host).cuda()
+    ratio = torch.from_numpy(ratio_host).cuda()
+    workspace = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    hidden_out = torch.empty((total_kept, w.hidden_dim), dtype=torch.bfloat16, device="cuda")
+    pos_out = torch.empty(total_kept, dtype=torch.int32, device="cuda")
+    kept_idx = torch.empty(total_kept, dtype=torch.int32, device="cuda")
+    new_cu = torch.empty(w.num_seqs + 1, dtype=torch.int32, device="cuda")
+    scores = torch.empty(w.total_tokens, dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    common = (p, q, k, hidden, pos, cu, cu_host, ratio, ratio_host, hidden_out, pos_out, kept_idx, new_cu,
+              scores, workspace, ws_bytes)
+
+    def step():
+        up.uniprefill_fused(*common, stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    ms_per_step = elapsed / args.steps * 1e3
+    tokens_per_s = w.total_tokens / (elapsed / args.steps)
+
+    alg_bytes = algorithmic_bytes(w, total_kept)
+    flops = product_flops(w)
+
+    # ---- per-kernel durations: the same five launches, each bracketed by events on the stream
+    phases = [("plan", up.UP_PHASE_PLAN), ("score_row_stats", up.UP_PHASE_ROW_STATS),
+              ("merge_stats", up.UP_PHASE_MERGE_STATS), ("score_column_sums", up.UP_PHASE_COLUMN_SUMS),
+              ("select_compact", up.UP_PHASE_SELECT_COMPACT)]
+    kernels = {}
+    if not args.no_phases:
+        acc = {name: 0.0 for name, _ in phases}
+        for it in range(args.steps):
+            evs = [torch.cuda.Event(enable_timing=True) for _ in range(len(phases) + 1)]
+            evs[0].record(stream)
+            for i, (name, mask) in enumerate(phases):
+                up.uniprefill_fused_phases(*common, mask, stream=stream)
+                evs[i + 1].record(stream)
+            torch.cuda.synchronize()
+            for i, (name, _) in enumerate(phases):
+                acc[name] += evs[i].elapsed_time(evs[i + 1])
+        kept_bytes = total_kept * (2 * w.hidden_dim * 2 + 12) + w.total_tokens * 4
+        k_bytes = w.total_tokens * w.num_kv_heads * w.head_dim * 2
+        for name, _ in phases:
+            us = acc[name] / args.steps * 1e3
+            ent = {"avg_us": round(us, 2)}
+            if name.startswith("score_"):
+                ent.update(bound="mfma", tflops=round(flops / (us * 1e-6) / 1e12, 1),
+                           frac_mfma=round(flops / (us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                           k_read_gbs=round(k_bytes / (us * 1e-6) / 1e9, 1))
+            elif name == "select_compact":
+                ent.update(bound="hbm", gbs=round(kept_bytes / (us * 1e-6) / 1e9, 1),
+                           frac_hbm=round(kept_bytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4))
+            kernels[name] = ent
+        dom = max(kernels, key=lambda n: kernels[n]["avg_us"])
+        if kernels[dom].get("bound") == "mfma":
+            roofline = {"kernel": dom, "bound": "mfma", "achieved": kernels[dom]["tflops"],
+                        "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": kernels[dom]["frac_mfma"],
+                        "traffic": None}
+        else:
+            roofline = {"kernel": dom, "bound": "hbm", "achieved": kernels[dom].get("gbs"),
+                        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": kernels[dom].get("frac_hbm"),
+                        "traffic": None}
+    else:
+        roofline = None
+
+    # ---- the oracle on this machine's host cores (a reported baseline, not a target)
+    cpu_baseline = None
+    parity = None
+    if not args.no_cpu_baseline:
+        sys.path.insert(0, os.path.join(ROOT, "tests"))
+        from gpu_util import oracle_run           # test infrastructure: the fp64 numpy oracle
+        try:
+            from threadpoolctl import threadpool_info
+            threads = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
+        except Exception:
+            threads = os.cpu_count() or 1
+        t1 = time.perf_counter()
+        ref = oracle_run(w)
+        cpu_s = time.perf_counter() - t1
+        cpu_baseline = {"value": round(w.total_tokens / cpu_s, 1), "unit": "tokens/s", "cores": int(threads),
+                        "kind": "oracle", "seconds": round(cpu_s, 2),
+                        "sample": f"the full {w.name} batch, one pass (BLAS threads = cores; numpy exp is single-threaded)"}
+        torch.cuda.synchronize()
+        parity = bool(np.array_equal(kept_idx.cpu().numpy(), ref["kept_idx"])
+                      and np.array_equal(hidden_out.view(torch.int16).cpu().numpy().view(np.uint16), ref["hidden_out"])
+                      and np.array_equal(pos_out.cpu().numpy(), ref["pos_out"]))
+
+    out = {
+        "metric": "tokens/s through fused score+select+compact op; % of MI355X HBM peak",
+        "value": round(tokens_per_s, 1),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": w.name, "total_tokens": w.total_tokens, "num_seqs": w.num_seqs,
+                   "total_kept": int(total_kept), "hidden_dim": w.hidden_dim, "q_heads": w.num_q_heads,
+                   "kv_heads": w.num_kv_heads, "block_size": w.block_size, "n_obs": w.n_obs, "n_sink": w.n_sink},
+        "algorithmic_bytes": int(alg_bytes),
+        "hbm_frac_fused": round(alg_bytes / (elapsed / args.steps) / 1e9 / HBM_PEAK_GBS, 4),
+        "product_flops_per_pass": int(flops),
+        "roofline": roofline,
+        "kernels": kernels,
+        "cpu_baseline": cpu_baseline,
+        "oracle_parity": parity,
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -153,6 +153,29 @@ int uniprefill_fused(const up_params* p, const void* q, const void* k, const voi
                      int32_t* kept_idx, int32_t* new_cu_seqlens_dev, float* scores_out,
                      void* workspace, size_t workspace_bytes, void* stream);
 
+/* The kernels behind uniprefill_fused, in stream order.  Measurement aid: a
+ * caller that wants to time one kernel enqueues the phases one by one. */
+enum {
+  UP_PHASE_PLAN = 1,            /* new_cu_seqlens_dev */
+  UP_PHASE_ROW_STATS = 2,       /* pass 1 of the two-pass softmax: per-chunk row statistics */
+  UP_PHASE_MERGE_STATS = 4,     /* merge of the per-chunk statistics */
+  UP_PHASE_COLUMN_SUMS = 8,     /* pass 2: normalised weights summed per token */
+  UP_PHASE_SELECT_COMPACT = 16, /* block-local top-k + gather of the kept rows */
+  UP_PHASE_ALL = 31
+};
+
+/* uniprefill_fused restricted to the phases in phase_mask (same arguments,
+ * same checks; UP_ERR_RANGE for unknown bits).  A phase reads what the earlier
+ * phases left in the workspace and outputs, so the phases of one call sequence
+ * must be enqueued in order on one stream with unchanged arguments; enqueuing
+ * all five one by one is exactly uniprefill_fused. */
+int uniprefill_fused_phases(const up_params* p, const void* q, const void* k, const void* hidden,
+                            const int32_t* pos, const int32_t* cu_seqlens_dev,
+                            const int32_t* cu_seqlens_host, const float* keep_ratio_dev,
+                            const float* keep_ratio_host, void* hidden_out, int32_t* pos_out,
+                            int32_t* kept_idx, int32_t* new_cu_seqlens_dev, float* scores_out,
+                            void* workspace, size_t workspace_bytes, int phase_mask, void* stream);
+
 /* Static, never NULL. */
 const char* uniprefill_status_string(int status);
 

@@ -19,7 +19,10 @@ UP_OK, UP_ERR_NULL, UP_ERR_SHAPE, UP_ERR_RANGE, UP_ERR_UNSUPPORTED, UP_ERR_ALIGN
 UP_BF16, UP_F32 = 0, 1
 
 EXPORTS = ["uniprefill_plan", "uniprefill_score", "uniprefill_select", "uniprefill_compact",
-           "uniprefill_scatter", "uniprefill_fused", "uniprefill_status_string"]
+           "uniprefill_scatter", "uniprefill_fused", "uniprefill_fused_phases", "uniprefill_status_string"]
+
+UP_PHASE_PLAN, UP_PHASE_ROW_STATS, UP_PHASE_MERGE_STATS, UP_PHASE_COLUMN_SUMS, UP_PHASE_SELECT_COMPACT = 1, 2, 4, 8, 16
+UP_PHASE_ALL = 31
 
 
 class up_params(ctypes.Structure):
@@ -55,6 +58,7 @@ def _load():
     lib.uniprefill_compact.argtypes = [P, vp, i32p, i32p, ctypes.c_int64, vp, i32p, vp]
     lib.uniprefill_scatter.argtypes = [P, vp, i32p, ctypes.c_int64, vp, vp]
     lib.uniprefill_fused.argtypes = [P, vp, vp, vp, i32p, i32p, i32p, f32p, f32p, vp, i32p, i32p, i32p, f32p, vp, ctypes.c_size_t, vp]
+    lib.uniprefill_fused_phases.argtypes = lib.uniprefill_fused.argtypes[:-1] + [ctypes.c_int, vp]
     for name in EXPORTS[:-1]:
         getattr(lib, name).restype = ctypes.c_int
     lib.uniprefill_status_string.argtypes = [ctypes.c_int]
@@ -158,3 +162,14 @@ def uniprefill_fused(p, q, k, hidden, pos, cu_seqlens_dev, cu_seqlens_host, keep
                                ptr(hidden_out), ptr(pos_out), ptr(kept_idx), ptr(new_cu_seqlens_dev),
                                ptr(scores_out), ptr(workspace), workspace_bytes, _stream(stream))
     return _check(st, "uniprefill_fused", check)
+
+
+def uniprefill_fused_phases(p, q, k, hidden, pos, cu_seqlens_dev, cu_seqlens_host, keep_ratio_dev,
+                            keep_ratio_host, hidden_out, pos_out, kept_idx, new_cu_seqlens_dev, scores_out,
+                            workspace, workspace_bytes, phase_mask, stream=None, check=True):
+    st = _lib.uniprefill_fused_phases(ctypes.byref(p), ptr(q), ptr(k), ptr(hidden), ptr(pos),
+                                      ptr(cu_seqlens_dev), ptr(cu_seqlens_host), ptr(keep_ratio_dev),
+                                      ptr(keep_ratio_host), ptr(hidden_out), ptr(pos_out), ptr(kept_idx),
+                                      ptr(new_cu_seqlens_dev), ptr(scores_out), ptr(workspace),
+                                      workspace_bytes, int(phase_mask), _stream(stream))
+    return _check(st, "uniprefill_fused_phases", check)

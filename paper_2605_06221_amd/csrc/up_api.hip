@@ -182,12 +182,12 @@ int uniprefill_scatter(const up_params* p, const void* hidden_compact, const int
   return UP_OK;
 }
 
-int uniprefill_fused(const up_params* p, const void* q, const void* k, const void* hidden,
-                     const int32_t* pos, const int32_t* cu_seqlens_dev,
-                     const int32_t* cu_seqlens_host, const float* keep_ratio_dev,
-                     const float* keep_ratio_host, void* hidden_out, int32_t* pos_out,
-                     int32_t* kept_idx, int32_t* new_cu_seqlens_dev, float* scores_out,
-                     void* workspace, size_t workspace_bytes, void* stream) {
+int uniprefill_fused_phases(const up_params* p, const void* q, const void* k, const void* hidden,
+                            const int32_t* pos, const int32_t* cu_seqlens_dev,
+                            const int32_t* cu_seqlens_host, const float* keep_ratio_dev,
+                            const float* keep_ratio_host, void* hidden_out, int32_t* pos_out,
+                            int32_t* kept_idx, int32_t* new_cu_seqlens_dev, float* scores_out,
+                            void* workspace, size_t workspace_bytes, int phase_mask, void* stream) {
   Problem pb;
   int st = check_params(p, true, true, &pb);
   if (st != UP_OK) return st;
@@ -202,16 +202,34 @@ int uniprefill_fused(const up_params* p, const void* q, const void* k, const voi
   const Workspace w = workspace_layout(pb);
   if (workspace == nullptr || workspace_bytes < w.total) return UP_ERR_WORKSPACE;
   if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return UP_ERR_ALIGN;
+  if (phase_mask & ~UP_PHASE_ALL) return UP_ERR_RANGE;
   hipStream_t s = (hipStream_t)stream;
-  if (launch_plan(pb, cu_seqlens_dev, keep_ratio_dev, new_cu_seqlens_dev, s) != hipSuccess)
+  if ((phase_mask & UP_PHASE_PLAN) &&
+      launch_plan(pb, cu_seqlens_dev, keep_ratio_dev, new_cu_seqlens_dev, s) != hipSuccess)
     return UP_ERR_HIP;
-  if (launch_score_passes(pb, q, k, cu_seqlens_dev, workspace, s) != hipSuccess) return UP_ERR_HIP;
+  for (int ph = 1; ph <= 3; ++ph)
+    if ((phase_mask & (UP_PHASE_PLAN << ph)) &&
+        launch_score_phase(pb, ph, q, k, cu_seqlens_dev, workspace, s) != hipSuccess)
+      return UP_ERR_HIP;
   const double* parts = (const double*)((const char*)workspace + w.part_o_off);
-  if (launch_select(pb, nullptr, parts, pb.Hkv * pb.n_slab, cu_seqlens_dev, keep_ratio_dev,
+  if ((phase_mask & UP_PHASE_SELECT_COMPACT) &&
+      launch_select(pb, nullptr, parts, pb.Hkv * pb.n_slab, cu_seqlens_dev, keep_ratio_dev,
                     new_cu_seqlens_dev, kept_idx, scores_out, hidden, pos, hidden_out, pos_out,
                     s) != hipSuccess)
     return UP_ERR_HIP;
   return UP_OK;
+}
+
+int uniprefill_fused(const up_params* p, const void* q, const void* k, const void* hidden,
+                     const int32_t* pos, const int32_t* cu_seqlens_dev,
+                     const int32_t* cu_seqlens_host, const float* keep_ratio_dev,
+                     const float* keep_ratio_host, void* hidden_out, int32_t* pos_out,
+                     int32_t* kept_idx, int32_t* new_cu_seqlens_dev, float* scores_out,
+                     void* workspace, size_t workspace_bytes, void* stream) {
+  return uniprefill_fused_phases(p, q, k, hidden, pos, cu_seqlens_dev, cu_seqlens_host,
+                                 keep_ratio_dev, keep_ratio_host, hidden_out, pos_out, kept_idx,
+                                 new_cu_seqlens_dev, scores_out, workspace, workspace_bytes,
+                                 UP_PHASE_ALL, stream);
 }
 
 const char* uniprefill_status_string(int status) {

@@ -50,6 +50,10 @@ hipError_t launch_select(const Problem& pb, const float* scores, const double* p
                          const int32_t* pos, void* hidden_out, int32_t* pos_out, hipStream_t s);
 
 // --- scoring (Eq. 2-3)
+// phase 1: row statistics per key chunk; 2: merge of the chunk statistics; 3: normalised
+// column sums (partial score planes in the workspace).
+hipError_t launch_score_phase(const Problem& pb, int phase, const void* q, const void* k,
+                              const int32_t* cu, void* workspace, hipStream_t s);
 hipError_t launch_score_passes(const Problem& pb, const void* q, const void* k, const int32_t* cu,
                                void* workspace, hipStream_t s);
 hipError_t launch_finalise_scores(const Problem& pb, const int32_t* cu, const void* workspace,

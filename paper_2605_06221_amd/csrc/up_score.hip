@@ -328,9 +328,8 @@ static hipError_t launch_pass(const Problem& pb, const ScoreArgs& a, hipStream_t
   return hipGetLastError();
 }
 
-hipError_t launch_score_passes(const Problem& pb, const void* q, const void* k, const int32_t* cu,
-                               void* workspace, hipStream_t s) {
-  if (pb.T == 0) return hipSuccess;
+static ScoreArgs make_score_args(const Problem& pb, const void* q, const void* k, const int32_t* cu,
+                                 void* workspace) {
   const Workspace w = workspace_layout(pb);
   char* ws = (char*)workspace;
   ScoreArgs a;
@@ -342,14 +341,30 @@ hipError_t launch_score_passes(const Problem& pb, const void* q, const void* k, 
   a.c = pb.scale * 1.44269504088896340736f;
   a.R = pb.R; a.T = pb.T; a.Hq = pb.Hq; a.Hkv = pb.Hkv; a.Gq = pb.Gq; a.n_obs = pb.n_obs;
   a.CK = pb.CK; a.n_slab = pb.n_slab;
-  hipError_t e = launch_pass<1>(pb, a, s);
-  if (e != hipSuccess) return e;
-  const long long threads = (long long)pb.row_slots * pb.Hq;
-  hipLaunchKernelGGL(k_combine, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, cu,
-                     a.stat_part, a.stat_fin, pb.R, pb.Hq, pb.n_obs, pb.CK, pb.row_slots);
-  e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  return a;
+}
+
+hipError_t launch_score_phase(const Problem& pb, int phase, const void* q, const void* k,
+                              const int32_t* cu, void* workspace, hipStream_t s) {
+  if (pb.T == 0) return hipSuccess;
+  const ScoreArgs a = make_score_args(pb, q, k, cu, workspace);
+  if (phase == 1) return launch_pass<1>(pb, a, s);
+  if (phase == 2) {
+    const long long threads = (long long)pb.row_slots * pb.Hq;
+    hipLaunchKernelGGL(k_combine, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, cu,
+                       a.stat_part, a.stat_fin, pb.R, pb.Hq, pb.n_obs, pb.CK, pb.row_slots);
+    return hipGetLastError();
+  }
   return launch_pass<2>(pb, a, s);
+}
+
+hipError_t launch_score_passes(const Problem& pb, const void* q, const void* k, const int32_t* cu,
+                               void* workspace, hipStream_t s) {
+  for (int phase = 1; phase <= 3; ++phase) {
+    const hipError_t e = launch_score_phase(pb, phase, q, k, cu, workspace, s);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 hipError_t launch_finalise_scores(const Problem& pb, const int32_t* cu, const void* workspace,
