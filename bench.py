@@ -116,9 +116,9 @@ def main():
     flops = product_flops(w)
 
     # ---- per-kernel durations: the same five launches, each bracketed by events on the stream
-    phases = [("plan", up.UP_PHASE_PLAN), ("score_row_stats", up.UP_PHASE_ROW_STATS),
-              ("merge_stats", up.UP_PHASE_MERGE_STATS), ("score_column_sums", up.UP_PHASE_COLUMN_SUMS),
-              ("select_compact", up.UP_PHASE_SELECT_COMPACT)]
+    phases = [("plan", up.UP_PHASE_PLAN), ("row_stats", up.UP_PHASE_ROW_STATS),
+              ("merge_stats", up.UP_PHASE_MERGE_STATS),
+              ("sweep_select_compact", up.UP_PHASE_SWEEP_SELECT_COMPACT)]
     kernels = {}
     if not args.no_phases:
         acc = {name: 0.0 for name, _ in phases}
@@ -136,13 +136,12 @@ def main():
         for name, _ in phases:
             us = acc[name] / args.steps * 1e3
             ent = {"avg_us": round(us, 2)}
-            if name.startswith("score_"):
+            if name in ("row_stats", "sweep_select_compact"):
                 ent.update(bound="mfma", tflops=round(flops / (us * 1e-6) / 1e12, 1),
-                           frac_mfma=round(flops / (us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
-                           k_read_gbs=round(k_bytes / (us * 1e-6) / 1e9, 1))
-            elif name == "select_compact":
-                ent.update(bound="hbm", gbs=round(kept_bytes / (us * 1e-6) / 1e9, 1),
-                           frac_hbm=round(kept_bytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4))
+                           frac_mfma=round(flops / (us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4))
+                moved = k_bytes + (kept_bytes if name == "sweep_select_compact" else 0)
+                ent.update(gbs=round(moved / (us * 1e-6) / 1e9, 1),
+                           frac_hbm=round(moved / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4))
             kernels[name] = ent
         dom = max(kernels, key=lambda n: kernels[n]["avg_us"])
         if kernels[dom].get("bound") == "mfma":

@@ -21,8 +21,8 @@ UP_BF16, UP_F32 = 0, 1
 EXPORTS = ["uniprefill_plan", "uniprefill_score", "uniprefill_select", "uniprefill_compact",
            "uniprefill_scatter", "uniprefill_fused", "uniprefill_fused_phases", "uniprefill_status_string"]
 
-UP_PHASE_PLAN, UP_PHASE_ROW_STATS, UP_PHASE_MERGE_STATS, UP_PHASE_COLUMN_SUMS, UP_PHASE_SELECT_COMPACT = 1, 2, 4, 8, 16
-UP_PHASE_ALL = 31
+UP_PHASE_PLAN, UP_PHASE_ROW_STATS, UP_PHASE_MERGE_STATS, UP_PHASE_SWEEP_SELECT_COMPACT = 1, 2, 4, 8
+UP_PHASE_ALL = 15
 
 
 class up_params(ctypes.Structure):

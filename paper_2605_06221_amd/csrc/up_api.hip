@@ -7,6 +7,7 @@
 
 #include "up_common.h"
 #include "up_kernels.h"
+#include "up_select.h"
 
 using namespace up;
 
@@ -27,7 +28,7 @@ int check_params(const up_params* p, bool need_qk, bool need_hidden, Problem* pb
   q.G = p->block_size; q.n_obs = p->n_obs; q.n_sink = p->n_sink;
   q.Hq = p->num_q_heads; q.Hkv = p->num_kv_heads; q.d = p->hidden_dim;
   q.q_stride = p->q_row_stride; q.k_stride = p->k_row_stride; q.h_stride = p->hidden_row_stride;
-  q.Gq = 1; q.CK = 128; q.tpw = 1; q.n_slab = 1;
+  q.Gq = 1;
   if (need_qk) {
     if (p->head_dim != 128) return UP_ERR_UNSUPPORTED;
     if (p->num_q_heads < 1 || p->num_kv_heads < 1) return UP_ERR_SHAPE;
@@ -43,14 +44,6 @@ int check_params(const up_params* p, bool need_qk, bool need_hidden, Problem* pb
     q.Gq = p->num_q_heads / p->num_kv_heads;
     q.qk_is_f32 = p->qk_dtype == UP_F32;
     q.scale = p->softmax_scale > 0.0f ? p->softmax_scale : 1.0f / sqrtf((float)p->head_dim);
-    // launch shape of the scoring passes
-    const int tiles = ceil_div(q.n_obs * q.Gq, 16);
-    q.tpw = imin(8, ceil_div(tiles, 8));
-    q.n_slab = ceil_div(tiles, 8 * q.tpw);
-    long long ck = ((long long)q.T * q.Hkv * q.n_slab / 1024) / 64 * 64;
-    if (ck < 128) ck = 128;
-    if (ck > 1024) ck = 1024;
-    q.CK = (int)ck;
   }
   if (need_hidden) {
     if (p->hidden_dim < 1) return UP_ERR_SHAPE;
@@ -61,7 +54,7 @@ int check_params(const up_params* p, bool need_qk, bool need_hidden, Problem* pb
         (p->hidden_row_stride * q.hidden_elem_bytes) % 16 != 0)
       return UP_ERR_ALIGN;
   }
-  q.chunk_slots = q.T / q.CK + q.R;
+  q.key_block_slots = q.T / kKeyBlock + q.R;
   const long long rs = (long long)q.R * q.n_obs;
   q.row_slots = rs < q.T ? (int)rs : q.T;
   *pb = q;
@@ -126,8 +119,9 @@ int uniprefill_score(const up_params* p, const void* q, const void* k, const int
   if (workspace == nullptr || workspace_bytes < workspace_layout(pb).total) return UP_ERR_WORKSPACE;
   if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return UP_ERR_ALIGN;
   hipStream_t s = (hipStream_t)stream;
-  if (launch_score_passes(pb, q, k, cu_seqlens_dev, workspace, s) != hipSuccess) return UP_ERR_HIP;
-  if (launch_finalise_scores(pb, cu_seqlens_dev, workspace, scores_out, s) != hipSuccess)
+  if (launch_row_stats(pb, q, k, cu_seqlens_dev, workspace, s) != hipSuccess) return UP_ERR_HIP;
+  if (launch_merge_stats(pb, cu_seqlens_dev, workspace, s) != hipSuccess) return UP_ERR_HIP;
+  if (launch_column_sums(pb, q, k, cu_seqlens_dev, workspace, scores_out, nullptr, s) != hipSuccess)
     return UP_ERR_HIP;
   return UP_OK;
 }
@@ -146,9 +140,9 @@ int uniprefill_select(const up_params* p, const float* scores, const int32_t* cu
   hipStream_t s = (hipStream_t)stream;
   if (launch_plan(pb, cu_seqlens_dev, keep_ratio_dev, new_cu_seqlens_dev, s) != hipSuccess)
     return UP_ERR_HIP;
-  if (launch_select(pb, scores, nullptr, 0, cu_seqlens_dev, keep_ratio_dev, new_cu_seqlens_dev,
-                    kept_idx, nullptr, nullptr, nullptr, nullptr, nullptr, s) != hipSuccess)
-    return UP_ERR_HIP;
+  const SelectArgs sa = make_select_args(pb, scores, cu_seqlens_dev, keep_ratio_dev, new_cu_seqlens_dev,
+                                         kept_idx, nullptr, nullptr, nullptr, nullptr);
+  if (launch_select(pb, sa, s) != hipSuccess) return UP_ERR_HIP;
   return UP_OK;
 }
 
@@ -207,16 +201,19 @@ int uniprefill_fused_phases(const up_params* p, const void* q, const void* k, co
   if ((phase_mask & UP_PHASE_PLAN) &&
       launch_plan(pb, cu_seqlens_dev, keep_ratio_dev, new_cu_seqlens_dev, s) != hipSuccess)
     return UP_ERR_HIP;
-  for (int ph = 1; ph <= 3; ++ph)
-    if ((phase_mask & (UP_PHASE_PLAN << ph)) &&
-        launch_score_phase(pb, ph, q, k, cu_seqlens_dev, workspace, s) != hipSuccess)
-      return UP_ERR_HIP;
-  const double* parts = (const double*)((const char*)workspace + w.part_o_off);
-  if ((phase_mask & UP_PHASE_SELECT_COMPACT) &&
-      launch_select(pb, nullptr, parts, pb.Hkv * pb.n_slab, cu_seqlens_dev, keep_ratio_dev,
-                    new_cu_seqlens_dev, kept_idx, scores_out, hidden, pos, hidden_out, pos_out,
-                    s) != hipSuccess)
+  if ((phase_mask & UP_PHASE_ROW_STATS) &&
+      launch_row_stats(pb, q, k, cu_seqlens_dev, workspace, s) != hipSuccess)
     return UP_ERR_HIP;
+  if ((phase_mask & UP_PHASE_MERGE_STATS) &&
+      launch_merge_stats(pb, cu_seqlens_dev, workspace, s) != hipSuccess)
+    return UP_ERR_HIP;
+  if (phase_mask & UP_PHASE_SWEEP_SELECT_COMPACT) {
+    const SelectArgs sa = make_select_args(pb, nullptr, cu_seqlens_dev, keep_ratio_dev,
+                                           new_cu_seqlens_dev, kept_idx, hidden, pos, hidden_out,
+                                           pos_out);
+    if (launch_column_sums(pb, q, k, cu_seqlens_dev, workspace, scores_out, &sa, s) != hipSuccess)
+      return UP_ERR_HIP;
+  }
   return UP_OK;
 }
 

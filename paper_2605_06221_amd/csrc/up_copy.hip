@@ -6,25 +6,9 @@
 // key tensor from the last-level cache between the two scoring passes.
 #include "up_common.h"
 #include "up_kernels.h"
+#include "up_select.h"
 
 namespace up {
-
-__device__ __forceinline__ void copy_row_wave(const char* __restrict__ src, char* __restrict__ dst,
-                                              long long row_bytes, int lane) {
-  constexpr int U = 4;
-  long long off = (long long)lane * 16;
-  for (; off + (U - 1) * 1024 < row_bytes; off += U * 1024) {
-    u32x4 v[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) v[u] = __builtin_nontemporal_load((const u32x4*)(src + off + u * 1024));
-#pragma unroll
-    for (int u = 0; u < U; ++u) __builtin_nontemporal_store(v[u], (u32x4*)(dst + off + u * 1024));
-  }
-  for (; off < row_bytes; off += 1024) {
-    u32x4 v = __builtin_nontemporal_load((const u32x4*)(src + off));
-    __builtin_nontemporal_store(v, (u32x4*)(dst + off));
-  }
-}
 
 template <bool SCATTER>
 __global__ __launch_bounds__(256) void k_rows(const char* __restrict__ src, char* __restrict__ dst,

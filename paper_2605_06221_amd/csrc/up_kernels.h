@@ -7,6 +7,8 @@
 
 namespace up {
 
+struct SelectArgs;
+
 // Static description of one call, derived on the host from up_params.
 struct Problem {
   int R, T;
@@ -17,17 +19,13 @@ struct Problem {
   int hidden_elem_bytes;      // 2 (bf16) or 4 (f32)
   int qk_is_f32;
   float scale;                // softmax scale (resolved, > 0)
-  // scoring launch shape
-  int CK;                     // keys per work-group chunk (multiple of 64)
-  int tpw;                    // 16-row query tiles per wave
-  int n_slab;                 // row slabs per kv head
-  int chunk_slots;            // T / CK + R
-  int row_slots;              // min(T, R * n_obs)
+  int key_block_slots;        // T / 256 + R: work-groups of the scoring sweeps
+  int row_slots;              // min(T, R * n_obs): window rows of all sequences
 };
 
 // Workspace carve-up (byte offsets, each 256-aligned).
 struct Workspace {
-  size_t stat_part_off, stat_fin_off, part_o_off, total;
+  size_t stat_part_off, stat_fin_off, total;
 };
 Workspace workspace_layout(const Problem& pb);
 
@@ -41,22 +39,20 @@ hipError_t launch_scatter(const Problem& pb, const void* hidden_compact, const i
 // --- selection
 hipError_t launch_plan(const Problem& pb, const int32_t* cu, const float* ratio, int32_t* new_cu,
                        hipStream_t s);
-// scores != nullptr: select on given scores.  Otherwise sum `parts` partial score
-// planes [n_parts][T] (double), normalise, floor, optionally write scores_out.
-// hidden != nullptr: also gather the kept rows (fused select+compact).
-hipError_t launch_select(const Problem& pb, const float* scores, const double* parts, int n_parts,
-                         const int32_t* cu, const float* ratio, const int32_t* new_cu,
-                         int32_t* kept_idx, float* scores_out, const void* hidden,
-                         const int32_t* pos, void* hidden_out, int32_t* pos_out, hipStream_t s);
+SelectArgs make_select_args(const Problem& pb, const float* scores, const int32_t* cu, const float* ratio,
+                            const int32_t* new_cu, int32_t* kept_idx, const void* hidden,
+                            const int32_t* pos, void* hidden_out, int32_t* pos_out);
+hipError_t launch_select(const Problem& pb, const SelectArgs& a, hipStream_t s);
 
 // --- scoring (Eq. 2-3)
-// phase 1: row statistics per key chunk; 2: merge of the chunk statistics; 3: normalised
-// column sums (partial score planes in the workspace).
-hipError_t launch_score_phase(const Problem& pb, int phase, const void* q, const void* k,
-                              const int32_t* cu, void* workspace, hipStream_t s);
-hipError_t launch_score_passes(const Problem& pb, const void* q, const void* k, const int32_t* cu,
-                               void* workspace, hipStream_t s);
-hipError_t launch_finalise_scores(const Problem& pb, const int32_t* cu, const void* workspace,
-                                  float* scores_out, hipStream_t s);
+// pass 1: softmax statistics of every window row per 256-key block (into the workspace)
+hipError_t launch_row_stats(const Problem& pb, const void* q, const void* k, const int32_t* cu,
+                            void* workspace, hipStream_t s);
+// merge of the per-block statistics into one (reference, 1/sum) per row
+hipError_t launch_merge_stats(const Problem& pb, const int32_t* cu, void* workspace, hipStream_t s);
+// pass 2: normalised weights summed per token; optional scores_out; sel != nullptr runs the
+// block-local top-k (and the gather when sel->hidden is set) in the same kernel
+hipError_t launch_column_sums(const Problem& pb, const void* q, const void* k, const int32_t* cu,
+                              void* workspace, float* scores_out, const SelectArgs* sel, hipStream_t s);
 
 }  // namespace up

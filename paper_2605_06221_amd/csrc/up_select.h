@@ -1,0 +1,121 @@
+// Block-local top-k selection with forced retention, and the gather of the kept
+// rows: device code shared by the stand-alone selection kernel and the fused
+// score+select+compact kernel.
+//
+// One selection block is G <= 128 consecutive tokens of one sequence.  Each
+// token builds the 64-bit ordering key of Eq. 14 -- the order-preserving
+// integer image of its float score in the upper word, the complemented in-block
+// index in the lower word, forced tokens (sinks, query window) lifted above
+// every score -- and finds its rank by counting larger keys in LDS.  Keys are
+// unique, so ranks are a permutation and "rank < k_g" keeps exactly k_g tokens
+// with ties going to the lower index.  Wavefront ballots give the ordered
+// output positions; the block's output offset is closed-form (kept_before), so
+// no scan over blocks is needed.
+#pragma once
+
+#include "up_common.h"
+
+namespace up {
+
+constexpr int kKeyBlock = 256;       // tokens per work-group of the fused kernel
+
+struct SelectArgs {
+  const float* scores;      // stand-alone kernel: given scores
+  const int32_t* cu;
+  const float* ratio;
+  const int32_t* new_cu;
+  int32_t* kept_idx;
+  const char* hidden;       // nullptr => selection only
+  const int32_t* pos;
+  char* hidden_out;
+  int32_t* pos_out;
+  long long row_bytes, stride_bytes;
+  int R, T, G, n_obs, n_sink;
+};
+
+struct SelectSmem {
+  unsigned long long keys[128];
+  int kept_local[128];
+  float score[kKeyBlock];
+  int cnt0, base;
+};
+
+// Monotone IEEE-754 -> unsigned map of Eq. 14 (sign read from the sign bit).
+__device__ __forceinline__ unsigned phi(float x) {
+  const unsigned b = __float_as_uint(x);
+  return (b & 0x80000000u) ? ~b : (b ^ 0x80000000u);
+}
+
+// One wave copies one row: 128-bit non-temporal accesses, four loads in flight.
+__device__ __forceinline__ void copy_row_wave(const char* __restrict__ src, char* __restrict__ dst,
+                                              long long row_bytes, int lane) {
+  constexpr int U = 4;
+  long long off = (long long)lane * 16;
+  for (; off + (U - 1) * 1024 < row_bytes; off += U * 1024) {
+    u32x4 v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) v[u] = __builtin_nontemporal_load((const u32x4*)(src + off + u * 1024));
+#pragma unroll
+    for (int u = 0; u < U; ++u) __builtin_nontemporal_store(v[u], (u32x4*)(dst + off + u * 1024));
+  }
+  for (; off < row_bytes; off += 1024) {
+    u32x4 v = __builtin_nontemporal_load((const u32x4*)(src + off));
+    __builtin_nontemporal_store(v, (u32x4*)(dst + off));
+  }
+}
+
+// Select (and, if a.hidden is set, gather) block g of sequence r.  Called by all
+// 256 threads of the work-group; `block_scores` points at the block's scores
+// (LDS or global), indexed by the token's position inside the block.
+__device__ __forceinline__ void select_block(const SelectArgs& a, SelectSmem& sm, int r, int c0, int N,
+                                             int g, const float* block_scores) {
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  SeqGeom sg{N, a.G, a.n_obs, a.n_sink, (double)a.ratio[r]};
+  const int lo = g * a.G;
+  const int L = imin(a.G, N - lo);
+  const int kg = block_kept(sg, g);
+  if (tid == 0) sm.base = a.new_cu[r] + kept_before(sg, g);
+
+  if (tid < L) {
+    const int i = lo + tid;
+    const bool forced = (i < a.n_sink) || (i >= N - a.n_obs);
+    const unsigned hi = forced ? 0xFFFFFFFFu : phi(block_scores[tid]);
+    sm.keys[tid] = ((unsigned long long)hi << 32) | (unsigned)(a.G - 1 - tid);
+  }
+  __syncthreads();
+  bool keep = false;
+  if (tid < L) {
+    if (kg >= L) {
+      keep = true;
+    } else {
+      const unsigned long long mine = sm.keys[tid];
+      int rank = 0;
+      for (int j = 0; j < L; ++j) rank += sm.keys[j] > mine ? 1 : 0;
+      keep = rank < kg;
+    }
+  }
+  // ordered positions: wave 0 holds tokens 0..63, wave 1 tokens 64..127
+  const unsigned long long bal = __ballot(keep);
+  const int before = __popcll(bal & ((1ull << lane) - 1ull));
+  if (wave == 0 && lane == 0) sm.cnt0 = __popcll(bal);
+  __syncthreads();
+  const int base = sm.base;
+  if (keep) {
+    const int at = before + (wave == 1 ? sm.cnt0 : 0);
+    sm.kept_local[at] = tid;
+    a.kept_idx[base + at] = c0 + lo + tid;
+  }
+  __syncthreads();
+  if (a.hidden != nullptr) {
+    for (int j = wave; j < kg; j += 4) {
+      const long long srow = c0 + lo + sm.kept_local[j];
+      copy_row_wave(a.hidden + srow * a.stride_bytes, a.hidden_out + (long long)(base + j) * a.stride_bytes,
+                    a.row_bytes, lane);
+    }
+    if (a.pos != nullptr && tid < kg) a.pos_out[base + tid] = a.pos[c0 + lo + sm.kept_local[tid]];
+  }
+  __syncthreads();   // the shared arrays are reused by the next block
+}
+
+}  // namespace up
