@@ -65,7 +65,7 @@ __device__ __forceinline__ void copy_row_wave(const char* __restrict__ src, char
 }
 
 // Select (and, if a.hidden is set, gather) block g of sequence r.  Called by all
-// 256 threads of the work-group; `block_scores` points at the block's scores
+// threads of the work-group (at least 128; whole waves); `block_scores` points at the block's scores
 // (LDS or global), indexed by the token's position inside the block.
 __device__ __forceinline__ void select_block(const SelectArgs& a, SelectSmem& sm, int r, int c0, int N,
                                              int g, const float* block_scores) {
@@ -108,7 +108,8 @@ __device__ __forceinline__ void select_block(const SelectArgs& a, SelectSmem& sm
   }
   __syncthreads();
   if (a.hidden != nullptr) {
-    for (int j = wave; j < kg; j += 4) {
+    const int n_waves = blockDim.x >> 6;
+    for (int j = wave; j < kg; j += n_waves) {
       const long long srow = c0 + lo + sm.kept_local[j];
       copy_row_wave(a.hidden + srow * a.stride_bytes, a.hidden_out + (long long)(base + j) * a.stride_bytes,
                     a.row_bytes, lane);
