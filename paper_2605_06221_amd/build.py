@@ -15,6 +15,9 @@ HIPCC_FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
     # packed-FP32 instructions are kept out of all device code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # device code never sees NaN by contract (finite inputs); without this every fmaxf drags a
+    # canonicalising v_max along.  Infinities are still honoured (masks use -inf).
+    "-Xarch_device", "-fno-honor-nans",
     "-Wno-unused-command-line-argument",
 ]
 

@@ -69,9 +69,10 @@ __device__ __forceinline__ void divmod(unsigned x, unsigned d, unsigned magic, i
   ro = (int)rr;
 }
 
-// LDS of one work-group (< 80 KB so that two work-groups share a CU).  The staged query
-// rows are dead once the sweep is over, so the selection state reuses their space; the
-// per-wave statistics (pass 1) and the per-row constants (pass 2) share another region.
+// LDS of one work-group.  The staged query rows are dead once the sweep is over, so the
+// selection state reuses their space.  Small per-unit tables live in rings: a unit's vector
+// work trails its matrix work by one phase and crosses the unit barrier, so the tables of
+// three units can be live at once.
 struct SweepSmem {
   union {
     __align__(16) unsigned char q[2][kUnit * kQRow];   // staged query rows (bf16), double-buffered
@@ -81,10 +82,23 @@ struct SweepSmem {
     } tail;
   };
   union {
-    float2 wstat[kSweepWaves][kUnit];                  // pass 1: per-wave (reference, sum) per staged row
-    __align__(16) float2 cst[2][kUnit];                // pass 2: (negative reference, 1/sum) per staged row
+    float2 wstat[3][kSweepWaves][kUnit];               // pass 1: per-wave (reference, sum) per staged row
+    __align__(16) float2 cst[4][kUnit];                // pass 2: (negative reference, 1/sum) per staged row
   };
-  __align__(16) int rowpos[2][kUnit];                  // local position of each staged row, -1 = no such row
+  __align__(16) int rowpos[4][kUnit];                  // local position of each staged row, -1 = no such row
+};
+
+// Position of a staging unit inside the sweep: kv head g, unit u of that head's rows and,
+// when units never straddle query heads, the query head hh inside the group and the first
+// window row jj0 of the unit.  Advanced without divisions.
+struct UnitCursor {
+  int g, u, hh, jj0;
+  __device__ __forceinline__ void advance(int n_units, int n_eff) {
+    ++u;
+    jj0 += kUnit;
+    if (jj0 >= n_eff) { jj0 = 0; ++hh; }
+    if (u == n_units) { u = 0; ++g; hh = 0; jj0 = 0; }
+  }
 };
 
 template <int PASS, bool EDGE>
@@ -102,68 +116,67 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem& sm, i
   const int key_base = kblock * kKeyBlock + wave * 32;     // first local key of this wave
   const float c = a.c;
   const int rs0 = rowslot_base(c0, r, a.n_obs);
+  const bool whole_heads = (n_eff % kUnit) == 0;           // a unit never straddles two query heads
 
-  // ---- key operands of one kv head: one 32-key tile, lane = (key l32, k-slice half)
-  bf16x8 kf[8];
-  auto load_keys = [&](int g) {
-    // keys past the end of the sequence re-read the last key (finite values): pass 1 masks
-    // them (such a block is always an edge block), pass 2 never emits their scores
-    const int key = imin(key_base + l32, N - 1);
-    const char* kp = a.k + (long long)(c0 + key) * a.k_stride_b + (long long)g * 256 + half * 16;
+  // ---- key operands of one kv head: one 32-key tile, lane = (key l32, k-slice half).
+  // The next head's keys are fetched into kfn one phase before they are needed.
+  bf16x8 kf[8], kfn[8];
+  // keys past the end of the sequence re-read the last key (finite values): pass 1 masks
+  // them (such a block is always an edge block), pass 2 never emits their scores
+  const char* k_lane = a.k + (long long)(c0 + imin(key_base + l32, N - 1)) * a.k_stride_b + half * 16;
+  auto load_keys = [&](bf16x8 (&dst)[8], int g) {
 #pragma unroll
-    for (int kk = 0; kk < 8; ++kk) kf[kk] = as_bf16x8(*(const u32x4*)(kp + kk * 32));
+    for (int kk = 0; kk < 8; ++kk) dst[kk] = as_bf16x8(*(const u32x4*)(k_lane + (long long)g * 256 + kk * 32));
   };
 
   // ---- staging of one unit of query rows: 2048 pieces of 16 bytes (128 rows x 16), 4 per
-  // thread, moved in two rounds of 2.  Thread t owns column t%16 of rows t/16 + 32*i.
-  const bool whole_heads = (n_eff % kUnit) == 0;     // a unit never straddles two heads
+  // thread: column t%16 of rows t/16 + 32*i.  Fetched into registers right after a unit
+  // barrier, written to LDS just before the next one.
   const int my_row = tid >> 4;
   const char* q_seq = a.q + (long long)(c0 + first_q) * a.q_stride_b + (tid & 15) * 16;
-  u32x4 pre_q[2];
-  auto fetch_round = [&](int f, int round) {
-    const int g = f / n_units;
-    const int u = f - g * n_units;
+  const long long my_row_off = (long long)my_row * a.q_stride_b;
+  u32x4 pre_q[4];
+  auto fetch_unit = [&](const UnitCursor& uc) {
     if (whole_heads) {
-      const int per_head = n_eff / kUnit;
-      const int hh = u / per_head;
-      const int jj0 = (u - hh * per_head) * kUnit;
-      const char* base = q_seq + (long long)(g * a.Gq + hh) * 256 + (long long)(jj0 + my_row) * a.q_stride_b;
+      const char* base = q_seq + (long long)(uc.g * a.Gq + uc.hh) * 256 + (long long)uc.jj0 * a.q_stride_b + my_row_off;
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
-        pre_q[i] = *(const u32x4*)(base + (long long)((round * 2 + i) * 32) * a.q_stride_b);
+      for (int i = 0; i < 4; ++i) pre_q[i] = *(const u32x4*)(base + (long long)(i * 32) * a.q_stride_b);
     } else {
       // general case: one division per piece; rows past the end re-read the last row
       // (finite values; their results are discarded through the per-row constants)
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const int rho = imin(u * kUnit + my_row + (round * 2 + i) * 32, rows_total - 1);
+      for (int i = 0; i < 4; ++i) {
+        const int rho = imin(uc.u * kUnit + my_row + i * 32, rows_total - 1);
         int hh, jj;
         divmod((unsigned)rho, (unsigned)n_eff, magic, hh, jj);
-        pre_q[i] = *(const u32x4*)(q_seq + (long long)jj * a.q_stride_b + (long long)(g * a.Gq + hh) * 256);
+        pre_q[i] = *(const u32x4*)(q_seq + (long long)jj * a.q_stride_b + (long long)(uc.g * a.Gq + hh) * 256);
       }
     }
   };
-  auto stash_round = [&](int buf, int round) {
+  auto stash_unit = [&](int buf) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
-      *(u32x4*)(&sm.q[buf][(my_row + (round * 2 + i) * 32) * kQRow + (tid & 15) * 16]) = pre_q[i];
+    for (int i = 0; i < 4; ++i)
+      *(u32x4*)(&sm.q[buf][(my_row + i * 32) * kQRow + (tid & 15) * 16]) = pre_q[i];
   };
-  // per-row constants of a unit: threads 0..127 take one row each
-  auto stage_meta = [&](int f, int buf) {
+  // row of a unit -> (query head inside the group, window row), or false if there is no such row
+  auto unit_row = [&](const UnitCursor& uc, int row, int& hh, int& jj) -> bool {
+    const int rho = uc.u * kUnit + row;
+    if (whole_heads) { hh = uc.hh; jj = uc.jj0 + row; return true; }
+    if (rho >= rows_total) { hh = 0; jj = 0; return false; }
+    divmod((unsigned)rho, (unsigned)n_eff, magic, hh, jj);
+    return true;
+  };
+  // per-row tables of a unit: threads 0..127 take one row each
+  auto stage_meta = [&](const UnitCursor& uc, int ring) {
     if (tid < kUnit) {
-      const int g = f / n_units;
-      const int u = f - g * n_units;
-      const int rho = u * kUnit + tid;
       float2 cst = make_float2(-INFINITY, 0.0f);   // no such row: weight exactly zero
-      int pos = -1;
-      if (rho < rows_total) {
-        int hh, jj;
-        divmod((unsigned)rho, (unsigned)n_eff, magic, hh, jj);
+      int pos = -1, hh, jj;
+      if (unit_row(uc, tid, hh, jj)) {
         pos = first_q + jj;
-        if (PASS == 2) cst = a.stat_fin[(size_t)(g * a.Gq + hh) * a.row_slots + rs0 + jj];
+        if (PASS == 2) cst = a.stat_fin[(size_t)(uc.g * a.Gq + hh) * a.row_slots + rs0 + jj];
       }
-      if (PASS == 2) sm.cst[buf][tid] = cst;
-      sm.rowpos[buf][tid] = pos;
+      if (PASS == 2) sm.cst[ring][tid] = cst;
+      sm.rowpos[ring][tid] = pos;
     }
   };
 
@@ -171,15 +184,16 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem& sm, i
 
   // ---- one phase = one 32x32 tile: row tile rt of the staged unit against the wave's keys.
   // A phase has a matrix half (8 MFMAs) and a vector half (softmax arithmetic on the 16
-  // results per lane).  In program order, two MFMAs of phase rt+1 are followed by a quarter
-  // of the vector half of phase rt, four times over, with scheduling barriers in between so
-  // that the order (and the register footprint) stays as written: the matrix pipe works on
-  // the MFMAs while the wave issues the vector instructions behind them.
-  u32x4 qv[8];                         // operand fragments of the row tile whose MFMAs are being issued
-  auto load_rows = [&](int buf, int rt) {
+  // results per lane).  In program order, two MFMAs of a phase are followed by the LDS reads
+  // that refill the two operand registers just consumed with the next phase's rows, and by a
+  // quarter of the vector half of the previous phase; scheduling barriers keep that order (and
+  // the register footprint) as written.  The matrix pipe works on the MFMAs while the wave
+  // issues the vector instructions behind them, and no LDS latency is exposed.
+  u32x4 qv[8];                         // operand fragments: row tile of the phase being issued / the next one
+  auto load_rows_part = [&](int buf, int rt, int part) {
     const unsigned char* qrow = &sm.q[buf][(rt * 32 + l32) * kQRow + half * 16];
 #pragma unroll
-    for (int kk = 0; kk < 8; ++kk) qv[kk] = *(const u32x4*)(qrow + kk * 32);
+    for (int kk = 2 * part; kk < 2 * part + 2; ++kk) qv[kk] = *(const u32x4*)(qrow + kk * 32);
   };
   auto mfma_part = [&](f32x16& acc, int part) {
     if (part == 0) {
@@ -196,19 +210,24 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem& sm, i
   };
   float p1_ref = 0.0f, p1_negref = 0.0f, p1_l0 = 0.0f, p1_l1 = 0.0f;   // pass 1 phase state
   float p2_cs0 = 0.0f, p2_cs1 = 0.0f;                                    // pass 2 phase state
-  auto valu_part = [&](int buf, int rt, f32x16& acc, int part) {
+  // vector quarter `part` of the phase (unit with table ring slots ring4 / ring3, row tile rt)
+  auto valu_part = [&](int ring4, int ring3, int rt, f32x16& acc, int part) {
     if (PASS == 1) {
       // element e = key 8*(e/4) + 4*half + e%4 of the wave's tile, query row rt*32 + l32
       if (part == 0) {
         if (EDGE) {
-          const int rp = sm.rowpos[buf][rt * 32 + l32];
+          const int rp = sm.rowpos[ring4][rt * 32 + l32];
 #pragma unroll
           for (int e = 0; e < 16; ++e)
             if (key_base + 8 * (e >> 2) + 4 * half + (e & 3) > rp) acc[e] = -INFINITY;
         }
-        float m = fmaxf(acc[0], acc[1]);
+        float m0 = fmaxf(acc[0], acc[1]), m1 = fmaxf(acc[2], acc[3]);
 #pragma unroll
-        for (int e = 2; e < 16; ++e) m = fmaxf(m, acc[e]);
+        for (int e = 4; e < 16; e += 4) {
+          m0 = fmaxf(m0, fmaxf(acc[e], acc[e + 1]));
+          m1 = fmaxf(m1, fmaxf(acc[e + 2], acc[e + 3]));
+        }
+        const float m = fmaxf(m0, m1);
         p1_ref = m * c;                          // reference in log2 units
         p1_negref = (EDGE && m == -INFINITY) ? 0.0f : -p1_ref;
         p1_l0 = 0.0f;
@@ -232,21 +251,21 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem& sm, i
           if (ref == -INFINITY) s_a = 0.0f;
           if (ref_o == -INFINITY) s_b = 0.0f;
         }
-        if (half == 0) sm.wstat[wave][rt * 32 + l32] = make_float2(mm, s_a + s_b);
+        if (half == 0) sm.wstat[ring3][wave][rt * 32 + l32] = make_float2(mm, s_a + s_b);
       }
     } else {
       // element e = query row rt*32 + 8*(e/4) + 4*half + e%4, key l32 of the wave's tile; part = e/4
       if (part == 0) { p2_cs0 = 0.0f; p2_cs1 = 0.0f; }
       const int row0 = rt * 32 + 8 * part + 4 * half;
-      const f32x4 cs01 = *(const f32x4*)(&sm.cst[buf][row0]);       // rows row0, row0+1
-      const f32x4 cs23 = *(const f32x4*)(&sm.cst[buf][row0 + 2]);   // rows row0+2, row0+3
+      const f32x4 cs01 = *(const f32x4*)(&sm.cst[ring4][row0]);       // rows row0, row0+1
+      const f32x4 cs23 = *(const f32x4*)(&sm.cst[ring4][row0 + 2]);   // rows row0+2, row0+3
       const float negm[4] = {cs01[0], cs01[2], cs23[0], cs23[2]};
       const float wr[4] = {cs01[1], cs01[3], cs23[1], cs23[3]};
       float x[4];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         x[i] = fmaf(acc[part * 4 + i], c, negm[i]);
-        if (EDGE && key_base + l32 > sm.rowpos[buf][row0 + i]) x[i] = -INFINITY;
+        if (EDGE && key_base + l32 > sm.rowpos[ring4][row0 + i]) x[i] = -INFINITY;
       }
       p2_cs0 = fmaf(exp2_hw(x[0]), wr[0], p2_cs0);
       p2_cs1 = fmaf(exp2_hw(x[1]), wr[1], p2_cs1);
@@ -255,84 +274,96 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem& sm, i
       if (part == 3) col64 += (double)(p2_cs0 + p2_cs1);
     }
   };
-  // keeps memory accesses (IR level) and all instructions (scheduler) on their side of this point
-  // (the running sums pass through the asm statement, so the arithmetic that feeds them
-  // cannot be sunk below it either)
+  // keeps memory accesses (IR level) and all instructions (scheduler) on their side of this
+  // point; the running sums pass through the asm statement, so the arithmetic that feeds
+  // them cannot be sunk below it either
   auto pin_order = [&]() {
     if (PASS == 1) asm volatile("" : "+v"(p1_l0), "+v"(p1_l1), "+v"(p1_negref) : : "memory");
     else asm volatile("" : "+v"(p2_cs0), "+v"(p2_cs1) : : "memory");
     __builtin_amdgcn_sched_barrier(0);
   };
-  // matrix half of the next row tile (into acc_m) next to the vector half of row tile rt_v (on acc_v)
-  auto overlapped = [&](int buf, f32x16& acc_m, int rt_v, f32x16& acc_v) {
+  // matrix half of a phase into acc_m, refilling the operand registers from (buf_n, rt_n),
+  // next to the vector half of the previous phase (acc_v; tables ring4_v / ring3_v, row tile rt_v)
+  auto overlapped = [&](f32x16& acc_m, int buf_n, int rt_n, bool refill, bool with_valu, int ring4_v,
+                        int ring3_v, int rt_v, f32x16& acc_v) {
 #pragma unroll
     for (int part = 0; part < 4; ++part) {
       mfma_part(acc_m, part);
-      valu_part(buf, rt_v, acc_v, part);
+      if (refill) load_rows_part(buf_n, rt_n, part);
+      if (with_valu) valu_part(ring4_v, ring3_v, rt_v, acc_v, part);
       pin_order();
     }
   };
+  // pass 1: merge the eight waves' statistics of the rows of unit `uc` (ring slot ring3) and
+  // write the key block's partial.  Wave w takes rows 16w..16w+15; four lanes share a row and
+  // take two waves' entries each.
+  auto merge_unit = [&](const UnitCursor& uc, int ring3) {
+    const int row = wave * 16 + (lane & 15), sub = lane >> 4;
+    const float2 s0 = sm.wstat[ring3][2 * sub][row], s1 = sm.wstat[ring3][2 * sub + 1][row];
+    float mm = fmaxf(s0.x, s1.x);
+    float l = (s0.x == -INFINITY ? 0.0f : s0.y * exp2_hw(s0.x - mm)) +
+              (s1.x == -INFINITY ? 0.0f : s1.y * exp2_hw(s1.x - mm));
+#pragma unroll
+    for (int sh = 16; sh <= 32; sh <<= 1) {
+      const float m_o = __shfl_xor(mm, sh);
+      const float l_o = __shfl_xor(l, sh);
+      const float m_n = fmaxf(mm, m_o);
+      l = (mm == -INFINITY ? 0.0f : l * exp2_hw(mm - m_n)) + (m_o == -INFINITY ? 0.0f : l_o * exp2_hw(m_o - m_n));
+      mm = m_n;
+    }
+    int hh, jj;
+    if (sub == 0 && unit_row(uc, row, hh, jj))
+      a.stat_part[(size_t)slot * (a.Hq * a.n_obs) + (size_t)(uc.g * a.Gq + hh) * a.n_obs + jj] = make_float2(mm, l);
+  };
 
-  fetch_round(0, 0);
-  stash_round(0, 0);
-  fetch_round(0, 1);
-  stash_round(0, 1);
-  stage_meta(0, 0);
+  // ---- prologue: unit 0 staged and visible, unit 1 in flight, first rows in registers
+  UnitCursor cur{0, 0, 0, 0};      // unit whose matrix work is being issued
+  UnitCursor prev = cur;           // the unit before it (its last vector half is still pending)
+  UnitCursor nxt = cur;            // unit being staged for the next iteration
+  fetch_unit(cur);
+  stash_unit(0);
+  stage_meta(cur, 0);
+  load_keys(kf, 0);
   __syncthreads();
+  nxt.advance(n_units, n_eff);
+  if (n_flat > 1) fetch_unit(nxt);
+#pragma unroll
+  for (int part = 0; part < 4; ++part) load_rows_part(0, 0, part);
 
-  int f = 0;
-  for (int g = 0; g < a.Hkv; ++g) {
-    load_keys(g);
-    for (int u = 0; u < n_units; ++u, ++f) {
-      const int buf = f & 1;
-      const bool more = f + 1 < n_flat;
-      f32x16 accA, accB;
+  f32x16 accA, accB;
+  for (int f = 0; f < n_flat; ++f) {
+    const int buf = f & 1;
+    const bool more = f + 1 < n_flat;
+    const bool head_ends = more && cur.u == n_units - 1;   // the next unit belongs to the next kv head
+    const int r4 = f & 3, r3 = f % 3;
+    const int pr4 = (f + 3) & 3, pr3 = (f + 2) % 3;         // ring slots of unit f-1
 
-      if (more) fetch_round(f + 1, 0);
-      load_rows(buf, 0);
+    if (head_ends) load_keys(kfn, cur.g + 1);   // needed four phases from now
+    // phase 0 of unit f next to the last vector half of unit f-1
+    overlapped(accA, buf, 1, true, f > 0, pr4, pr3, 3, accB);
+    overlapped(accB, buf, 2, true, true, r4, r3, 0, accA);
+    overlapped(accA, buf, 3, true, true, r4, r3, 1, accB);
+    if (more) { stash_unit(buf ^ 1); stage_meta(nxt, (f + 1) & 3); }
+    __syncthreads();     // unit f+1 is visible; every read of unit f's rows has completed
+    if (PASS == 1 && f > 0) merge_unit(prev, pr3);
+    prev = cur;
+    cur = nxt;
+    if (f + 2 < n_flat) { nxt.advance(n_units, n_eff); fetch_unit(nxt); }
+    // last phase of unit f; the operand registers are refilled with the first rows of unit f+1
+    overlapped(accB, buf ^ 1, 0, more, true, r4, r3, 2, accA);
+    if (head_ends) {
 #pragma unroll
-      for (int part = 0; part < 4; ++part) mfma_part(accA, part);
-      pin_order();
-      load_rows(buf, 1);
-      overlapped(buf, accB, 0, accA);
-      if (more) { stash_round(buf ^ 1, 0); fetch_round(f + 1, 1); }
-      load_rows(buf, 2);
-      overlapped(buf, accA, 1, accB);
-      load_rows(buf, 3);
-      overlapped(buf, accB, 2, accA);
-#pragma unroll
-      for (int part = 0; part < 4; ++part) { valu_part(buf, 3, accB, part); pin_order(); }
-      if (more) { stash_round(buf ^ 1, 1); stage_meta(f + 1, buf ^ 1); }
-      __syncthreads();
-
-      if (PASS == 1) {
-        if (tid < kUnit) {
-          // merge the eight waves' statistics of one staged row, write the key block's partial
-          const int rho = u * kUnit + tid;
-          if (rho < rows_total) {
-            float2 st[kSweepWaves];
-#pragma unroll
-            for (int w2 = 0; w2 < kSweepWaves; ++w2) st[w2] = sm.wstat[w2][tid];
-            float mm = st[0].x;
-#pragma unroll
-            for (int w2 = 1; w2 < kSweepWaves; ++w2) mm = fmaxf(mm, st[w2].x);
-            float l = 0.0f;
-#pragma unroll
-            for (int w2 = 0; w2 < kSweepWaves; ++w2)
-              if (st[w2].x != -INFINITY) l += st[w2].y * exp2_hw(st[w2].x - mm);
-            int hh, jj;
-            divmod((unsigned)rho, (unsigned)n_eff, magic, hh, jj);
-            a.stat_part[(size_t)slot * (a.Hq * a.n_obs) + (size_t)(g * a.Gq + hh) * a.n_obs + jj] =
-                make_float2(mm, l);
-          }
-        }
-        __syncthreads();   // the statistics buffer is written again by the next unit
-      }
+      for (int kk = 0; kk < 8; ++kk) kf[kk] = kfn[kk];
     }
   }
+  // the last vector half, then (pass 1) the statistics of the last unit
+#pragma unroll
+  for (int part = 0; part < 4; ++part) { valu_part((n_flat + 3) & 3, (n_flat + 2) % 3, 3, accB, part); pin_order(); }
+  __syncthreads();
+  if (PASS == 1) merge_unit(prev, (n_flat + 2) % 3);
 
   if (PASS == 2) {
-    // (the loop's last barrier has passed: the staged rows are dead and their space is reused)
+    // (a barrier has passed since the last read of the staged rows: their space is reused)
     // the two lane halves hold the same key over different rows: add them (fixed order)
     const double other = __shfl_xor(col64, 32);
     if (half == 0) sm.tail.o64[wave * 32 + l32] = col64 + other;
@@ -340,7 +371,7 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem& sm, i
 }
 
 template <int PASS>
-__global__ __launch_bounds__(kSweepThreads, 2) void k_sweep(SweepArgs a) {
+__global__ __launch_bounds__(kSweepThreads) void k_sweep(SweepArgs a) {
   __shared__ SweepSmem sm;
   const int slot = blockIdx.x;
   const int r = locate_slot(a.cu, a.R, kKeyBlock, slot);
