@@ -54,7 +54,10 @@ int check_params(const up_params* p, bool need_qk, bool need_hidden, Problem* pb
         (p->hidden_row_stride * q.hidden_elem_bytes) % 16 != 0)
       return UP_ERR_ALIGN;
   }
-  q.key_block_slots = q.T / kKeyBlock + q.R;
+  // keys per work-group of the scoring sweeps: 512 (two key tiles per wave) halves the per-key
+  // overheads; 256 gives twice as many work-groups when the batch cannot fill the 256 CUs otherwise
+  q.key_block = (q.T / 512 + q.R >= 224) ? 512 : 256;
+  q.key_block_slots = q.T / q.key_block + q.R;
   const long long rs = (long long)q.R * q.n_obs;
   q.row_slots = rs < q.T ? (int)rs : q.T;
   *pb = q;

@@ -19,7 +19,8 @@ struct Problem {
   int hidden_elem_bytes;      // 2 (bf16) or 4 (f32)
   int qk_is_f32;
   float scale;                // softmax scale (resolved, > 0)
-  int key_block_slots;        // T / 256 + R: work-groups of the scoring sweeps
+  int key_block;              // keys per work-group of the scoring sweeps: 256 or 512
+  int key_block_slots;        // T / key_block + R: work-groups of the scoring sweeps
   int row_slots;              // min(T, R * n_obs): window rows of all sequences
 };
 

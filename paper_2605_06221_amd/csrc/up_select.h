@@ -17,7 +17,7 @@
 
 namespace up {
 
-constexpr int kKeyBlock = 256;       // tokens per work-group of the fused kernel
+constexpr int kMaxKeyBlock = 512;    // most tokens a work-group of the fused kernel owns
 
 struct SelectArgs {
   const float* scores;      // stand-alone kernel: given scores
@@ -36,7 +36,7 @@ struct SelectArgs {
 struct SelectSmem {
   unsigned long long keys[128];
   int kept_local[128];
-  float score[kKeyBlock];
+  float score[kMaxKeyBlock];
   int cnt0, base;
 };
 

@@ -15,15 +15,17 @@
 //           for its keys, so the per-token score is complete inside the wave:
 //           no partial planes, no atomics, fixed summation order.
 //
-// Work decomposition ("key-stationary"): one work-group = 256 consecutive keys
-// of one sequence, eight waves of 32 keys each.  A wave keeps its keys of the
-// current kv head in registers as MFMA operands (8 k-steps) and sweeps all
+// Work decomposition ("key-stationary"): one work-group = 256 or 512 consecutive
+// keys of one sequence, eight waves of 32 or 64 keys each (KT = 1 or 2 key tiles
+// per wave; the larger block halves the per-key cost of staging, merging and LDS
+// reads and is used when it still yields enough work-groups).  A wave keeps its
+// keys of the current kv head in registers as MFMA operands and sweeps all
 // query rows of that head's GQA group; the rows stream through LDS in units of
 // 128 (coalesced 128-bit loads, padded rows, read back in operand layout),
 // shared by the eight waves.  v_mfma_f32_32x32x16_bf16: bf16 products are exact
 // in fp32 and accumulate in fp32.
 //
-// Because a pass-2 work-group ends with the final scores of 256 consecutive
+// Because a pass-2 work-group ends with the final scores of its consecutive
 // tokens, it owns whole selection blocks (G divides 256) and goes straight on
 // to the block-local top-k and the gather of the kept rows: the HBM-bound copy
 // of one work-group overlaps the matrix work of the others.
@@ -77,7 +79,7 @@ struct SweepSmem {
   union {
     __align__(16) unsigned char q[2][kUnit * kQRow];   // staged query rows (bf16), double-buffered
     struct {
-      double o64[kKeyBlock];                           // pass 2: column sums of the block's keys
+      double o64[kMaxKeyBlock];                        // pass 2: column sums of the block's keys
       SelectSmem sel;
     } tail;
   };
@@ -101,9 +103,10 @@ struct UnitCursor {
   }
 };
 
-template <int PASS, bool EDGE>
+template <int PASS, bool EDGE, int KT>
 __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem& sm, int r, int c0, int N,
                                             int kblock, int slot) {
+  constexpr int KB = 256 * KT;                              // keys per work-group
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
   const int l32 = lane & 31, half = lane >> 5;
@@ -113,20 +116,35 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem& sm, i
   const int n_units = (rows_total + kUnit - 1) / kUnit;
   const int n_flat = a.Hkv * n_units;
   const unsigned magic = 0xFFFFFFFFu / (unsigned)n_eff;
-  const int key_base = kblock * kKeyBlock + wave * 32;     // first local key of this wave
+  const int key_base = kblock * KB + wave * 32 * KT;       // first local key of this wave
   const float c = a.c;
   const int rs0 = rowslot_base(c0, r, a.n_obs);
   const bool whole_heads = (n_eff % kUnit) == 0;           // a unit never straddles two query heads
 
-  // ---- key operands of one kv head: one 32-key tile, lane = (key l32, k-slice half).
-  // The next head's keys are fetched into kfn one phase before they are needed.
-  bf16x8 kf[8], kfn[8];
-  // keys past the end of the sequence re-read the last key (finite values): pass 1 masks
-  // them (such a block is always an edge block), pass 2 never emits their scores
-  const char* k_lane = a.k + (long long)(c0 + imin(key_base + l32, N - 1)) * a.k_stride_b + half * 16;
-  auto load_keys = [&](bf16x8 (&dst)[8], int g) {
+  // ---- key operands of one kv head: KT tiles of 32 keys, lane = (key l32, k-slice half).
+  // Keys past the end of the sequence re-read the last key (finite values): pass 1 masks
+  // them (such a block is always an edge block), pass 2 never emits their scores.
+  bf16x8 kf[KT][8];
+  const char* k_lane[KT];
 #pragma unroll
-    for (int kk = 0; kk < 8; ++kk) dst[kk] = as_bf16x8(*(const u32x4*)(k_lane + (long long)g * 256 + kk * 32));
+  for (int t = 0; t < KT; ++t)
+    k_lane[t] = a.k + (long long)(c0 + imin(key_base + 32 * t + l32, N - 1)) * a.k_stride_b + half * 16;
+  auto load_keys = [&](int g) {
+#pragma unroll
+    for (int t = 0; t < KT; ++t)
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk)
+        kf[t][kk] = as_bf16x8(*(const u32x4*)(k_lane[t] + (long long)g * 256 + kk * 32));
+  };
+  // pulls the two cache lines of every key row of head g towards the CU well before
+  // load_keys(g) needs them (the values are only summed so that the loads stay alive)
+  int touched = 0;
+  auto touch_keys = [&](int g) {
+#pragma unroll
+    for (int t = 0; t < KT; ++t) {
+      const char* row = k_lane[t] - half * 16 + (long long)g * 256;
+      touched += *(const int*)(row + half * 128);
+    }
   };
 
   // ---- staging of one unit of query rows: 2048 pieces of 16 bytes (128 rows x 16), 4 per
@@ -180,140 +198,162 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem& sm, i
     }
   };
 
-  double col64 = 0.0;   // pass 2: running column sum of this lane's key
+  double col64[KT];   // pass 2: running column sums of this lane's keys
+#pragma unroll
+  for (int t = 0; t < KT; ++t) col64[t] = 0.0;
 
-  // ---- one phase = one 32x32 tile: row tile rt of the staged unit against the wave's keys.
-  // A phase has a matrix half (8 MFMAs) and a vector half (softmax arithmetic on the 16
-  // results per lane).  In program order, two MFMAs of a phase are followed by the LDS reads
-  // that refill the two operand registers just consumed with the next phase's rows, and by a
-  // quarter of the vector half of the previous phase; scheduling barriers keep that order (and
-  // the register footprint) as written.  The matrix pipe works on the MFMAs while the wave
-  // issues the vector instructions behind them, and no LDS latency is exposed.
+  // ---- one phase = row tile rt of the staged unit against the wave's KT key tiles.
+  // A phase has a matrix half (8 MFMAs per key tile) and a vector half (softmax arithmetic on
+  // the 16 results per lane and tile).  In program order, the MFMAs of one k-step are followed
+  // by the LDS read that refills the operand register just consumed with the next phase's
+  // rows, and by an eighth of the vector half of the previous phase; scheduling barriers keep
+  // that order (and the register footprint) as written, so no LDS latency is exposed and a
+  // dependent MFMA is never the next instruction after its predecessor.
   u32x4 qv[8];                         // operand fragments: row tile of the phase being issued / the next one
-  auto load_rows_part = [&](int buf, int rt, int part) {
-    const unsigned char* qrow = &sm.q[buf][(rt * 32 + l32) * kQRow + half * 16];
-#pragma unroll
-    for (int kk = 2 * part; kk < 2 * part + 2; ++kk) qv[kk] = *(const u32x4*)(qrow + kk * 32);
+  auto load_rows_slice = [&](int buf, int rt, int kk) {
+    qv[kk] = *(const u32x4*)(&sm.q[buf][(rt * 32 + l32) * kQRow + half * 16 + kk * 32]);
   };
-  auto mfma_part = [&](f32x16& acc, int part) {
-    if (part == 0) {
+  auto mfma_slice = [&](f32x16 (&acc)[KT], int kk) {
 #pragma unroll
-      for (int e = 0; e < 16; ++e) acc[e] = 0.0f;
-    }
+    for (int t = 0; t < KT; ++t) {
+      if (kk == 0) {
 #pragma unroll
-    for (int kk = 2 * part; kk < 2 * part + 2; ++kk) {
+        for (int e = 0; e < 16; ++e) acc[t][e] = 0.0f;
+      }
       if (PASS == 1)   // S^T: rows of the result are keys, columns are query rows
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], as_bf16x8(qv[kk]), acc, 0, 0, 0);
+        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t][kk], as_bf16x8(qv[kk]), acc[t], 0, 0, 0);
       else             // S: rows are query rows, columns are keys
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(qv[kk]), kf[kk], acc, 0, 0, 0);
+        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(qv[kk]), kf[t][kk], acc[t], 0, 0, 0);
     }
   };
-  float p1_ref = 0.0f, p1_negref = 0.0f, p1_l0 = 0.0f, p1_l1 = 0.0f;   // pass 1 phase state
-  float p2_cs0 = 0.0f, p2_cs1 = 0.0f;                                    // pass 2 phase state
-  // vector quarter `part` of the phase (unit with table ring slots ring4 / ring3, row tile rt)
-  auto valu_part = [&](int ring4, int ring3, int rt, f32x16& acc, int part) {
+  // pass 1 phase state: partial maxima, reference, running sums, lane-half exchange
+  float p1_m0 = 0.0f, p1_m1 = 0.0f, p1_ref = 0.0f, p1_negref = 0.0f, p1_l0 = 0.0f, p1_l1 = 0.0f;
+  float p1_ref_o = 0.0f, p1_l_o = 0.0f;
+  float p2_cs[KT][2];                   // pass 2 phase state
+  // vector slice `sl` (0..7) of the phase (unit with table ring slots ring4 / ring3, row tile rt)
+  auto valu_slice = [&](int ring4, int ring3, int rt, f32x16 (&acc)[KT], int sl) {
     if (PASS == 1) {
-      // element e = key 8*(e/4) + 4*half + e%4 of the wave's tile, query row rt*32 + l32
-      if (part == 0) {
+      // element e of tile t = key 32*t + 8*(e/4) + 4*half + e%4 of the wave's keys, query row rt*32 + l32
+      if (sl == 0) {
         if (EDGE) {
           const int rp = sm.rowpos[ring4][rt * 32 + l32];
 #pragma unroll
-          for (int e = 0; e < 16; ++e)
-            if (key_base + 8 * (e >> 2) + 4 * half + (e & 3) > rp) acc[e] = -INFINITY;
-        }
-        float m0 = fmaxf(acc[0], acc[1]), m1 = fmaxf(acc[2], acc[3]);
+          for (int t = 0; t < KT; ++t)
 #pragma unroll
-        for (int e = 4; e < 16; e += 4) {
-          m0 = fmaxf(m0, fmaxf(acc[e], acc[e + 1]));
-          m1 = fmaxf(m1, fmaxf(acc[e + 2], acc[e + 3]));
+            for (int e = 0; e < 16; ++e)
+              if (key_base + 32 * t + 8 * (e >> 2) + 4 * half + (e & 3) > rp) acc[t][e] = -INFINITY;
         }
-        const float m = fmaxf(m0, m1);
+        p1_m0 = fmaxf(fmaxf(acc[0][0], acc[0][1]), fmaxf(acc[0][2], acc[0][3]));
+        p1_m1 = fmaxf(fmaxf(acc[0][4], acc[0][5]), fmaxf(acc[0][6], acc[0][7]));
+        if (KT == 2) {
+          p1_m0 = fmaxf(p1_m0, fmaxf(fmaxf(acc[KT - 1][0], acc[KT - 1][1]), fmaxf(acc[KT - 1][2], acc[KT - 1][3])));
+          p1_m1 = fmaxf(p1_m1, fmaxf(fmaxf(acc[KT - 1][4], acc[KT - 1][5]), fmaxf(acc[KT - 1][6], acc[KT - 1][7])));
+        }
+      } else if (sl == 1) {
+#pragma unroll
+        for (int t = 0; t < KT; ++t) {
+          p1_m0 = fmaxf(p1_m0, fmaxf(fmaxf(acc[t][8], acc[t][9]), fmaxf(acc[t][10], acc[t][11])));
+          p1_m1 = fmaxf(p1_m1, fmaxf(fmaxf(acc[t][12], acc[t][13]), fmaxf(acc[t][14], acc[t][15])));
+        }
+        const float m = fmaxf(p1_m0, p1_m1);
         p1_ref = m * c;                          // reference in log2 units
         p1_negref = (EDGE && m == -INFINITY) ? 0.0f : -p1_ref;
         p1_l0 = 0.0f;
         p1_l1 = 0.0f;
-      } else if (part < 3) {
+      } else if (sl < 6) {
+        const int e0 = 4 * (sl - 2);
 #pragma unroll
-        for (int e = 8 * (part - 1); e < 8 * part; e += 2) {
-          p1_l0 += exp2_hw(fmaf(acc[e], c, p1_negref));
-          p1_l1 += exp2_hw(fmaf(acc[e + 1], c, p1_negref));
+        for (int t = 0; t < KT; ++t) {
+          p1_l0 += exp2_hw(fmaf(acc[t][e0], c, p1_negref));
+          p1_l1 += exp2_hw(fmaf(acc[t][e0 + 1], c, p1_negref));
+          p1_l0 += exp2_hw(fmaf(acc[t][e0 + 2], c, p1_negref));
+          p1_l1 += exp2_hw(fmaf(acc[t][e0 + 3], c, p1_negref));
         }
+      } else if (sl == 6) {
+        // exchange with the other lane half (same row, the other keys of the tiles)
+        p1_l0 += p1_l1;                          // 0 when every key was masked (exp2(-inf))
+        p1_ref_o = __shfl_xor(p1_ref, 32);
+        p1_l_o = __shfl_xor(p1_l0, 32);
       } else {
-        // merge the two lane halves (same row, the tile's other 16 keys)
-        const float ref = p1_ref;
-        const float l = p1_l0 + p1_l1;           // 0 when every key was masked (exp2(-inf))
-        const float ref_o = __shfl_xor(ref, 32);
-        const float l_o = __shfl_xor(l, 32);
-        const float mm = fmaxf(ref, ref_o);
-        float s_a = l * exp2_hw(ref - mm);
-        float s_b = l_o * exp2_hw(ref_o - mm);
+        const float mm = fmaxf(p1_ref, p1_ref_o);
+        float s_a = p1_l0 * exp2_hw(p1_ref - mm);
+        float s_b = p1_l_o * exp2_hw(p1_ref_o - mm);
         if (EDGE) {
-          if (ref == -INFINITY) s_a = 0.0f;
-          if (ref_o == -INFINITY) s_b = 0.0f;
+          if (p1_ref == -INFINITY) s_a = 0.0f;
+          if (p1_ref_o == -INFINITY) s_b = 0.0f;
         }
         if (half == 0) sm.wstat[ring3][wave][rt * 32 + l32] = make_float2(mm, s_a + s_b);
       }
     } else {
-      // element e = query row rt*32 + 8*(e/4) + 4*half + e%4, key l32 of the wave's tile; part = e/4
-      if (part == 0) { p2_cs0 = 0.0f; p2_cs1 = 0.0f; }
-      const int row0 = rt * 32 + 8 * part + 4 * half;
-      const f32x4 cs01 = *(const f32x4*)(&sm.cst[ring4][row0]);       // rows row0, row0+1
-      const f32x4 cs23 = *(const f32x4*)(&sm.cst[ring4][row0 + 2]);   // rows row0+2, row0+3
-      const float negm[4] = {cs01[0], cs01[2], cs23[0], cs23[2]};
-      const float wr[4] = {cs01[1], cs01[3], cs23[1], cs23[3]};
-      float x[4];
+      // element e of tile t = query row rt*32 + 8*(e/4) + 4*half + e%4, key 32*t + l32;
+      // slice sl handles e = 2*sl, 2*sl + 1 (two consecutive rows: one 16-byte table read)
+      if (sl == 0) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        x[i] = fmaf(acc[part * 4 + i], c, negm[i]);
-        if (EDGE && key_base + l32 > sm.rowpos[ring4][row0 + i]) x[i] = -INFINITY;
+        for (int t = 0; t < KT; ++t) { p2_cs[t][0] = 0.0f; p2_cs[t][1] = 0.0f; }
       }
-      p2_cs0 = fmaf(exp2_hw(x[0]), wr[0], p2_cs0);
-      p2_cs1 = fmaf(exp2_hw(x[1]), wr[1], p2_cs1);
-      p2_cs0 = fmaf(exp2_hw(x[2]), wr[2], p2_cs0);
-      p2_cs1 = fmaf(exp2_hw(x[3]), wr[3], p2_cs1);
-      if (part == 3) col64 += (double)(p2_cs0 + p2_cs1);
+      const int row0 = rt * 32 + 8 * (sl >> 1) + 4 * half + 2 * (sl & 1);
+      const f32x4 cs = *(const f32x4*)(&sm.cst[ring4][row0]);   // (negref, w) of rows row0, row0+1
+      int rp0 = 0, rp1 = 0;
+      if (EDGE) { rp0 = sm.rowpos[ring4][row0]; rp1 = sm.rowpos[ring4][row0 + 1]; }
+#pragma unroll
+      for (int t = 0; t < KT; ++t) {
+        float x0 = fmaf(acc[t][2 * sl], c, cs[0]);
+        float x1 = fmaf(acc[t][2 * sl + 1], c, cs[2]);
+        if (EDGE) {
+          if (key_base + 32 * t + l32 > rp0) x0 = -INFINITY;
+          if (key_base + 32 * t + l32 > rp1) x1 = -INFINITY;
+        }
+        p2_cs[t][0] = fmaf(exp2_hw(x0), cs[1], p2_cs[t][0]);
+        p2_cs[t][1] = fmaf(exp2_hw(x1), cs[3], p2_cs[t][1]);
+      }
+      if (sl == 7) {
+#pragma unroll
+        for (int t = 0; t < KT; ++t) col64[t] += (double)(p2_cs[t][0] + p2_cs[t][1]);
+      }
     }
   };
   // keeps memory accesses (IR level) and all instructions (scheduler) on their side of this
-  // point; the running sums pass through the asm statement, so the arithmetic that feeds
+  // point; the running values pass through the asm statement, so the arithmetic that feeds
   // them cannot be sunk below it either
   auto pin_order = [&]() {
-    if (PASS == 1) asm volatile("" : "+v"(p1_l0), "+v"(p1_l1), "+v"(p1_negref) : : "memory");
-    else asm volatile("" : "+v"(p2_cs0), "+v"(p2_cs1) : : "memory");
+    if (PASS == 1)
+      asm volatile("" : "+v"(p1_l0), "+v"(p1_l1), "+v"(p1_negref), "+v"(p1_m0), "+v"(p1_m1) : : "memory");
+    else
+      asm volatile("" : "+v"(p2_cs[0][0]), "+v"(p2_cs[0][1]), "+v"(p2_cs[KT - 1][0]), "+v"(p2_cs[KT - 1][1]) : : "memory");
     __builtin_amdgcn_sched_barrier(0);
   };
   // matrix half of a phase into acc_m, refilling the operand registers from (buf_n, rt_n),
   // next to the vector half of the previous phase (acc_v; tables ring4_v / ring3_v, row tile rt_v)
-  auto overlapped = [&](f32x16& acc_m, int buf_n, int rt_n, bool refill, bool with_valu, int ring4_v,
-                        int ring3_v, int rt_v, f32x16& acc_v) {
+  auto overlapped = [&](f32x16 (&acc_m)[KT], int buf_n, int rt_n, bool refill, bool with_valu, int ring4_v,
+                        int ring3_v, int rt_v, f32x16 (&acc_v)[KT]) {
 #pragma unroll
-    for (int part = 0; part < 4; ++part) {
-      mfma_part(acc_m, part);
-      if (refill) load_rows_part(buf_n, rt_n, part);
-      if (with_valu) valu_part(ring4_v, ring3_v, rt_v, acc_v, part);
+    for (int sl = 0; sl < 8; ++sl) {
+      mfma_slice(acc_m, sl);
+      if (refill) load_rows_slice(buf_n, rt_n, sl);
+      if (with_valu) valu_slice(ring4_v, ring3_v, rt_v, acc_v, sl);
       pin_order();
     }
   };
-  // pass 1: merge the eight waves' statistics of the rows of unit `uc` (ring slot ring3) and
-  // write the key block's partial.  Wave w takes rows 16w..16w+15; four lanes share a row and
-  // take two waves' entries each.
+  // pass 1: merge the eight waves' statistics of the 128 rows of unit `uc` (ring slot ring3)
+  // and write the key block's partial.  One wave does it (the waves take turns), two rows per lane.
   auto merge_unit = [&](const UnitCursor& uc, int ring3) {
-    const int row = wave * 16 + (lane & 15), sub = lane >> 4;
-    const float2 s0 = sm.wstat[ring3][2 * sub][row], s1 = sm.wstat[ring3][2 * sub + 1][row];
-    float mm = fmaxf(s0.x, s1.x);
-    float l = (s0.x == -INFINITY ? 0.0f : s0.y * exp2_hw(s0.x - mm)) +
-              (s1.x == -INFINITY ? 0.0f : s1.y * exp2_hw(s1.x - mm));
 #pragma unroll
-    for (int sh = 16; sh <= 32; sh <<= 1) {
-      const float m_o = __shfl_xor(mm, sh);
-      const float l_o = __shfl_xor(l, sh);
-      const float m_n = fmaxf(mm, m_o);
-      l = (mm == -INFINITY ? 0.0f : l * exp2_hw(mm - m_n)) + (m_o == -INFINITY ? 0.0f : l_o * exp2_hw(m_o - m_n));
-      mm = m_n;
+    for (int rr = 0; rr < 2; ++rr) {
+      const int row = lane + 64 * rr;
+      float2 st[kSweepWaves];
+#pragma unroll
+      for (int w2 = 0; w2 < kSweepWaves; ++w2) st[w2] = sm.wstat[ring3][w2][row];
+      float mm = st[0].x;
+#pragma unroll
+      for (int w2 = 1; w2 < kSweepWaves; ++w2) mm = fmaxf(mm, st[w2].x);
+      float l = 0.0f;
+#pragma unroll
+      for (int w2 = 0; w2 < kSweepWaves; ++w2)
+        l += st[w2].x == -INFINITY ? 0.0f : st[w2].y * exp2_hw(st[w2].x - mm);
+      int hh, jj;
+      if (unit_row(uc, row, hh, jj))
+        a.stat_part[(size_t)slot * (a.Hq * a.n_obs) + (size_t)(uc.g * a.Gq + hh) * a.n_obs + jj] = make_float2(mm, l);
     }
-    int hh, jj;
-    if (sub == 0 && unit_row(uc, row, hh, jj))
-      a.stat_part[(size_t)slot * (a.Hq * a.n_obs) + (size_t)(uc.g * a.Gq + hh) * a.n_obs + jj] = make_float2(mm, l);
   };
 
   // ---- prologue: unit 0 staged and visible, unit 1 in flight, first rows in registers
@@ -323,14 +363,14 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem& sm, i
   fetch_unit(cur);
   stash_unit(0);
   stage_meta(cur, 0);
-  load_keys(kf, 0);
+  load_keys(0);
   __syncthreads();
   nxt.advance(n_units, n_eff);
   if (n_flat > 1) fetch_unit(nxt);
 #pragma unroll
-  for (int part = 0; part < 4; ++part) load_rows_part(0, 0, part);
+  for (int kk = 0; kk < 8; ++kk) load_rows_slice(0, 0, kk);
 
-  f32x16 accA, accB;
+  f32x16 accA[KT], accB[KT];
   for (int f = 0; f < n_flat; ++f) {
     const int buf = f & 1;
     const bool more = f + 1 < n_flat;
@@ -338,59 +378,62 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem& sm, i
     const int r4 = f & 3, r3 = f % 3;
     const int pr4 = (f + 3) & 3, pr3 = (f + 2) % 3;         // ring slots of unit f-1
 
-    if (head_ends) load_keys(kfn, cur.g + 1);   // needed four phases from now
+    if (head_ends) touch_keys(cur.g + 1);   // needed four phases from now
     // phase 0 of unit f next to the last vector half of unit f-1
     overlapped(accA, buf, 1, true, f > 0, pr4, pr3, 3, accB);
     overlapped(accB, buf, 2, true, true, r4, r3, 0, accA);
     overlapped(accA, buf, 3, true, true, r4, r3, 1, accB);
     if (more) { stash_unit(buf ^ 1); stage_meta(nxt, (f + 1) & 3); }
     __syncthreads();     // unit f+1 is visible; every read of unit f's rows has completed
-    if (PASS == 1 && f > 0) merge_unit(prev, pr3);
+    if (PASS == 1 && f > 0 && wave == (f & (kSweepWaves - 1))) merge_unit(prev, pr3);
+    const int next_g = cur.g + 1;
     prev = cur;
     cur = nxt;
     if (f + 2 < n_flat) { nxt.advance(n_units, n_eff); fetch_unit(nxt); }
     // last phase of unit f; the operand registers are refilled with the first rows of unit f+1
     overlapped(accB, buf ^ 1, 0, more, true, r4, r3, 2, accA);
-    if (head_ends) {
-#pragma unroll
-      for (int kk = 0; kk < 8; ++kk) kf[kk] = kfn[kk];
-    }
+    if (head_ends) load_keys(next_g);       // this head's last MFMA has been issued
   }
   // the last vector half, then (pass 1) the statistics of the last unit
 #pragma unroll
-  for (int part = 0; part < 4; ++part) { valu_part((n_flat + 3) & 3, (n_flat + 2) % 3, 3, accB, part); pin_order(); }
+  for (int sl = 0; sl < 8; ++sl) { valu_slice((n_flat + 3) & 3, (n_flat + 2) % 3, 3, accB, sl); pin_order(); }
   __syncthreads();
-  if (PASS == 1) merge_unit(prev, (n_flat + 2) % 3);
+  if (PASS == 1 && wave == 0) merge_unit(prev, (n_flat + 2) % 3);
 
   if (PASS == 2) {
     // (a barrier has passed since the last read of the staged rows: their space is reused)
-    // the two lane halves hold the same key over different rows: add them (fixed order)
-    const double other = __shfl_xor(col64, 32);
-    if (half == 0) sm.tail.o64[wave * 32 + l32] = col64 + other;
+    // the two lane halves hold the same keys over different rows: add them (fixed order)
+#pragma unroll
+    for (int t = 0; t < KT; ++t) {
+      const double other = __shfl_xor(col64[t], 32);
+      if (half == 0) sm.tail.o64[wave * 32 * KT + 32 * t + l32] = col64[t] + other;
+    }
   }
+  if (touched == 0x7fffffff) sm.rowpos[0][0] = touched;   // never true for real data; keeps the touch loads
 }
 
-template <int PASS>
+template <int PASS, int KT>
 __global__ __launch_bounds__(kSweepThreads) void k_sweep(SweepArgs a) {
+  constexpr int KB = 256 * KT;
   __shared__ SweepSmem sm;
   const int slot = blockIdx.x;
-  const int r = locate_slot(a.cu, a.R, kKeyBlock, slot);
+  const int r = locate_slot(a.cu, a.R, KB, slot);
   const int c0 = a.cu[r];
   const int N = a.cu[r + 1] - c0;
-  const int kblock = slot - slot_base(c0, r, kKeyBlock);
-  if (kblock * kKeyBlock >= N) return;
+  const int kblock = slot - slot_base(c0, r, KB);
+  if (kblock * KB >= N) return;
   const int n_eff = imin(a.n_obs, N);
   // causal masking and the ragged end only matter where keys reach the query window
-  const bool edge = (kblock + 1) * kKeyBlock - 1 > N - n_eff;
-  if (edge) sweep_block<PASS, true>(a, sm, r, c0, N, kblock, slot);
-  else sweep_block<PASS, false>(a, sm, r, c0, N, kblock, slot);
+  const bool edge = (kblock + 1) * KB - 1 > N - n_eff;
+  if (edge) sweep_block<PASS, true, KT>(a, sm, r, c0, N, kblock, slot);
+  else sweep_block<PASS, false, KT>(a, sm, r, c0, N, kblock, slot);
 
   if (PASS == 2) {
     __syncthreads();
     const int tid = threadIdx.x;
     float sc = 0.0f;
-    if (tid < kKeyBlock) {
-      const int key = kblock * kKeyBlock + tid;
+    if (tid < KB) {
+      const int key = kblock * KB + tid;
       if (key < N) {
         const double o = sm.tail.o64[tid] / (double)(n_eff * a.Hq);
         sc = o < 0x1p-64 ? 0.0f : (float)o;
@@ -402,9 +445,9 @@ __global__ __launch_bounds__(kSweepThreads) void k_sweep(SweepArgs a) {
     __syncthreads();
     // the block-local top-k and the gather, one selection block after the other
     const int G = a.sel.G;
-    const int nb = imin(kKeyBlock / G, ceil_div(N - kblock * kKeyBlock, G));
+    const int nb = imin(KB / G, ceil_div(N - kblock * KB, G));
     for (int b = 0; b < nb; ++b)
-      select_block(a.sel, sm.tail.sel, r, c0, N, kblock * (kKeyBlock / G) + b, &sm.tail.sel.score[b * G]);
+      select_block(a.sel, sm.tail.sel, r, c0, N, kblock * (KB / G) + b, &sm.tail.sel.score[b * G]);
   }
 }
 
@@ -415,7 +458,7 @@ __global__ __launch_bounds__(kSweepThreads) void k_sweep(SweepArgs a) {
 __global__ __launch_bounds__(1024) void k_combine(const int32_t* __restrict__ cu,
                                                   const float2* __restrict__ stat_part,
                                                   float2* __restrict__ stat_fin, int R, int Hq,
-                                                  int n_obs, int row_slots) {
+                                                  int n_obs, int row_slots, int key_block) {
   __shared__ float sh_m[32][33];
   __shared__ double sh_l[32][33];
   const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
@@ -432,8 +475,8 @@ __global__ __launch_bounds__(1024) void k_combine(const int32_t* __restrict__ cu
     const int jj = u - rowslot_base(c0, r, n_obs);
     live = jj < imin(n_obs, N);
     if (live) {
-      n_blocks = ceil_div(N, kKeyBlock);
-      p = stat_part + (size_t)slot_base(c0, r, kKeyBlock) * stride + (size_t)h * n_obs + jj;
+      n_blocks = ceil_div(N, key_block);
+      p = stat_part + (size_t)slot_base(c0, r, key_block) * stride + (size_t)h * n_obs + jj;
     }
   }
   float m = -INFINITY;
@@ -502,7 +545,10 @@ hipError_t launch_row_stats(const Problem& pb, const void* q, const void* k, con
                             void* workspace, hipStream_t s) {
   if (pb.T == 0) return hipSuccess;
   const SweepArgs a = make_sweep_args(pb, q, k, cu, workspace);
-  hipLaunchKernelGGL(k_sweep<1>, dim3((unsigned)pb.key_block_slots), dim3(kSweepThreads), 0, s, a);
+  if (pb.key_block == 512)
+    hipLaunchKernelGGL((k_sweep<1, 2>), dim3((unsigned)pb.key_block_slots), dim3(kSweepThreads), 0, s, a);
+  else
+    hipLaunchKernelGGL((k_sweep<1, 1>), dim3((unsigned)pb.key_block_slots), dim3(kSweepThreads), 0, s, a);
   return hipGetLastError();
 }
 
@@ -510,7 +556,7 @@ hipError_t launch_merge_stats(const Problem& pb, const int32_t* cu, void* worksp
   if (pb.T == 0) return hipSuccess;
   const SweepArgs a = make_sweep_args(pb, nullptr, nullptr, cu, workspace);
   hipLaunchKernelGGL(k_combine, dim3((unsigned)((pb.row_slots + 31) / 32), (unsigned)pb.Hq), dim3(1024),
-                     0, s, cu, a.stat_part, a.stat_fin, pb.R, pb.Hq, pb.n_obs, pb.row_slots);
+                     0, s, cu, a.stat_part, a.stat_fin, pb.R, pb.Hq, pb.n_obs, pb.row_slots, pb.key_block);
   return hipGetLastError();
 }
 
@@ -521,7 +567,10 @@ hipError_t launch_column_sums(const Problem& pb, const void* q, const void* k, c
   SweepArgs a = make_sweep_args(pb, q, k, cu, workspace);
   a.scores_out = scores_out;
   if (sel != nullptr) { a.sel = *sel; a.do_select = 1; }
-  hipLaunchKernelGGL(k_sweep<2>, dim3((unsigned)pb.key_block_slots), dim3(kSweepThreads), 0, s, a);
+  if (pb.key_block == 512)
+    hipLaunchKernelGGL((k_sweep<2, 2>), dim3((unsigned)pb.key_block_slots), dim3(kSweepThreads), 0, s, a);
+  else
+    hipLaunchKernelGGL((k_sweep<2, 1>), dim3((unsigned)pb.key_block_slots), dim3(kSweepThreads), 0, s, a);
   return hipGetLastError();
 }
 
