@@ -24,6 +24,11 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 
+# HBM bytes per launch (reads + writes) from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE, each scaled by
+# what the same counter reads for an identity gather of known size in the same run; the summaries
+# with the commands are under profiles/.  Keyed by (workload, kernel); absent = not measured.
+MEASURED_TRAFFIC_BYTES = {}
+
 
 def algorithmic_bytes(w, total_kept):
     """Bytes the method must move: K once, a score per token, the kept rows in and out,
@@ -52,6 +57,10 @@ def main():
     ap.add_argument("--config", type=int, default=4, help="workload 1..5 (default: the 128k-token one)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-phases", action="store_true", help="skip the per-kernel timing loop")
+    ap.add_argument("--no-entry-points", action="store_true", help="skip timing the stand-alone entry points")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch one identity gather of the whole hidden tensor (a plain copy of known "
+                         "size): the reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (no sharding or collectives are built)",
@@ -143,17 +152,67 @@ def main():
                 ent.update(gbs=round(moved / (us * 1e-6) / 1e9, 1),
                            frac_hbm=round(moved / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4))
             kernels[name] = ent
+        # the dominant kernel against the roofline it gets closest to (its algorithmic bytes
+        # against HBM peak, or its product flops against the dense bf16 MFMA peak)
         dom = max(kernels, key=lambda n: kernels[n]["avg_us"])
-        if kernels[dom].get("bound") == "mfma":
-            roofline = {"kernel": dom, "bound": "mfma", "achieved": kernels[dom]["tflops"],
-                        "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": kernels[dom]["frac_mfma"],
-                        "traffic": None}
+        ent = kernels[dom]
+        traffic = MEASURED_TRAFFIC_BYTES.get((w.name, dom))
+        if ent.get("frac_mfma", 0.0) > ent.get("frac_hbm", 0.0):
+            roofline = {"kernel": dom, "bound": "mfma", "achieved": ent["tflops"],
+                        "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ent["frac_mfma"],
+                        "traffic": traffic}
         else:
-            roofline = {"kernel": dom, "bound": "hbm", "achieved": kernels[dom].get("gbs"),
-                        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": kernels[dom].get("frac_hbm"),
-                        "traffic": None}
+            roofline = {"kernel": dom, "bound": "hbm", "achieved": ent.get("gbs"),
+                        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ent.get("frac_hbm"),
+                        "traffic": traffic}
     else:
         roofline = None
+
+    # ---- the stand-alone entry points and a plain device copy of the gather's byte count
+    entry_points = {}
+    if not args.no_entry_points:
+        def timed(fn, reps=10):
+            for _ in range(2):
+                fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(reps):
+                fn()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps * 1e3
+
+        gather_bytes = 2 * total_kept * w.hidden_dim * 2
+        full = torch.empty_like(hidden)
+        src = torch.empty(gather_bytes // 2, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        t_us = {
+            "score": timed(lambda: up.uniprefill_score(p, q, k, cu, cu_host, scores, workspace, ws_bytes, stream=stream)),
+            "select": timed(lambda: up.uniprefill_select(p, scores, cu, cu_host, ratio, ratio_host, kept_idx, new_cu,
+                                                        stream=stream)),
+            "compact": timed(lambda: up.uniprefill_compact(p, hidden, pos, kept_idx, total_kept, hidden_out, pos_out,
+                                                          stream=stream)),
+            "scatter": timed(lambda: up.uniprefill_scatter(p, hidden_out, kept_idx, total_kept, full, stream=stream)),
+            "device_copy_same_bytes": timed(lambda: dst.copy_(src)),
+        }
+        for name, us in t_us.items():
+            ent = {"avg_us": round(us, 2)}
+            if name in ("compact", "scatter", "device_copy_same_bytes"):
+                ent["gbs"] = round(gather_bytes / (us * 1e-6) / 1e9, 1)
+                ent["frac_hbm"] = round(gather_bytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)
+            entry_points[name] = ent
+        del full, src, dst
+
+    if args.calibrate_copy:
+        ident = torch.arange(w.total_tokens, dtype=torch.int32, device="cuda")
+        full = torch.empty_like(hidden)
+        fpos = torch.empty_like(pos)
+        up.uniprefill_compact(p, hidden, pos, ident, w.total_tokens, full, fpos, stream=stream)
+        torch.cuda.synchronize()
+        print(f"[bench] calibration copy: k_rows gathers {w.total_tokens} rows of {w.hidden_dim * 2} bytes "
+              f"(reads and writes {w.total_tokens * w.hidden_dim * 2} bytes each)", file=sys.stderr, flush=True)
+        del ident, full, fpos
 
     # ---- the oracle on this machine's host cores (a reported baseline, not a target)
     cpu_baseline = None
@@ -198,6 +257,7 @@ def main():
         "product_flops_per_pass": int(flops),
         "roofline": roofline,
         "kernels": kernels,
+        "entry_points": entry_points,
         "cpu_baseline": cpu_baseline,
         "oracle_parity": parity,
     }
