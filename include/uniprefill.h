@@ -3,9 +3,10 @@
  * for AMD MI355X (gfx950).
  *
  * The operator works on a packed continuous-batching batch: R sequences stored
- * back to back ("variable-length packed token representation indexed by
- * cu_seqlens", section "Fused Kernel and vLLM Integration", kernel-design
- * paragraph).  Sequence r owns packed rows [cu_seqlens[r], cu_seqlens[r+1]).
+ * back to back with no padding and addressed through cu_seqlens, the token
+ * layout the kernel-design paragraph of section "Fused Kernel and vLLM
+ * Integration" prescribes.  Sequence r owns packed rows
+ * [cu_seqlens[r], cu_seqlens[r+1]).
  *
  * Conventions shared by every entry point
  *   - "dev"  pointers are device (HBM) addresses, "host" pointers are host
@@ -143,8 +144,9 @@ int uniprefill_scatter(const up_params* p, const void* hidden_compact,
                        void* hidden_full_inout, void* stream);
 
 /* The whole path in one call: score -> select -> compact, enqueued back to back
- * on `stream` with no host synchronisation ("sequence of fused kernels ...
- * without CPU round-trips").  Outputs as in the single entries; scores_out may
+ * on `stream` with no host synchronisation (the kernel-design paragraph asks for
+ * a chain of kernels on the packed layout with no round trip through the host).
+ * Outputs as in the single entries; scores_out may
  * be NULL.  hidden_out needs room for the plan's total_kept rows. */
 int uniprefill_fused(const up_params* p, const void* q, const void* k, const void* hidden,
                      const int32_t* pos, const int32_t* cu_seqlens_dev,
