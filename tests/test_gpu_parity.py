@@ -185,6 +185,42 @@ def test_scores_match_oracle(case):
             assert abs(float(got[a:e].astype(np.float64).sum()) - 1.0) < 1e-4
 
 
+@pytest.mark.parametrize("n_obs,Hq,Hkv", [(128, 8, 2), (200, 6, 2), (32, 4, 4)])
+def test_scores_many_short_sequences_use_the_wide_work_groups(n_obs, Hq, Hkv):
+    """230+ sequences push the launch geometry to 512-key work-groups (16 waves) although every
+    sequence is short: lengths around the tile, unit and key-block boundaries, empty ones included."""
+    special = [0, 1, 2, 31, 32, 33, 63, 127, 128, 129, 255, 256, 257, 383, 511, 512, 513, 640, 1023, 1024, 1025, 1500]
+    rng = np.random.default_rng(5)
+    lengths = special + [int(x) for x in rng.integers(1, 700, size=230 - len(special))]
+    rng.shuffle(lengths)
+    _say("score many sequences", n_obs, Hq, Hkv, "T", sum(lengths))
+    w = workloads.make_custom(name="many", seed=21, lengths=lengths, keep_ratio=[0.4] * len(lengths),
+                              hidden_dim=8, num_q_heads=Hq, num_kv_heads=Hkv, block_size=64, n_obs=n_obs)
+    assert w.total_tokens // 512 + w.num_seqs >= 224      # the geometry this test is about
+    b = DeviceBatch(w)
+    b.score()
+    got = b.results()["scores"]
+    want = oracle.quantise_scores(oracle.importance_scores(
+        _q_f32(w), workloads.bf16_bits_to_f32(w.k), w.cu_seqlens, n_obs=w.n_obs))
+    ok, worst = _score_close(got, want)
+    _say("  worst relative score error", worst)
+    assert ok
+    assert b.canaries_intact()
+
+
+def test_fused_many_short_sequences_bit_exact():
+    rng = np.random.default_rng(6)
+    lengths = [0, 1, 33, 127, 129, 300, 511, 512, 513, 1025, 2049] + [int(x) for x in rng.integers(1, 900, size=225)]
+    _say("fused many sequences T", sum(lengths))
+    ratios = [float(x) for x in rng.uniform(0.2, 0.9, size=len(lengths))]
+    w = workloads.make_custom(name="manyf", seed=22, lengths=lengths, keep_ratio=ratios, hidden_dim=64,
+                              num_q_heads=8, num_kv_heads=2, block_size=128, n_obs=128)
+    assert w.total_tokens // 512 + w.num_seqs >= 224
+    b = DeviceBatch(w)
+    b.fused()
+    _assert_fused_exact(w, b, oracle_run(w))
+
+
 def test_scores_custom_scale_and_heavy_tail():
     _say("score heavy tail")
     w = workloads.make_custom(name="ht", seed=3, lengths=[4000], keep_ratio=[0.25], hidden_dim=8,
