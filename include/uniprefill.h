@@ -82,7 +82,7 @@ typedef struct {
   int64_t k_row_stride;      /* elements between consecutive tokens of k */
   int64_t hidden_row_stride; /* elements between consecutive rows of hidden */
   float softmax_scale;       /* 0 => 1/sqrt(head_dim)  (Eq. 2) */
-  int32_t qk_dtype;          /* up_dtype of q and k */
+  int32_t qk_dtype;          /* up_dtype of q and k (UP_F32: fp32 products, a slower correctness path) */
   int32_t hidden_dtype;      /* up_dtype of hidden (bit-copied, never computed on) */
 } up_params;
 

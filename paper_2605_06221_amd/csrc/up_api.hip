@@ -34,7 +34,7 @@ int check_params(const up_params* p, bool need_qk, bool need_hidden, Problem* pb
     if (p->num_q_heads < 1 || p->num_kv_heads < 1) return UP_ERR_SHAPE;
     if (p->num_q_heads % p->num_kv_heads != 0) return UP_ERR_UNSUPPORTED;
     if (p->num_q_heads / p->num_kv_heads > 64) return UP_ERR_UNSUPPORTED;
-    if (p->qk_dtype != UP_BF16) return UP_ERR_UNSUPPORTED;   // fp32 q/k: not built yet
+    if (p->qk_dtype != UP_BF16 && p->qk_dtype != UP_F32) return UP_ERR_UNSUPPORTED;
     if (!(p->softmax_scale >= 0.0f) || isinf(p->softmax_scale)) return UP_ERR_RANGE;
     if (p->q_row_stride < (int64_t)p->num_q_heads * p->head_dim ||
         p->k_row_stride < (int64_t)p->num_kv_heads * p->head_dim)
@@ -56,7 +56,8 @@ int check_params(const up_params* p, bool need_qk, bool need_hidden, Problem* pb
   }
   // keys per work-group of the scoring sweeps: 512 (two key tiles per wave) halves the per-key
   // overheads; 256 gives twice as many work-groups when the batch cannot fill the 256 CUs otherwise
-  q.key_block = (q.T / 512 + q.R >= 224) ? 512 : 256;
+  // (fp32 operands need twice the registers and LDS: 256-key work-groups only)
+  q.key_block = (q.T / 512 + q.R >= 224 && !q.qk_is_f32) ? 512 : 256;
   q.key_block_slots = q.T / q.key_block + q.R;
   const long long rs = (long long)q.R * q.n_obs;
   q.row_slots = rs < q.T ? (int)rs : q.T;

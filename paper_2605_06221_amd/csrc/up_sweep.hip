@@ -41,7 +41,10 @@
 namespace up {
 
 constexpr int kUnit = 128;           // query rows per LDS staging unit (4 MFMA row tiles)
-constexpr int kQRow = 272;           // LDS bytes per query row: 256 + 16 pad (conflict-free b128 reads)
+// bytes of one head row (128 elements) in global memory, and in LDS with a 16-byte pad that makes
+// the 128-bit operand reads conflict-free
+template <bool F32> constexpr int kHeadRowBytes = F32 ? 512 : 256;
+template <bool F32> constexpr int kQRow = kHeadRowBytes<F32> + 16;
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
@@ -81,10 +84,10 @@ __device__ __forceinline__ void divmod(unsigned x, unsigned d, unsigned magic, i
 // LDS of one work-group of NW waves.  The staged query rows are dead once the sweep is over,
 // so the selection state reuses their space.  The per-unit tables are double-buffered like
 // the rows: the tables of unit f+1 are written while unit f is being read.
-template <int NW>
+template <int NW, bool F32>
 struct SweepSmem {
   union {
-    __align__(16) unsigned char q[2][kUnit * kQRow];   // staged query rows (bf16), double-buffered
+    __align__(16) unsigned char q[2][kUnit * kQRow<F32>];   // staged query rows, double-buffered
     struct {
       double o64[32 * NW];                             // pass 2: column sums of the block's keys
       SelectSmem sel;
@@ -110,13 +113,16 @@ struct UnitCursor {
   }
 };
 
-template <int PASS, bool EDGE, int NW>
-__device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem<NW>& sm, int r, int c0, int N,
+template <int PASS, bool EDGE, int NW, bool F32>
+__device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem<NW, F32>& sm, int r, int c0, int N,
                                             int kblock, int slot) {
   constexpr int KB = 32 * NW;                               // keys per work-group
   constexpr int THREADS = 64 * NW;
-  constexpr int PIECES = 2048 / THREADS;                    // 16-byte pieces of a unit per thread
-  constexpr int ROWSTEP = THREADS / 16;                     // rows between a thread's pieces
+  constexpr int SRCB = kHeadRowBytes<F32>;                  // bytes of a head row in global memory
+  constexpr int ROWB = kQRow<F32>;                          // ... and in LDS
+  constexpr int PPR = SRCB / 16;                            // 16-byte pieces per row
+  constexpr int PIECES = kUnit * PPR / THREADS;             // pieces of a unit per thread
+  constexpr int ROWSTEP = THREADS / PPR;                    // rows between a thread's pieces
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
   const int l32 = lane & 31, half = lane >> 5;
@@ -131,32 +137,38 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem<NW>& s
   const int rs0 = rowslot_base(c0, r, a.n_obs);
   const bool whole_heads = (n_eff % kUnit) == 0;           // a unit never straddles two query heads
 
-  // ---- key operands of one kv head: 32 keys, lane = (key l32, k-slice half).
+  // ---- key operands of one kv head: 32 keys, lane = (key l32, half of the contraction).
+  // bf16: MFMA step kk contracts elements 16*kk .. 16*kk+15, lane half h supplies 8*h .. 8*h+7 of
+  // them (one 128-bit register group per step).  fp32 (v_mfma_f32_32x32x2_f32, two elements per
+  // step): step t contracts elements t and 64+t, so that a lane half owns 64 consecutive
+  // elements and loads them with 128-bit accesses; queries use the same order.
   // Keys past the end of the sequence re-read the last key (finite values): pass 1 masks
   // them (such a block is always an edge block), pass 2 never emits their scores.
-  bf16x8 kf[8];
-  const char* k_lane = a.k + (long long)(c0 + imin(key_base + l32, N - 1)) * a.k_stride_b + half * 16;
+  constexpr int KREG = F32 ? 16 : 8;
+  u32x4 kf[KREG];
+  const char* k_lane = a.k + (long long)(c0 + imin(key_base + l32, N - 1)) * a.k_stride_b + half * (F32 ? 256 : 16);
   auto load_keys = [&](int g) {
 #pragma unroll
-    for (int kk = 0; kk < 8; ++kk) kf[kk] = as_bf16x8(*(const u32x4*)(k_lane + (long long)g * 256 + kk * 32));
+    for (int kk = 0; kk < KREG; ++kk)
+      kf[kk] = *(const u32x4*)(k_lane + (long long)g * SRCB + kk * (F32 ? 16 : 32));
   };
-  // pulls the two cache lines of the key row of head g towards the CU well before
+  // pulls the two cache lines of the (bf16) key row of head g towards the CU well before
   // load_keys(g) needs them (the values are only summed so that the loads stay alive)
   int touched = 0, touch_val = 0;
   auto touch_keys = [&](int g) {
-    touch_val = *(const int*)(k_lane - half * 16 + (long long)g * 256 + half * 128);
+    if (!F32) touch_val = *(const int*)(k_lane - half * 16 + (long long)g * 256 + half * 128);
   };
 
   // ---- staging of one unit of query rows: 2048 pieces of 16 bytes (128 rows x 16), PIECES per
   // thread: column t%16 of rows t/16 + ROWSTEP*i.  Fetched into registers at the start of the
   // previous unit's matrix work, written to LDS just before the barrier that ends it.
-  const int my_row = tid >> 4;
-  const char* q_seq = a.q + (long long)(c0 + first_q) * a.q_stride_b + (tid & 15) * 16;
+  const int my_row = tid / PPR, my_col = tid % PPR;
+  const char* q_seq = a.q + (long long)(c0 + first_q) * a.q_stride_b + my_col * 16;
   const long long my_row_off = (long long)my_row * a.q_stride_b;
   u32x4 pre_q[PIECES];
   auto fetch_unit = [&](const UnitCursor& uc) {
     if (whole_heads) {
-      const char* base = q_seq + (long long)(uc.g * a.Gq + uc.hh) * 256 + (long long)uc.jj0 * a.q_stride_b + my_row_off;
+      const char* base = q_seq + (long long)(uc.g * a.Gq + uc.hh) * SRCB + (long long)uc.jj0 * a.q_stride_b + my_row_off;
 #pragma unroll
       for (int i = 0; i < PIECES; ++i) pre_q[i] = *(const u32x4*)(base + (long long)(i * ROWSTEP) * a.q_stride_b);
     } else {
@@ -167,14 +179,14 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem<NW>& s
         const int rho = imin(uc.u * kUnit + my_row + i * ROWSTEP, rows_total - 1);
         int hh, jj;
         divmod((unsigned)rho, (unsigned)n_eff, magic, hh, jj);
-        pre_q[i] = *(const u32x4*)(q_seq + (long long)jj * a.q_stride_b + (long long)(uc.g * a.Gq + hh) * 256);
+        pre_q[i] = *(const u32x4*)(q_seq + (long long)jj * a.q_stride_b + (long long)(uc.g * a.Gq + hh) * SRCB);
       }
     }
   };
   auto stash_unit = [&](int buf) {
 #pragma unroll
     for (int i = 0; i < PIECES; ++i)
-      *(u32x4*)(&sm.q[buf][(my_row + i * ROWSTEP) * kQRow + (tid & 15) * 16]) = pre_q[i];
+      *(u32x4*)(&sm.q[buf][(my_row + i * ROWSTEP) * ROWB + my_col * 16]) = pre_q[i];
   };
   // row of a unit -> (query head inside the group, window row), or false if there is no such row
   auto unit_row = [&](const UnitCursor& uc, int row, int& hh, int& jj) -> bool {
@@ -212,19 +224,33 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem<NW>& s
   // MASK: some (row, key) pairs of the tile are not visible (key after the row, or past the end)
   auto tile = [&](auto mask_tag, int buf, int tb, int rt) {
     constexpr bool MASK = decltype(mask_tag)::value;
-    u32x4 qv[8];
+    u32x4 qv[KREG];
 #pragma unroll
-    for (int kk = 0; kk < 8; ++kk)
-      qv[kk] = *(const u32x4*)(&sm.q[buf][(rt * 32 + l32) * kQRow + half * 16 + kk * 32]);
+    for (int kk = 0; kk < KREG; ++kk)
+      qv[kk] = *(const u32x4*)(&sm.q[buf][(rt * 32 + l32) * ROWB + half * (F32 ? 256 : 16) + kk * (F32 ? 16 : 32)]);
     f32x16 acc;
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[e] = 0.0f;
+    // pass 1 computes S^T (rows of the result are keys, columns are query rows), pass 2 S
+    if (F32) {
+      auto step = [&](unsigned kbits, unsigned qbits) {
+        const float kx = __builtin_bit_cast(float, kbits), qx = __builtin_bit_cast(float, qbits);
+        acc = PASS == 1 ? __builtin_amdgcn_mfma_f32_32x32x2f32(kx, qx, acc, 0, 0, 0)
+                        : __builtin_amdgcn_mfma_f32_32x32x2f32(qx, kx, acc, 0, 0, 0);
+      };
 #pragma unroll
-    for (int kk = 0; kk < 8; ++kk) {
-      if (PASS == 1)   // S^T: rows of the result are keys, columns are query rows
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], as_bf16x8(qv[kk]), acc, 0, 0, 0);
-      else             // S: rows are query rows, columns are keys
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(qv[kk]), kf[kk], acc, 0, 0, 0);
+      for (int kk = 0; kk < 16; ++kk) {
+        const u32x4 k4 = kf[kk], q4 = qv[kk];
+        step(k4.x, q4.x);
+        step(k4.y, q4.y);
+        step(k4.z, q4.z);
+        step(k4.w, q4.w);
+      }
+    } else {
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk)
+        acc = PASS == 1 ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kf[kk]), as_bf16x8(qv[kk]), acc, 0, 0, 0)
+                        : __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(qv[kk]), as_bf16x8(kf[kk]), acc, 0, 0, 0);
     }
     if (PASS == 1) {
       // element e = key 8*(e/4) + 4*half + e%4 of the wave's keys, query row rt*32 + l32
@@ -370,10 +396,10 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem<NW>& s
   if (touched == 0x7fffffff) sm.rowpos[0][0] = touched;   // never true for real data; keeps the touch loads
 }
 
-template <int PASS, int NW>
+template <int PASS, int NW, bool F32>
 __global__ __launch_bounds__(64 * NW) void k_sweep(SweepArgs a) {
   constexpr int KB = 32 * NW;
-  __shared__ SweepSmem<NW> sm;
+  __shared__ SweepSmem<NW, F32> sm;
   const int slot = blockIdx.x;
   const int r = locate_slot(a.cu, a.R, KB, slot);
   const int c0 = a.cu[r];
@@ -383,8 +409,8 @@ __global__ __launch_bounds__(64 * NW) void k_sweep(SweepArgs a) {
   const int n_eff = imin(a.n_obs, N);
   // causal masking and the ragged end only matter where keys reach the query window
   const bool edge = (kblock + 1) * KB - 1 > N - n_eff;
-  if (edge) sweep_block<PASS, true, NW>(a, sm, r, c0, N, kblock, slot);
-  else sweep_block<PASS, false, NW>(a, sm, r, c0, N, kblock, slot);
+  if (edge) sweep_block<PASS, true, NW, F32>(a, sm, r, c0, N, kblock, slot);
+  else sweep_block<PASS, false, NW, F32>(a, sm, r, c0, N, kblock, slot);
 
   if (PASS == 2) {
     __syncthreads();
@@ -491,7 +517,8 @@ static SweepArgs make_sweep_args(const Problem& pb, const void* q, const void* k
   a.stat_part = (float2*)(ws + w.stat_part_off);
   a.stat_fin = (float2*)(ws + w.stat_fin_off);
   a.scores_out = nullptr;
-  a.q_stride_b = pb.q_stride * 2; a.k_stride_b = pb.k_stride * 2;
+  const int eb = pb.qk_is_f32 ? 4 : 2;
+  a.q_stride_b = pb.q_stride * eb; a.k_stride_b = pb.k_stride * eb;
   a.c = pb.scale * 1.44269504088896340736f;
   a.R = pb.R; a.T = pb.T; a.Hq = pb.Hq; a.Hkv = pb.Hkv; a.Gq = pb.Gq; a.n_obs = pb.n_obs;
   a.row_slots = pb.row_slots;
@@ -503,10 +530,12 @@ hipError_t launch_row_stats(const Problem& pb, const void* q, const void* k, con
                             void* workspace, hipStream_t s) {
   if (pb.T == 0) return hipSuccess;
   const SweepArgs a = make_sweep_args(pb, q, k, cu, workspace);
-  if (pb.key_block == 512)
-    hipLaunchKernelGGL((k_sweep<1, 16>), dim3((unsigned)pb.key_block_slots), dim3(1024), 0, s, a);
+  if (pb.qk_is_f32)
+    hipLaunchKernelGGL((k_sweep<1, 8, true>), dim3((unsigned)pb.key_block_slots), dim3(512), 0, s, a);
+  else if (pb.key_block == 512)
+    hipLaunchKernelGGL((k_sweep<1, 16, false>), dim3((unsigned)pb.key_block_slots), dim3(1024), 0, s, a);
   else
-    hipLaunchKernelGGL((k_sweep<1, 8>), dim3((unsigned)pb.key_block_slots), dim3(512), 0, s, a);
+    hipLaunchKernelGGL((k_sweep<1, 8, false>), dim3((unsigned)pb.key_block_slots), dim3(512), 0, s, a);
   return hipGetLastError();
 }
 
@@ -525,10 +554,12 @@ hipError_t launch_column_sums(const Problem& pb, const void* q, const void* k, c
   SweepArgs a = make_sweep_args(pb, q, k, cu, workspace);
   a.scores_out = scores_out;
   if (sel != nullptr) { a.sel = *sel; a.do_select = 1; }
-  if (pb.key_block == 512)
-    hipLaunchKernelGGL((k_sweep<2, 16>), dim3((unsigned)pb.key_block_slots), dim3(1024), 0, s, a);
+  if (pb.qk_is_f32)
+    hipLaunchKernelGGL((k_sweep<2, 8, true>), dim3((unsigned)pb.key_block_slots), dim3(512), 0, s, a);
+  else if (pb.key_block == 512)
+    hipLaunchKernelGGL((k_sweep<2, 16, false>), dim3((unsigned)pb.key_block_slots), dim3(1024), 0, s, a);
   else
-    hipLaunchKernelGGL((k_sweep<2, 8>), dim3((unsigned)pb.key_block_slots), dim3(512), 0, s, a);
+    hipLaunchKernelGGL((k_sweep<2, 8, false>), dim3((unsigned)pb.key_block_slots), dim3(512), 0, s, a);
   return hipGetLastError();
 }
 

@@ -21,18 +21,25 @@ def host_bits(t: torch.Tensor) -> np.ndarray:
 class DeviceBatch:
     """A workload resident in HBM plus output buffers sized by uniprefill_plan."""
 
-    def __init__(self, w, softmax_scale: float = 0.0, canary: bool = True):
+    def __init__(self, w, softmax_scale: float = 0.0, canary: bool = True, qk_f32=None):
+        """qk_f32 = (q, k) float32 arrays of the workload's shapes: score from those instead of
+        the workload's bf16 tensors (the fp32 operand path)."""
         self.w = w
         self.cu_host = np.ascontiguousarray(w.cu_seqlens, dtype=np.int32)
         self.ratio_host = np.ascontiguousarray(w.keep_ratio, dtype=np.float32)
         self.p = up.make_params(
             num_seqs=w.num_seqs, total_tokens=w.total_tokens, block_size=w.block_size, n_obs=w.n_obs,
             n_sink=w.n_sink, num_q_heads=w.num_q_heads, num_kv_heads=w.num_kv_heads, head_dim=w.head_dim,
-            hidden_dim=w.hidden_dim, softmax_scale=softmax_scale)
+            hidden_dim=w.hidden_dim, softmax_scale=softmax_scale,
+            qk_dtype=up.UP_BF16 if qk_f32 is None else up.UP_F32)
         _, self.new_cu_plan, self.total_kept, self.ws_bytes = up.uniprefill_plan(self.p, self.cu_host, self.ratio_host)
         T, d = w.total_tokens, w.hidden_dim
-        self.q = dev_bf16(w.q)
-        self.k = dev_bf16(w.k)
+        if qk_f32 is None:
+            self.q = dev_bf16(w.q)
+            self.k = dev_bf16(w.k)
+        else:
+            self.q = torch.from_numpy(np.ascontiguousarray(qk_f32[0], dtype=np.float32)).cuda()
+            self.k = torch.from_numpy(np.ascontiguousarray(qk_f32[1], dtype=np.float32)).cuda()
         self.hidden = dev_bf16(w.hidden)
         self.pos = torch.from_numpy(w.pos).cuda()
         self.cu = torch.from_numpy(self.cu_host).cuda()

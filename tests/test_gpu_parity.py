@@ -221,6 +221,63 @@ def test_fused_many_short_sequences_bit_exact():
     _assert_fused_exact(w, b, oracle_run(w))
 
 
+# fp32 operands: tolerance stated for this build; what the arithmetic gives is derived in the design notes
+SCORE_RTOL_F32 = 1e-5
+
+
+def _f32_operands(w, seed):
+    """float32 q and k that are not bf16-representable; q rows outside the window are NaN."""
+    rng = np.random.default_rng(seed)
+    k = rng.standard_normal(w.k.shape, dtype=np.float32)
+    q = np.full(w.q.shape, np.nan, dtype=np.float32)
+    for r in range(w.num_seqs):
+        a, e = int(w.cu_seqlens[r]), int(w.cu_seqlens[r + 1])
+        n_eff = min(w.n_obs, e - a)
+        q[e - n_eff:e] = rng.standard_normal((n_eff,) + w.q.shape[1:], dtype=np.float32)
+    return q, k
+
+
+@pytest.mark.parametrize("case", [
+    dict(lengths=[700], Hq=8, Hkv=8, n_obs=128),
+    dict(lengths=[1, 5, 130, 0, 257, 1000, 64], Hq=8, Hkv=2, n_obs=128),
+    dict(lengths=[2100, 300], Hq=12, Hkv=4, n_obs=200),
+])
+def test_scores_from_fp32_operands_match_oracle(case):
+    _say("score fp32", case)
+    w = workloads.make_custom(name="f32", seed=12, lengths=case["lengths"], keep_ratio=[0.5] * len(case["lengths"]),
+                              hidden_dim=8, num_q_heads=case["Hq"], num_kv_heads=case["Hkv"], block_size=64,
+                              n_obs=case["n_obs"])
+    q32, k32 = _f32_operands(w, 31)
+    b = DeviceBatch(w, qk_f32=(q32, k32))
+    b.score()
+    got = b.results()["scores"].astype(np.float64)
+    want = oracle.quantise_scores(oracle.importance_scores(q32, k32, w.cu_seqlens, n_obs=w.n_obs)).astype(np.float64)
+    err = np.abs(got - want)
+    worst = (err / np.maximum(want, 1e-300))[want > 0].max()
+    _say("  worst relative score error", worst)
+    assert (err <= SCORE_RTOL_F32 * want + SCORE_ATOL).all()
+    assert b.canaries_intact()
+
+
+def test_fused_from_fp32_operands_bit_exact():
+    _say("fused fp32")
+    w = workloads.make_custom(name="f32f", seed=13, lengths=[1500, 40, 777], keep_ratio=[0.3, 0.5, 0.7],
+                              hidden_dim=64, num_q_heads=8, num_kv_heads=2, block_size=64, n_obs=128)
+    q32, k32 = _f32_operands(w, 32)
+    b = DeviceBatch(w, qk_f32=(q32, k32))
+    b.fused()
+    ref = oracle.sparsify(q32, k32, w.hidden, w.pos, w.cu_seqlens, w.keep_ratio, block_size=w.block_size,
+                          n_obs=w.n_obs, n_sink=w.n_sink)
+    res = b.results()
+    err = np.abs(res["scores"].astype(np.float64) - ref["scores"].astype(np.float64))
+    assert (err <= SCORE_RTOL_F32 * ref["scores"] + SCORE_ATOL).all()
+    np.testing.assert_array_equal(res["new_cu_seqlens"], ref["new_cu_seqlens"])
+    np.testing.assert_array_equal(res["kept_idx"], ref["kept_idx"])
+    np.testing.assert_array_equal(res["pos_out"], ref["pos_out"])
+    np.testing.assert_array_equal(res["hidden_out"], ref["hidden_out"])
+    assert b.canaries_intact()
+
+
 def test_scores_custom_scale_and_heavy_tail():
     _say("score heavy tail")
     w = workloads.make_custom(name="ht", seed=3, lengths=[4000], keep_ratio=[0.25], hidden_dim=8,

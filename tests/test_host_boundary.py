@@ -88,7 +88,9 @@ def test_plan_rejects_bad_arguments():
     assert plan(_params(n_sink=-1)) == up.UP_ERR_RANGE
     assert plan(_params(head_dim=64)) == up.UP_ERR_UNSUPPORTED
     assert plan(_params(num_q_heads=6, num_kv_heads=4)) == up.UP_ERR_UNSUPPORTED
-    assert plan(_params(qk_dtype=up.UP_F32)) == up.UP_ERR_UNSUPPORTED
+    assert plan(_params(qk_dtype=up.UP_F32)) == up.UP_OK
+    assert plan(_params(qk_dtype=7)) == up.UP_ERR_UNSUPPORTED
+    assert plan(_params(qk_dtype=up.UP_F32, q_row_stride=8 * 128 + 2)) == up.UP_ERR_ALIGN
     assert plan(_params(softmax_scale=-1.0)) == up.UP_ERR_RANGE
     assert plan(_params(softmax_scale=float("nan"))) == up.UP_ERR_RANGE
     assert plan(_params(q_row_stride=8 * 128 + 4)) == up.UP_ERR_ALIGN
