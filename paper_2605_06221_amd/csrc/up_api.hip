@@ -54,11 +54,10 @@ int check_params(const up_params* p, bool need_qk, bool need_hidden, Problem* pb
         (p->hidden_row_stride * q.hidden_elem_bytes) % 16 != 0)
       return UP_ERR_ALIGN;
   }
-  // keys per work-group of the scoring sweeps: 512 (two key tiles per wave) halves the per-key
-  // overheads; 256 gives twice as many work-groups when the batch cannot fill the 256 CUs otherwise
-  // (fp32 operands need twice the registers and LDS: 256-key work-groups only)
-  q.key_block = (q.T / 512 + q.R >= 224 && !q.qk_is_f32) ? 512 : 256;
+  // launch geometry of the scoring sweeps: provisional until choose_geometry has seen the lengths
+  q.key_block = q.qk_is_f32 ? 256 : 512;
   q.key_block_slots = q.T / q.key_block + q.R;
+  q.split = 1;
   const long long rs = (long long)q.R * q.n_obs;
   q.row_slots = rs < q.T ? (int)rs : q.T;
   *pb = q;
@@ -79,6 +78,36 @@ int check_ratio(const up_params* p, const float* ratio_host) {
   for (int r = 0; r < p->num_seqs; ++r)
     if (!(ratio_host[r] > 0.0f && ratio_host[r] <= 1.0f)) return UP_ERR_RANGE;
   return UP_OK;
+}
+
+// Launch geometry of the scoring sweeps from the sequence lengths.  A work-group owns one key
+// block (512 keys with 16 waves; 256 with 8 waves for fp32 operands, or when even a full head
+// split leaves most of the chip idle) and `split` work-groups share a key block, each sweeping
+// Hkv / split kv heads.  The split grows (powers of two dividing Hkv) until the launch has about
+// one work-group per CU, and a launch of a few uneven rounds is split once more so that its last
+// round is fuller.
+void choose_geometry(Problem* pb, const int32_t* cu) {
+  constexpr int kCUs = 256, kEnough = 224;
+  auto blocks = [&](int kb) {
+    long long n = 0;
+    for (int r = 0; r < pb->R; ++r) n += (cu[r + 1] - cu[r] + kb - 1) / kb;
+    return n;
+  };
+  int kb = pb->qk_is_f32 ? 256 : 512;
+  long long nb = blocks(kb);
+  int split = 1;
+  auto can_double = [&]() { return 2 * split <= pb->Hkv && pb->Hkv % (2 * split) == 0; };
+  while (nb * split < kEnough && can_double()) split *= 2;
+  if (nb * split < kEnough && kb == 512) {
+    kb = 256;
+    nb = blocks(kb);
+  }
+  const long long wgs = nb * split;
+  const long long rounds = (wgs + kCUs - 1) / kCUs;
+  if (rounds >= 2 && rounds <= 4 && wgs * 100 < rounds * kCUs * 85 && can_double()) split *= 2;
+  pb->key_block = kb;
+  pb->key_block_slots = pb->T / kb + pb->R;
+  pb->split = split;
 }
 
 long long host_total_kept(const Problem& pb, const int32_t* cu, const float* ratio,
@@ -107,6 +136,7 @@ int uniprefill_plan(const up_params* p, const int32_t* cu_seqlens_host, const fl
   if ((st = check_ratio(p, keep_ratio_host)) != UP_OK) return st;
   const long long total = host_total_kept(pb, cu_seqlens_host, keep_ratio_host, new_cu_seqlens_host);
   if (total_kept) *total_kept = total;
+  if (want_ws) choose_geometry(&pb, cu_seqlens_host);
   if (want_ws) *workspace_bytes = workspace_layout(pb).total;
   return UP_OK;
 }
@@ -120,6 +150,7 @@ int uniprefill_score(const up_params* p, const void* q, const void* k, const int
   if (!q || !k || !cu_seqlens_dev || !scores_out) return UP_ERR_NULL;
   if ((st = check_cu(p, cu_seqlens_host)) != UP_OK) return st;
   if (!aligned16(q) || !aligned16(k)) return UP_ERR_ALIGN;
+  choose_geometry(&pb, cu_seqlens_host);
   if (workspace == nullptr || workspace_bytes < workspace_layout(pb).total) return UP_ERR_WORKSPACE;
   if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return UP_ERR_ALIGN;
   hipStream_t s = (hipStream_t)stream;
@@ -197,6 +228,7 @@ int uniprefill_fused_phases(const up_params* p, const void* q, const void* k, co
   if ((st = check_ratio(p, keep_ratio_host)) != UP_OK) return st;
   if (!aligned16(q) || !aligned16(k) || !aligned16(hidden) || !aligned16(hidden_out))
     return UP_ERR_ALIGN;
+  choose_geometry(&pb, cu_seqlens_host);
   const Workspace w = workspace_layout(pb);
   if (workspace == nullptr || workspace_bytes < w.total) return UP_ERR_WORKSPACE;
   if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return UP_ERR_ALIGN;

@@ -20,13 +20,14 @@ struct Problem {
   int qk_is_f32;
   float scale;                // softmax scale (resolved, > 0)
   int key_block;              // keys per work-group of the scoring sweeps: 256 or 512
-  int key_block_slots;        // T / key_block + R: work-groups of the scoring sweeps
+  int key_block_slots;        // T / key_block + R: key blocks of all sequences (an upper bound)
+  int split;                  // work-groups per key block: each sweeps Hkv / split kv heads
   int row_slots;              // min(T, R * n_obs): window rows of all sequences
 };
 
 // Workspace carve-up (byte offsets, each 256-aligned).
 struct Workspace {
-  size_t stat_part_off, stat_fin_off, total;
+  size_t stat_part_off, stat_fin_off, o_part_off, total;
 };
 Workspace workspace_layout(const Problem& pb);
 

@@ -55,9 +55,11 @@ struct SweepArgs {
   float2* stat_part;   // [key_block_slots][Hq * n_obs]  (reference in log2 units, sum)
   float2* stat_fin;    // [Hq][row_slots]                 (negative reference, 1/sum)
   float* scores_out;   // pass 2: optional
+  double* o_part;      // pass 2, split > 1: [key_block_slots][split][keys per block] partial column sums
   long long q_stride_b, k_stride_b;   // bytes between tokens
   float c;             // scale * log2(e)
   int R, T, Hq, Hkv, Gq, n_obs, row_slots;
+  int split;           // work-groups per key block; each sweeps Hkv / split kv heads
   int do_select;       // pass 2: run the block-local top-k (+ gather if sel.hidden != nullptr)
   SelectArgs sel;
 };
@@ -115,7 +117,7 @@ struct UnitCursor {
 
 template <int PASS, bool EDGE, int NW, bool F32>
 __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem<NW, F32>& sm, int r, int c0, int N,
-                                            int kblock, int slot) {
+                                            int kblock, int slot, int g0, int n_heads) {
   constexpr int KB = 32 * NW;                               // keys per work-group
   constexpr int THREADS = 64 * NW;
   constexpr int SRCB = kHeadRowBytes<F32>;                  // bytes of a head row in global memory
@@ -130,7 +132,7 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem<NW, F3
   const int first_q = N - n_eff;
   const int rows_total = n_eff * a.Gq;
   const int n_units = (rows_total + kUnit - 1) / kUnit;
-  const int n_flat = a.Hkv * n_units;
+  const int n_flat = n_heads * n_units;            // this work-group sweeps kv heads g0 .. g0 + n_heads - 1
   const unsigned magic = 0xFFFFFFFFu / (unsigned)n_eff;
   const int key_base = kblock * KB + wave * 32;            // first local key of this wave
   const float c = a.c;
@@ -330,11 +332,11 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem<NW, F3
   };
 
   // ---- prologue: unit 0 staged and visible
-  UnitCursor cur{0, 0, 0, 0};      // unit being processed
+  UnitCursor cur{g0, 0, 0, 0};     // unit being processed
   UnitCursor nxt = cur;            // unit being staged
   fetch_unit(cur);
   fetch_meta(cur);
-  load_keys(0);
+  load_keys(g0);
   stash_unit(0);
   stash_meta(0);
   __syncthreads();
@@ -400,7 +402,7 @@ template <int PASS, int NW, bool F32>
 __global__ __launch_bounds__(64 * NW) void k_sweep(SweepArgs a) {
   constexpr int KB = 32 * NW;
   __shared__ SweepSmem<NW, F32> sm;
-  const int slot = blockIdx.x;
+  const int slot = blockIdx.x / a.split, part = blockIdx.x % a.split;
   const int r = locate_slot(a.cu, a.R, KB, slot);
   const int c0 = a.cu[r];
   const int N = a.cu[r + 1] - c0;
@@ -409,12 +411,19 @@ __global__ __launch_bounds__(64 * NW) void k_sweep(SweepArgs a) {
   const int n_eff = imin(a.n_obs, N);
   // causal masking and the ragged end only matter where keys reach the query window
   const bool edge = (kblock + 1) * KB - 1 > N - n_eff;
-  if (edge) sweep_block<PASS, true, NW, F32>(a, sm, r, c0, N, kblock, slot);
-  else sweep_block<PASS, false, NW, F32>(a, sm, r, c0, N, kblock, slot);
+  const int n_heads = a.Hkv / a.split;
+  if (edge) sweep_block<PASS, true, NW, F32>(a, sm, r, c0, N, kblock, slot, part * n_heads, n_heads);
+  else sweep_block<PASS, false, NW, F32>(a, sm, r, c0, N, kblock, slot, part * n_heads, n_heads);
 
   if (PASS == 2) {
     __syncthreads();
     const int tid = threadIdx.x;
+    if (a.split > 1) {
+      // the key block's heads are shared by `split` work-groups: each leaves its partial sums in
+      // the workspace and k_finish adds them up (in a fixed order) after this kernel has ended
+      if (tid < KB) a.o_part[((size_t)slot * a.split + part) * KB + tid] = sm.tail.o64[tid];
+      return;
+    }
     float sc = 0.0f;
     if (tid < KB) {
       const int key = kblock * KB + tid;
@@ -433,6 +442,39 @@ __global__ __launch_bounds__(64 * NW) void k_sweep(SweepArgs a) {
     for (int b = 0; b < nb; ++b)
       select_block(a.sel, sm.tail.sel, r, c0, N, kblock * (KB / G) + b, &sm.tail.sel.score[b * G]);
   }
+}
+
+// When the kv heads of a key block were shared by several work-groups (split > 1): one
+// work-group per selection block adds the parts' column sums in a fixed order, forms the
+// scores (mean, floor) and runs the block-local top-k and the gather.
+__global__ __launch_bounds__(256) void k_finish(SweepArgs a, int key_block) {
+  __shared__ SelectSmem sm;
+  const int G = a.sel.G;
+  const int slot = blockIdx.x;
+  const int r = locate_slot(a.cu, a.R, G, slot);
+  const int c0 = a.cu[r];
+  const int N = a.cu[r + 1] - c0;
+  const int g = slot - slot_base(c0, r, G);
+  if (g * G >= N) return;   // slack slot (also every slot of an empty sequence)
+  const int tid = threadIdx.x;
+  const int key = g * G + tid;
+  if (tid < G) {
+    float sc = 0.0f;
+    if (key < N) {
+      const int kblock = key / key_block;
+      const double* part0 = a.o_part + (size_t)(slot_base(c0, r, key_block) + kblock) * a.split * key_block +
+                            (key - kblock * key_block);
+      double sum = 0.0;
+      for (int pp = 0; pp < a.split; ++pp) sum += part0[(size_t)pp * key_block];
+      const double o = sum / (double)(imin(a.n_obs, N) * a.Hq);
+      sc = o < 0x1p-64 ? 0.0f : (float)o;
+      if (a.scores_out != nullptr) a.scores_out[c0 + key] = sc;
+    }
+    sm.score[tid] = sc;
+  }
+  if (!a.do_select) return;
+  __syncthreads();
+  select_block(a.sel, sm, r, c0, N, g, sm.score);
 }
 
 // Merge the per-key-block softmax statistics of every (sequence, window row, head):
@@ -504,6 +546,8 @@ Workspace workspace_layout(const Problem& pb) {
   off = al(off + (size_t)pb.key_block_slots * pb.Hq * pb.n_obs * sizeof(float2));
   w.stat_fin_off = off;
   off = al(off + (size_t)pb.row_slots * pb.Hq * sizeof(float2));
+  w.o_part_off = off;
+  if (pb.split > 1) off = al(off + (size_t)pb.key_block_slots * pb.split * pb.key_block * sizeof(double));
   w.total = off;
   return w;
 }
@@ -517,6 +561,8 @@ static SweepArgs make_sweep_args(const Problem& pb, const void* q, const void* k
   a.stat_part = (float2*)(ws + w.stat_part_off);
   a.stat_fin = (float2*)(ws + w.stat_fin_off);
   a.scores_out = nullptr;
+  a.o_part = (double*)(ws + w.o_part_off);
+  a.split = pb.split;
   const int eb = pb.qk_is_f32 ? 4 : 2;
   a.q_stride_b = pb.q_stride * eb; a.k_stride_b = pb.k_stride * eb;
   a.c = pb.scale * 1.44269504088896340736f;
@@ -531,11 +577,11 @@ hipError_t launch_row_stats(const Problem& pb, const void* q, const void* k, con
   if (pb.T == 0) return hipSuccess;
   const SweepArgs a = make_sweep_args(pb, q, k, cu, workspace);
   if (pb.qk_is_f32)
-    hipLaunchKernelGGL((k_sweep<1, 8, true>), dim3((unsigned)pb.key_block_slots), dim3(512), 0, s, a);
+    hipLaunchKernelGGL((k_sweep<1, 8, true>), dim3((unsigned)(pb.key_block_slots * pb.split)), dim3(512), 0, s, a);
   else if (pb.key_block == 512)
-    hipLaunchKernelGGL((k_sweep<1, 16, false>), dim3((unsigned)pb.key_block_slots), dim3(1024), 0, s, a);
+    hipLaunchKernelGGL((k_sweep<1, 16, false>), dim3((unsigned)(pb.key_block_slots * pb.split)), dim3(1024), 0, s, a);
   else
-    hipLaunchKernelGGL((k_sweep<1, 8, false>), dim3((unsigned)pb.key_block_slots), dim3(512), 0, s, a);
+    hipLaunchKernelGGL((k_sweep<1, 8, false>), dim3((unsigned)(pb.key_block_slots * pb.split)), dim3(512), 0, s, a);
   return hipGetLastError();
 }
 
@@ -554,12 +600,15 @@ hipError_t launch_column_sums(const Problem& pb, const void* q, const void* k, c
   SweepArgs a = make_sweep_args(pb, q, k, cu, workspace);
   a.scores_out = scores_out;
   if (sel != nullptr) { a.sel = *sel; a.do_select = 1; }
+  else { a.sel.G = pb.G; }
   if (pb.qk_is_f32)
-    hipLaunchKernelGGL((k_sweep<2, 8, true>), dim3((unsigned)pb.key_block_slots), dim3(512), 0, s, a);
+    hipLaunchKernelGGL((k_sweep<2, 8, true>), dim3((unsigned)(pb.key_block_slots * pb.split)), dim3(512), 0, s, a);
   else if (pb.key_block == 512)
-    hipLaunchKernelGGL((k_sweep<2, 16, false>), dim3((unsigned)pb.key_block_slots), dim3(1024), 0, s, a);
+    hipLaunchKernelGGL((k_sweep<2, 16, false>), dim3((unsigned)(pb.key_block_slots * pb.split)), dim3(1024), 0, s, a);
   else
-    hipLaunchKernelGGL((k_sweep<2, 8, false>), dim3((unsigned)pb.key_block_slots), dim3(512), 0, s, a);
+    hipLaunchKernelGGL((k_sweep<2, 8, false>), dim3((unsigned)(pb.key_block_slots * pb.split)), dim3(512), 0, s, a);
+  if (pb.split > 1)
+    hipLaunchKernelGGL(k_finish, dim3((unsigned)(pb.T / pb.G + pb.R)), dim3(256), 0, s, a, pb.key_block);
   return hipGetLastError();
 }
 
