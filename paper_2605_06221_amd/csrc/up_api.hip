@@ -58,6 +58,7 @@ int check_params(const up_params* p, bool need_qk, bool need_hidden, Problem* pb
   q.key_block = q.qk_is_f32 ? 256 : 512;
   q.key_block_slots = q.T / q.key_block + q.R;
   q.split = 1;
+  q.max_key_blocks = q.key_block_slots;
   const long long rs = (long long)q.R * q.n_obs;
   q.row_slots = rs < q.T ? (int)rs : q.T;
   *pb = q;
@@ -108,6 +109,9 @@ void choose_geometry(Problem* pb, const int32_t* cu) {
   pb->key_block = kb;
   pb->key_block_slots = pb->T / kb + pb->R;
   pb->split = split;
+  int longest = 0;
+  for (int r = 0; r < pb->R; ++r) longest = cu[r + 1] - cu[r] > longest ? cu[r + 1] - cu[r] : longest;
+  pb->max_key_blocks = (longest + kb - 1) / kb;
 }
 
 long long host_total_kept(const Problem& pb, const int32_t* cu, const float* ratio,

@@ -22,6 +22,7 @@ struct Problem {
   int key_block;              // keys per work-group of the scoring sweeps: 256 or 512
   int key_block_slots;        // T / key_block + R: key blocks of all sequences (an upper bound)
   int split;                  // work-groups per key block: each sweeps Hkv / split kv heads
+  int max_key_blocks;         // key blocks of the longest sequence
   int row_slots;              // min(T, R * n_obs): window rows of all sequences
 };
 

@@ -479,14 +479,18 @@ __global__ __launch_bounds__(256) void k_finish(SweepArgs a, int key_block) {
 
 // Merge the per-key-block softmax statistics of every (sequence, window row, head):
 // final reference = max of the block references, sum rescaled to it.  A work-group
-// handles 32 consecutive window rows of one head (coalesced along the rows); the 32
-// threads that share a row each take 16 key blocks per round, all loads in flight.
-__global__ __launch_bounds__(1024) void k_combine(const int32_t* __restrict__ cu,
-                                                  const float2* __restrict__ stat_part,
-                                                  float2* __restrict__ stat_fin, int R, int Hq,
-                                                  int n_obs, int row_slots, int key_block) {
-  __shared__ float sh_m[32][33];
-  __shared__ double sh_l[32][33];
+// handles 32 consecutive window rows of one head (coalesced along the rows); the LPR
+// threads that share a row each take 16 key blocks per round, all loads in flight
+// (LPR = 32 for long sequences, 8 when no sequence has more than 128 key blocks).
+// Row slots are laid out with slack between sequences; a work-group without a live row
+// ends at once.
+template <int LPR>
+__global__ __launch_bounds__(32 * LPR) void k_combine(const int32_t* __restrict__ cu,
+                                                      const float2* __restrict__ stat_part,
+                                                      float2* __restrict__ stat_fin, int R, int Hq,
+                                                      int n_obs, int row_slots, int key_block) {
+  __shared__ float sh_m[LPR][33];
+  __shared__ double sh_l[LPR][33];
   const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
   const int u = blockIdx.x * 32 + tx;
   const int h = blockIdx.y;
@@ -505,9 +509,10 @@ __global__ __launch_bounds__(1024) void k_combine(const int32_t* __restrict__ cu
       p = stat_part + (size_t)slot_base(c0, r, key_block) * stride + (size_t)h * n_obs + jj;
     }
   }
+  if (__syncthreads_or(live) == 0) return;
   float m = -INFINITY;
   double L = 0.0;
-  for (int b0 = ty * 16; b0 < n_blocks; b0 += 512) {
+  for (int b0 = ty * 16; b0 < n_blocks; b0 += 16 * LPR) {
     float2 v[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i)
@@ -530,9 +535,9 @@ __global__ __launch_bounds__(1024) void k_combine(const int32_t* __restrict__ cu
   __syncthreads();
   if (ty == 0 && live) {
     float mm = -INFINITY;
-    for (int i = 0; i < 32; ++i) mm = fmaxf(mm, sh_m[i][tx]);
+    for (int i = 0; i < LPR; ++i) mm = fmaxf(mm, sh_m[i][tx]);
     double tot = 0.0;
-    for (int i = 0; i < 32; ++i)
+    for (int i = 0; i < LPR; ++i)
       if (sh_m[i][tx] != -INFINITY) tot += sh_l[i][tx] * exp2((double)sh_m[i][tx] - (double)mm);
     stat_fin[(size_t)h * row_slots + u] = make_float2(-mm, (float)(1.0 / tot));
   }
@@ -588,8 +593,13 @@ hipError_t launch_row_stats(const Problem& pb, const void* q, const void* k, con
 hipError_t launch_merge_stats(const Problem& pb, const int32_t* cu, void* workspace, hipStream_t s) {
   if (pb.T == 0) return hipSuccess;
   const SweepArgs a = make_sweep_args(pb, nullptr, nullptr, cu, workspace);
-  hipLaunchKernelGGL(k_combine, dim3((unsigned)((pb.row_slots + 31) / 32), (unsigned)pb.Hq), dim3(1024),
-                     0, s, cu, a.stat_part, a.stat_fin, pb.R, pb.Hq, pb.n_obs, pb.row_slots, pb.key_block);
+  const dim3 grid((unsigned)((pb.row_slots + 31) / 32), (unsigned)pb.Hq);
+  if (pb.max_key_blocks > 128)
+    hipLaunchKernelGGL(k_combine<32>, grid, dim3(1024), 0, s, cu, a.stat_part, a.stat_fin, pb.R, pb.Hq,
+                       pb.n_obs, pb.row_slots, pb.key_block);
+  else
+    hipLaunchKernelGGL(k_combine<8>, grid, dim3(256), 0, s, cu, a.stat_part, a.stat_fin, pb.R, pb.Hq,
+                       pb.n_obs, pb.row_slots, pb.key_block);
   return hipGetLastError();
 }
 
