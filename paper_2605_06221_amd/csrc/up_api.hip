@@ -160,7 +160,7 @@ int uniprefill_score(const up_params* p, const void* q, const void* k, const int
   hipStream_t s = (hipStream_t)stream;
   if (launch_row_stats(pb, q, k, cu_seqlens_dev, workspace, s) != hipSuccess) return UP_ERR_HIP;
   if (launch_merge_stats(pb, cu_seqlens_dev, workspace, s) != hipSuccess) return UP_ERR_HIP;
-  if (launch_column_sums(pb, q, k, cu_seqlens_dev, workspace, scores_out, nullptr, s) != hipSuccess)
+  if (launch_column_sums(pb, q, k, cu_seqlens_dev, workspace, scores_out, nullptr, 0, s) != hipSuccess)
     return UP_ERR_HIP;
   return UP_OK;
 }
@@ -251,7 +251,8 @@ int uniprefill_fused_phases(const up_params* p, const void* q, const void* k, co
     const SelectArgs sa = make_select_args(pb, nullptr, cu_seqlens_dev, keep_ratio_dev,
                                            new_cu_seqlens_dev, kept_idx, hidden, pos, hidden_out,
                                            pos_out);
-    if (launch_column_sums(pb, q, k, cu_seqlens_dev, workspace, scores_out, &sa, s) != hipSuccess)
+    const long long total_kept = host_total_kept(pb, cu_seqlens_host, keep_ratio_host, nullptr);
+    if (launch_column_sums(pb, q, k, cu_seqlens_dev, workspace, scores_out, &sa, total_kept, s) != hipSuccess)
       return UP_ERR_HIP;
   }
   return UP_OK;

@@ -55,7 +55,10 @@ hipError_t launch_row_stats(const Problem& pb, const void* q, const void* k, con
 hipError_t launch_merge_stats(const Problem& pb, const int32_t* cu, void* workspace, hipStream_t s);
 // pass 2: normalised weights summed per token; optional scores_out; sel != nullptr runs the
 // block-local top-k (and the gather when sel->hidden is set) in the same kernel
+// (total_kept: rows the selection keeps, from the closed form; used when the gather runs as a
+// launch of its own)
 hipError_t launch_column_sums(const Problem& pb, const void* q, const void* k, const int32_t* cu,
-                              void* workspace, float* scores_out, const SelectArgs* sel, hipStream_t s);
+                              void* workspace, float* scores_out, const SelectArgs* sel,
+                              long long total_kept, hipStream_t s);
 
 }  // namespace up

@@ -446,7 +446,8 @@ __global__ __launch_bounds__(64 * NW) void k_sweep(SweepArgs a) {
 
 // When the kv heads of a key block were shared by several work-groups (split > 1): one
 // work-group per selection block adds the parts' column sums in a fixed order, forms the
-// scores (mean, floor) and runs the block-local top-k and the gather.
+// scores (mean, floor) and runs the block-local top-k; the gather follows as a launch of
+// its own (one wave per kept row fills the chip, four waves per block would not).
 __global__ __launch_bounds__(256) void k_finish(SweepArgs a, int key_block) {
   __shared__ SelectSmem sm;
   const int G = a.sel.G;
@@ -605,12 +606,14 @@ hipError_t launch_merge_stats(const Problem& pb, const int32_t* cu, void* worksp
 
 hipError_t launch_column_sums(const Problem& pb, const void* q, const void* k, const int32_t* cu,
                               void* workspace, float* scores_out, const SelectArgs* sel,
-                              hipStream_t s) {
+                              long long total_kept, hipStream_t s) {
   if (pb.T == 0) return hipSuccess;
   SweepArgs a = make_sweep_args(pb, q, k, cu, workspace);
   a.scores_out = scores_out;
   if (sel != nullptr) { a.sel = *sel; a.do_select = 1; }
   else { a.sel.G = pb.G; }
+  const bool gather_apart = pb.split > 1 && sel != nullptr && sel->hidden != nullptr;
+  if (gather_apart) a.sel.hidden = nullptr;     // k_finish selects only
   if (pb.qk_is_f32)
     hipLaunchKernelGGL((k_sweep<2, 8, true>), dim3((unsigned)(pb.key_block_slots * pb.split)), dim3(512), 0, s, a);
   else if (pb.key_block == 512)
@@ -619,7 +622,10 @@ hipError_t launch_column_sums(const Problem& pb, const void* q, const void* k, c
     hipLaunchKernelGGL((k_sweep<2, 8, false>), dim3((unsigned)(pb.key_block_slots * pb.split)), dim3(512), 0, s, a);
   if (pb.split > 1)
     hipLaunchKernelGGL(k_finish, dim3((unsigned)(pb.T / pb.G + pb.R)), dim3(256), 0, s, a, pb.key_block);
-  return hipGetLastError();
+  if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
+  if (gather_apart)
+    return launch_compact(pb, sel->hidden, sel->pos, sel->kept_idx, total_kept, sel->hidden_out, sel->pos_out, s);
+  return hipSuccess;
 }
 
 }  // namespace up
