@@ -21,7 +21,8 @@ What is computed, step by step (paper section / equation in brackets):
    tokens and the last n tokens [Top-p Token Selection, last sentence; expansion
    kernel in the kernel-design paragraph].
 4. block-local top-k by keep ratio (the selection rule of this build's target;
-   the paper's own block-level top-p rule is ``select_blocks_top_p`` below),
+   the paper's own block-level top-p rule is ``select_blocks_top_p`` in fp64 and
+   ``select_tokens_top_p`` on the quantised scores, below),
    ordered with the packed integer key of Eq. 14, index complemented so that a
    descending order prefers the lower index among equal scores.
 5. compaction of hidden states / position ids onto the kept rows [Sparsity
@@ -240,3 +241,67 @@ def select_blocks_top_p(o_seq, p, *, block_size, n_obs, n_sink):
     keep_block[order[:kstar]] = True
     mask = np.repeat(keep_block, block_size)[:N]
     return mask | forced_mask(N, n_obs, n_sink)
+
+
+# --------------------------------------------------------------------------- #
+# block-level top-p on the quantised scores: the form a kernel can match bit for bit
+# --------------------------------------------------------------------------- #
+def block_mass_f32(scores_f32, N, block_size):
+    """Block masses as 32-bit floats (the key encoding of Eq. 14 acts on float bits): the
+    fp32 token scores of a block added one after the other in double, rounded once."""
+    s = np.asarray(scores_f32, dtype=np.float32).astype(np.float64)
+    out = []
+    for lo in range(0, N, block_size):
+        acc = 0.0
+        for v in s[lo:min(N, lo + block_size)]:
+            acc += float(v)
+        out.append(np.float32(acc))
+    return np.array(out, dtype=np.float32)
+
+
+def top_p_block_keys(mass_f32):
+    """(phi(mass) << 32) | (nb-1-g): the packed word of Eq. 14 for blocks, block index
+    complemented so that a descending order puts the lower block first among equal masses."""
+    b = np.asarray(mass_f32, dtype=np.float32)
+    nb = b.shape[0]
+    return (phi(b).astype(np.uint64) << np.uint64(32)) | (np.uint64(nb - 1) - np.arange(nb, dtype=np.uint64))
+
+
+def top_p_kept_blocks(mass_f32, p):
+    """Boolean keep flag per block under Eq. 5: blocks in descending key order, running sum
+    of their masses in double (one addition after the other, in that order), k* the first
+    position where the running sum reaches p times the total.  p is a float32 widened to
+    double."""
+    b = np.asarray(mass_f32, dtype=np.float32)
+    nb = b.shape[0]
+    order = np.argsort(top_p_block_keys(b), kind="stable")[::-1]
+    run = np.add.accumulate(b[order].astype(np.float64))          # sequential by definition
+    thr = float(np.float32(p)) * float(run[-1])
+    kstar = int(np.count_nonzero(run < thr)) + 1                   # run is non-decreasing (masses >= 0)
+    kstar = min(kstar, nb)
+    keep = np.zeros(nb, dtype=bool)
+    keep[order[:kstar]] = True
+    return keep
+
+
+def select_tokens_top_p(scores_f32, cu_seqlens, top_p, *, block_size, n_obs, n_sink):
+    """kept_idx (ascending packed row ids) and new_cu_seqlens under the paper's rule:
+    whole blocks chosen by cumulative mass (Eq. 4-5), sinks and query window always kept
+    (last sentence of "Top-p Token Selection"; expansion kernel of the kernel-design paragraph)."""
+    s = np.asarray(scores_f32, dtype=np.float32)
+    cu = np.asarray(cu_seqlens, dtype=np.int64)
+    kept = []
+    new_cu = np.zeros(len(cu), dtype=np.int32)
+    for r in range(len(cu) - 1):
+        c0, c1 = int(cu[r]), int(cu[r + 1])
+        N = c1 - c0
+        if N == 0:
+            new_cu[r + 1] = new_cu[r]
+            continue
+        keep_block = top_p_kept_blocks(block_mass_f32(s[c0:c1], N, block_size), top_p[r])
+        mask = np.repeat(keep_block, block_size)[:N] | forced_mask(N, n_obs, n_sink)
+        idx = np.nonzero(mask)[0]
+        kept.append((c0 + idx).astype(np.int32))
+        new_cu[r + 1] = new_cu[r] + len(idx)
+    kept_idx = np.concatenate(kept) if kept else np.zeros(0, dtype=np.int32)
+    return kept_idx.astype(np.int32), new_cu

@@ -268,3 +268,97 @@ def test_top_p_forces_sinks_and_window_and_p1_keeps_all_positive_mass():
     for g, lo in enumerate(range(0, N, G)):
         if b[g] > 0:
             assert m1[lo]
+
+
+# ----------------------------------------------------------------------------- top-p on quantised scores
+def _brute_force_top_p(mass, p):
+    """Smallest k, then (descending mass, lower index first) prefix -- by enumeration of k."""
+    nb = len(mass)
+    order = sorted(range(nb), key=lambda g: (-float(mass[g]), g))
+    total = 0.0
+    for g in order:
+        total += float(mass[g])
+    run = 0.0
+    for k, g in enumerate(order, 1):
+        run += float(mass[g])
+        if run >= float(np.float32(p)) * total:
+            return set(order[:k])
+    return set(order)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_quantised_top_p_blocks_against_enumeration(seed):
+    rng = np.random.default_rng(100 + seed)
+    nb = int(rng.integers(1, 40))
+    mass = (rng.random(nb) ** 6).astype(np.float32)
+    if seed % 2:
+        mass[rng.integers(0, nb, size=nb // 2)] = mass[0]      # ties
+    if seed == 3:
+        mass[:] = 0.0                                            # nothing to go by: first block only
+    for p in [0.1, 0.5, 0.9, 0.99, 1.0]:
+        keep = oracle.top_p_kept_blocks(mass, p)
+        assert set(np.nonzero(keep)[0]) == _brute_force_top_p(mass, p)
+        kept_mass = float(mass[keep].astype(np.float64).sum())
+        assert kept_mass >= float(np.float32(p)) * float(mass.astype(np.float64).sum()) * (1 - 1e-12)   # Eq. 6
+        if keep.sum() > 1:   # minimal: without its lightest kept block the set misses p
+            assert kept_mass - float(mass[keep].min()) < float(np.float32(p)) * float(mass.astype(np.float64).sum())
+
+
+def test_block_mass_f32_is_the_rounded_exact_sum():
+    rng = np.random.default_rng(9)
+    s = (rng.random(1000) ** 8).astype(np.float32)
+    b = oracle.block_mass_f32(s, 1000, 64)
+    from fractions import Fraction
+    for g, lo in enumerate(range(0, 1000, 64)):
+        exact = sum(Fraction(float(v)) for v in s[lo:lo + 64])
+        assert abs(Fraction(float(b[g])) - exact) <= Fraction(float(np.spacing(b[g]))) / 2 + exact * Fraction(1, 2 ** 50)
+    assert len(b) == 16 and b.dtype == np.float32
+
+
+def test_top_p_block_keys_order():
+    b = np.array([0.5, 0.25, 0.5, 0.0, 1.0], dtype=np.float32)
+    order = np.argsort(oracle.top_p_block_keys(b))[::-1]
+    assert list(order) == [4, 0, 2, 1, 3]          # descending mass, equal masses: lower block first
+
+
+def test_select_tokens_top_p_shape_forced_and_consistency_with_fp64_rule():
+    rng = np.random.default_rng(10)
+    lengths = [700, 0, 64, 1, 333]
+    cu = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int32)
+    o = rng.random(cu[-1]) ** 12
+    for r in range(len(lengths)):
+        if lengths[r]:
+            o[cu[r]:cu[r + 1]] /= o[cu[r]:cu[r + 1]].sum()
+    s32 = oracle.quantise_scores(o)
+    top_p = np.array([0.9, 0.5, 0.99, 0.7, 0.6], dtype=np.float32)
+    G, n, A = 32, 40, 8
+    kept, new_cu = oracle.select_tokens_top_p(s32, cu, top_p, block_size=G, n_obs=n, n_sink=A)
+    assert (np.diff(kept) > 0).all() and kept.dtype == np.int32
+    assert new_cu[-1] == len(kept) and new_cu[0] == 0
+    for r, N in enumerate(lengths):
+        mine = kept[new_cu[r]:new_cu[r + 1]] - cu[r]
+        assert ((mine >= 0) & (mine < max(N, 1))).all()
+        if N == 0:
+            assert len(mine) == 0
+            continue
+        mask = np.zeros(N, bool)
+        mask[mine] = True
+        assert mask[:A].all() and mask[max(0, N - n):].all()                 # sinks and window
+        # non-forced tokens are kept or dropped block by block
+        f = oracle.forced_mask(N, n, A)
+        for lo in range(0, N, G):
+            blk = mask[lo:lo + G][~f[lo:lo + G]]
+            assert blk.all() or not blk.any()
+        # same decision as the fp64 statement of the rule (scores here are far from any tie)
+        ref = oracle.select_blocks_top_p(s32[cu[r]:cu[r + 1]].astype(np.float64), float(top_p[r]),
+                                         block_size=G, n_obs=n, n_sink=A)
+        np.testing.assert_array_equal(mask, ref)
+    # p = 1 keeps every block of positive mass
+    kept1, _ = oracle.select_tokens_top_p(s32, cu, np.ones(5, np.float32), block_size=G, n_obs=0, n_sink=0)
+    m1 = np.zeros(cu[-1], bool)
+    m1[kept1] = True
+    for r, N in enumerate(lengths):
+        for lo in range(0, N, G):
+            blk = slice(cu[r] + lo, cu[r] + min(N, lo + G))
+            if s32[blk].sum() > 0:
+                assert m1[blk].all()
