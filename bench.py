@@ -199,12 +199,28 @@ def main():
             "scatter": timed(lambda: up.uniprefill_scatter(p, hidden_out, kept_idx, total_kept, full, stream=stream)),
             "device_copy_same_bytes": timed(lambda: dst.copy_(src)),
         }
+        # the paper's own rule (block-level top-p at the paper's p = 0.99) on the scores just computed;
+        # its outputs are sized for the worst case
+        try:
+            top_p_host = np.full(w.num_seqs, 0.99, dtype=np.float32)
+            top_p_dev = torch.from_numpy(top_p_host).cuda()
+            idx_all = torch.empty(w.total_tokens, dtype=torch.int32, device="cuda")
+            cu_tp = torch.empty(w.num_seqs + 1, dtype=torch.int32, device="cuda")
+            t_us["select_top_p"] = timed(lambda: up.uniprefill_select_top_p(
+                p, scores, cu, cu_host, top_p_dev, top_p_host, idx_all, cu_tp, workspace, ws_bytes, stream=stream))
+            top_p_kept = int(cu_tp[-1].item())
+            del idx_all, cu_tp
+        except up.UniPrefillError as e:      # e.g. more blocks per sequence than the top-p kernel orders
+            top_p_kept = None
+            print(f"[bench] top-p selection skipped: {e}", file=sys.stderr, flush=True)
         for name, us in t_us.items():
             ent = {"avg_us": round(us, 2)}
             if name in ("compact", "scatter", "device_copy_same_bytes"):
                 ent["gbs"] = round(gather_bytes / (us * 1e-6) / 1e9, 1)
                 ent["frac_hbm"] = round(gather_bytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)
             entry_points[name] = ent
+        if top_p_kept is not None:
+            entry_points["select_top_p"]["kept_at_p0.99"] = top_p_kept
         del full, src, dst
 
     if args.calibrate_copy:

@@ -155,6 +155,45 @@ int uniprefill_fused(const up_params* p, const void* q, const void* k, const voi
                      int32_t* kept_idx, int32_t* new_cu_seqlens_dev, float* scores_out,
                      void* workspace, size_t workspace_bytes, void* stream);
 
+/* Block-level top-p selection, the rule of Eq. 4-6: inside each sequence the
+ * blocks of G tokens are ordered by their mass (sum of the token scores; packed
+ * integer key of Eq. 14 on the 32-bit float mass, block index complemented so
+ * that equal masses resolve to the lower block) and the shortest prefix of that
+ * order whose cumulative mass reaches top_p of the sequence's total is kept
+ * whole; the first A and the last n tokens of a sequence are kept regardless
+ * ("Top-p Token Selection"; top-p and expansion kernels of the kernel-design
+ * paragraph).  Kept counts depend on the data: kept_idx must have room for
+ * total_tokens entries, and the totals stay on the device --
+ * new_cu_seqlens_dev[R] is the number of entries written.
+ *   Decisions are taken in fixed arithmetic: block mass = double sum of the
+ *   float scores in index order, rounded to float; running sum over the ordered
+ *   blocks in double, in that order; threshold (double)top_p * total.
+ *   top_p_dev/host [R] each, same values, in (0,1]
+ *   workspace      device scratch from uniprefill_plan (its first part is used)
+ *   UP_ERR_UNSUPPORTED if a sequence has more than 4096 blocks */
+int uniprefill_select_top_p(const up_params* p, const float* scores,
+                            const int32_t* cu_seqlens_dev, const int32_t* cu_seqlens_host,
+                            const float* top_p_dev, const float* top_p_host, int32_t* kept_idx,
+                            int32_t* new_cu_seqlens_dev, void* workspace, size_t workspace_bytes,
+                            void* stream);
+
+/* uniprefill_compact with the row count on the device (Eq. 7 after a selection
+ * whose size is data-dependent): rows t < total_kept_dev[0] are gathered;
+ * capacity (<= total_tokens) bounds the launch and the output buffers. */
+int uniprefill_compact_counted(const up_params* p, const void* hidden, const int32_t* pos,
+                               const int32_t* kept_idx, const int32_t* total_kept_dev,
+                               int64_t capacity, void* hidden_out, int32_t* pos_out, void* stream);
+
+/* score -> block-level top-p selection -> compact in one call, no host
+ * synchronisation.  hidden_out, pos_out and kept_idx need room for
+ * total_tokens rows / entries; scores (device float [T]) is required. */
+int uniprefill_fused_top_p(const up_params* p, const void* q, const void* k, const void* hidden,
+                           const int32_t* pos, const int32_t* cu_seqlens_dev,
+                           const int32_t* cu_seqlens_host, const float* top_p_dev,
+                           const float* top_p_host, void* hidden_out, int32_t* pos_out,
+                           int32_t* kept_idx, int32_t* new_cu_seqlens_dev, float* scores,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
 /* The kernels behind uniprefill_fused, in stream order.  Measurement aid: a
  * caller that wants to time one kernel enqueues the phases one by one. */
 enum {

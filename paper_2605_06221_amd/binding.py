@@ -19,7 +19,8 @@ UP_OK, UP_ERR_NULL, UP_ERR_SHAPE, UP_ERR_RANGE, UP_ERR_UNSUPPORTED, UP_ERR_ALIGN
 UP_BF16, UP_F32 = 0, 1
 
 EXPORTS = ["uniprefill_plan", "uniprefill_score", "uniprefill_select", "uniprefill_compact",
-           "uniprefill_scatter", "uniprefill_fused", "uniprefill_fused_phases", "uniprefill_status_string"]
+           "uniprefill_scatter", "uniprefill_fused", "uniprefill_fused_phases", "uniprefill_select_top_p",
+           "uniprefill_compact_counted", "uniprefill_fused_top_p", "uniprefill_status_string"]
 
 UP_PHASE_PLAN, UP_PHASE_ROW_STATS, UP_PHASE_MERGE_STATS, UP_PHASE_SWEEP_SELECT_COMPACT = 1, 2, 4, 8
 UP_PHASE_ALL = 15
@@ -59,6 +60,9 @@ def _load():
     lib.uniprefill_scatter.argtypes = [P, vp, i32p, ctypes.c_int64, vp, vp]
     lib.uniprefill_fused.argtypes = [P, vp, vp, vp, i32p, i32p, i32p, f32p, f32p, vp, i32p, i32p, i32p, f32p, vp, ctypes.c_size_t, vp]
     lib.uniprefill_fused_phases.argtypes = lib.uniprefill_fused.argtypes[:-1] + [ctypes.c_int, vp]
+    lib.uniprefill_select_top_p.argtypes = [P, f32p, i32p, i32p, f32p, f32p, i32p, i32p, vp, ctypes.c_size_t, vp]
+    lib.uniprefill_compact_counted.argtypes = [P, vp, i32p, i32p, i32p, ctypes.c_int64, vp, i32p, vp]
+    lib.uniprefill_fused_top_p.argtypes = lib.uniprefill_fused.argtypes
     for name in EXPORTS[:-1]:
         getattr(lib, name).restype = ctypes.c_int
     lib.uniprefill_status_string.argtypes = [ctypes.c_int]
@@ -173,3 +177,30 @@ def uniprefill_fused_phases(p, q, k, hidden, pos, cu_seqlens_dev, cu_seqlens_hos
                                       ptr(new_cu_seqlens_dev), ptr(scores_out), ptr(workspace),
                                       workspace_bytes, int(phase_mask), _stream(stream))
     return _check(st, "uniprefill_fused_phases", check)
+
+
+def uniprefill_select_top_p(p, scores, cu_seqlens_dev, cu_seqlens_host, top_p_dev, top_p_host, kept_idx,
+                            new_cu_seqlens_dev, workspace, workspace_bytes, stream=None, check=True):
+    st = _lib.uniprefill_select_top_p(ctypes.byref(p), ptr(scores), ptr(cu_seqlens_dev), ptr(cu_seqlens_host),
+                                      ptr(top_p_dev), ptr(top_p_host), ptr(kept_idx), ptr(new_cu_seqlens_dev),
+                                      ptr(workspace), workspace_bytes, _stream(stream))
+    return _check(st, "uniprefill_select_top_p", check)
+
+
+def uniprefill_compact_counted(p, hidden, pos, kept_idx, total_kept_dev, capacity, hidden_out, pos_out,
+                               stream=None, check=True):
+    st = _lib.uniprefill_compact_counted(ctypes.byref(p), ptr(hidden), ptr(pos), ptr(kept_idx),
+                                         ptr(total_kept_dev), int(capacity), ptr(hidden_out), ptr(pos_out),
+                                         _stream(stream))
+    return _check(st, "uniprefill_compact_counted", check)
+
+
+def uniprefill_fused_top_p(p, q, k, hidden, pos, cu_seqlens_dev, cu_seqlens_host, top_p_dev, top_p_host,
+                           hidden_out, pos_out, kept_idx, new_cu_seqlens_dev, scores, workspace,
+                           workspace_bytes, stream=None, check=True):
+    st = _lib.uniprefill_fused_top_p(ctypes.byref(p), ptr(q), ptr(k), ptr(hidden), ptr(pos),
+                                     ptr(cu_seqlens_dev), ptr(cu_seqlens_host), ptr(top_p_dev),
+                                     ptr(top_p_host), ptr(hidden_out), ptr(pos_out), ptr(kept_idx),
+                                     ptr(new_cu_seqlens_dev), ptr(scores), ptr(workspace), workspace_bytes,
+                                     _stream(stream))
+    return _check(st, "uniprefill_fused_top_p", check)

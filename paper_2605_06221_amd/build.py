@@ -9,7 +9,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libuniprefill.so")
-SOURCES = ["up_api.hip", "up_copy.hip", "up_select.hip", "up_sweep.hip"]
+SOURCES = ["up_api.hip", "up_copy.hip", "up_select.hip", "up_sweep.hip", "up_topp.hip"]
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",

@@ -185,6 +185,78 @@ int uniprefill_select(const up_params* p, const float* scores, const int32_t* cu
   return UP_OK;
 }
 
+int uniprefill_select_top_p(const up_params* p, const float* scores, const int32_t* cu_seqlens_dev,
+                            const int32_t* cu_seqlens_host, const float* top_p_dev,
+                            const float* top_p_host, int32_t* kept_idx, int32_t* new_cu_seqlens_dev,
+                            void* workspace, size_t workspace_bytes, void* stream) {
+  Problem pb;
+  int st = check_params(p, false, false, &pb);
+  if (st != UP_OK) return st;
+  if (!scores || !cu_seqlens_dev || !top_p_dev || !kept_idx || !new_cu_seqlens_dev) return UP_ERR_NULL;
+  if ((st = check_cu(p, cu_seqlens_host)) != UP_OK) return st;
+  if ((st = check_ratio(p, top_p_host)) != UP_OK) return st;
+  for (int r = 0; r < p->num_seqs; ++r)
+    if ((cu_seqlens_host[r + 1] - cu_seqlens_host[r] + pb.G - 1) / pb.G > kMaxTopPBlocks)
+      return UP_ERR_UNSUPPORTED;
+  if (workspace == nullptr || workspace_bytes < workspace_layout(pb).tp_total) return UP_ERR_WORKSPACE;
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return UP_ERR_ALIGN;
+  if (launch_top_p(pb, scores, cu_seqlens_dev, top_p_dev, kept_idx, new_cu_seqlens_dev, workspace,
+                   (hipStream_t)stream) != hipSuccess)
+    return UP_ERR_HIP;
+  return UP_OK;
+}
+
+int uniprefill_compact_counted(const up_params* p, const void* hidden, const int32_t* pos,
+                               const int32_t* kept_idx, const int32_t* total_kept_dev,
+                               int64_t capacity, void* hidden_out, int32_t* pos_out, void* stream) {
+  Problem pb;
+  int st = check_params(p, false, true, &pb);
+  if (st != UP_OK) return st;
+  if (capacity < 0 || capacity > p->total_tokens) return UP_ERR_RANGE;
+  if (!hidden || !kept_idx || !hidden_out || !total_kept_dev) return UP_ERR_NULL;
+  if ((pos == nullptr) != (pos_out == nullptr)) return UP_ERR_NULL;
+  if (!aligned16(hidden) || !aligned16(hidden_out)) return UP_ERR_ALIGN;
+  if (launch_compact_counted(pb, hidden, pos, kept_idx, total_kept_dev, capacity, hidden_out, pos_out,
+                             (hipStream_t)stream) != hipSuccess)
+    return UP_ERR_HIP;
+  return UP_OK;
+}
+
+int uniprefill_fused_top_p(const up_params* p, const void* q, const void* k, const void* hidden,
+                           const int32_t* pos, const int32_t* cu_seqlens_dev,
+                           const int32_t* cu_seqlens_host, const float* top_p_dev,
+                           const float* top_p_host, void* hidden_out, int32_t* pos_out,
+                           int32_t* kept_idx, int32_t* new_cu_seqlens_dev, float* scores,
+                           void* workspace, size_t workspace_bytes, void* stream) {
+  // every check of the three steps before the first launch
+  Problem pb;
+  int st = check_params(p, true, true, &pb);
+  if (st != UP_OK) return st;
+  if (!q || !k || !hidden || !cu_seqlens_dev || !top_p_dev || !hidden_out || !kept_idx ||
+      !new_cu_seqlens_dev || !scores)
+    return UP_ERR_NULL;
+  if ((pos == nullptr) != (pos_out == nullptr)) return UP_ERR_NULL;
+  if ((st = check_cu(p, cu_seqlens_host)) != UP_OK) return st;
+  if ((st = check_ratio(p, top_p_host)) != UP_OK) return st;
+  for (int r = 0; r < p->num_seqs; ++r)
+    if ((cu_seqlens_host[r + 1] - cu_seqlens_host[r] + pb.G - 1) / pb.G > kMaxTopPBlocks)
+      return UP_ERR_UNSUPPORTED;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(hidden) || !aligned16(hidden_out))
+    return UP_ERR_ALIGN;
+  choose_geometry(&pb, cu_seqlens_host);
+  if (workspace == nullptr || workspace_bytes < workspace_layout(pb).total) return UP_ERR_WORKSPACE;
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return UP_ERR_ALIGN;
+  if ((st = uniprefill_score(p, q, k, cu_seqlens_dev, cu_seqlens_host, scores, workspace,
+                             workspace_bytes, stream)) != UP_OK)
+    return st;
+  if ((st = uniprefill_select_top_p(p, scores, cu_seqlens_dev, cu_seqlens_host, top_p_dev, top_p_host,
+                                    kept_idx, new_cu_seqlens_dev, workspace, workspace_bytes,
+                                    stream)) != UP_OK)
+    return st;
+  return uniprefill_compact_counted(p, hidden, pos, kept_idx, new_cu_seqlens_dev + p->num_seqs,
+                                    p->total_tokens, hidden_out, pos_out, stream);
+}
+
 int uniprefill_compact(const up_params* p, const void* hidden, const int32_t* pos,
                        const int32_t* kept_idx, int64_t total_kept, void* hidden_out,
                        int32_t* pos_out, void* stream) {

@@ -15,10 +15,12 @@ __global__ __launch_bounds__(256) void k_rows(const char* __restrict__ src, char
                                               const int32_t* __restrict__ idx, long long total_kept,
                                               long long row_bytes, long long stride_bytes,
                                               const int32_t* __restrict__ pos,
-                                              int32_t* __restrict__ pos_out) {
+                                              int32_t* __restrict__ pos_out,
+                                              const int32_t* __restrict__ count_dev) {
   const int lane = threadIdx.x & 63;
   const long long t = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (t >= total_kept) return;
+  // (count_dev: the number of rows lives on the device; the launch covers the capacity)
+  if (t >= (count_dev != nullptr ? (long long)count_dev[0] : total_kept)) return;
   const long long row = idx[t];
   if (SCATTER) {
     copy_row_wave(src + t * stride_bytes, dst + row * stride_bytes, row_bytes, lane);
@@ -36,7 +38,19 @@ hipError_t launch_compact(const Problem& pb, const void* hidden, const int32_t* 
   const long long stride_bytes = pb.h_stride * pb.hidden_elem_bytes;
   const unsigned grid = (unsigned)((total_kept + 3) / 4);
   hipLaunchKernelGGL(k_rows<false>, dim3(grid), dim3(256), 0, s, (const char*)hidden,
-                     (char*)hidden_out, kept_idx, total_kept, row_bytes, stride_bytes, pos, pos_out);
+                     (char*)hidden_out, kept_idx, total_kept, row_bytes, stride_bytes, pos, pos_out, (const int32_t*)nullptr);
+  return hipGetLastError();
+}
+
+hipError_t launch_compact_counted(const Problem& pb, const void* hidden, const int32_t* pos,
+                                  const int32_t* kept_idx, const int32_t* count_dev, long long capacity,
+                                  void* hidden_out, int32_t* pos_out, hipStream_t s) {
+  if (capacity == 0) return hipSuccess;
+  const long long row_bytes = (long long)pb.d * pb.hidden_elem_bytes;
+  const long long stride_bytes = pb.h_stride * pb.hidden_elem_bytes;
+  const unsigned grid = (unsigned)((capacity + 3) / 4);
+  hipLaunchKernelGGL(k_rows<false>, dim3(grid), dim3(256), 0, s, (const char*)hidden,
+                     (char*)hidden_out, kept_idx, capacity, row_bytes, stride_bytes, pos, pos_out, count_dev);
   return hipGetLastError();
 }
 
@@ -48,7 +62,7 @@ hipError_t launch_scatter(const Problem& pb, const void* hidden_compact, const i
   const unsigned grid = (unsigned)((total_kept + 3) / 4);
   hipLaunchKernelGGL(k_rows<true>, dim3(grid), dim3(256), 0, s, (const char*)hidden_compact,
                      (char*)hidden_full, kept_idx, total_kept, row_bytes, stride_bytes,
-                     (const int32_t*)nullptr, (int32_t*)nullptr);
+                     (const int32_t*)nullptr, (int32_t*)nullptr, (const int32_t*)nullptr);
   return hipGetLastError();
 }
 

@@ -29,6 +29,7 @@ struct Problem {
 // Workspace carve-up (byte offsets, each 256-aligned).
 struct Workspace {
   size_t stat_part_off, stat_fin_off, o_part_off, total;
+  size_t tp_keep_off, tp_off_off, tp_seq_off, tp_mass_off, tp_total;   // top-p selection part (first tp_total bytes)
 };
 Workspace workspace_layout(const Problem& pb);
 
@@ -46,6 +47,27 @@ SelectArgs make_select_args(const Problem& pb, const float* scores, const int32_
                             const int32_t* new_cu, int32_t* kept_idx, const void* hidden,
                             const int32_t* pos, void* hidden_out, int32_t* pos_out);
 hipError_t launch_select(const Problem& pb, const SelectArgs& a, hipStream_t s);
+
+// --- block-level top-p selection (Eq. 4-6); kept_idx needs room for T entries
+constexpr int kMaxTopPBlocks = 4096;   // blocks of one sequence that the top-p kernel orders in LDS
+struct TopPArgs {
+  const float* scores;
+  const int32_t* cu;
+  const float* top_p;
+  int32_t* kept_idx;
+  int32_t* new_cu;
+  int32_t* blk_keep;     // [T/G + R] block chosen by the top-p rule
+  int32_t* blk_off;      // [T/G + R] kept tokens of the sequence before this block
+  int32_t* seq_kept;     // [R] kept tokens per sequence
+  float* blk_mass;       // [T/G + R] block masses
+  int R, T, G, n_obs, n_sink;
+};
+hipError_t launch_top_p(const Problem& pb, const float* scores, const int32_t* cu, const float* top_p,
+                        int32_t* kept_idx, int32_t* new_cu, void* workspace, hipStream_t s);
+// gather with the row count on the device (count_dev[0] rows, at most capacity)
+hipError_t launch_compact_counted(const Problem& pb, const void* hidden, const int32_t* pos,
+                                  const int32_t* kept_idx, const int32_t* count_dev, long long capacity,
+                                  void* hidden_out, int32_t* pos_out, hipStream_t s);
 
 // --- scoring (Eq. 2-3)
 // pass 1: softmax statistics of every window row per 256-key block (into the workspace)

@@ -548,6 +548,18 @@ Workspace workspace_layout(const Problem& pb) {
   auto al = [](size_t x) { return (x + 255) & ~(size_t)255; };
   Workspace w;
   size_t off = 0;
+  // block-level top-p selection: flags and offsets per selection block, totals per sequence.
+  // First in the buffer: their place depends on T, G and R only, not on the scoring geometry.
+  const size_t sel_slots = (size_t)(pb.T / pb.G + pb.R);
+  w.tp_keep_off = off;
+  off = al(off + sel_slots * sizeof(int32_t));
+  w.tp_off_off = off;
+  off = al(off + sel_slots * sizeof(int32_t));
+  w.tp_seq_off = off;
+  off = al(off + (size_t)(pb.R + 1) * sizeof(int32_t));
+  w.tp_mass_off = off;
+  off = al(off + sel_slots * sizeof(float));
+  w.tp_total = off;
   w.stat_part_off = off;
   off = al(off + (size_t)pb.key_block_slots * pb.Hq * pb.n_obs * sizeof(float2));
   w.stat_fin_off = off;

@@ -1,0 +1,245 @@
+// Block-level top-p selection (Eq. 4-6; top-p kernel and expansion kernel of the
+// kernel-design paragraph): per sequence, the mass of every block of G tokens,
+// blocks ordered by the packed integer key of Eq. 14, the shortest prefix of
+// that order whose mass reaches p of the total, expanded to tokens with the
+// attention sinks and the query window always kept.
+//
+// Kept counts depend on the data, so the outputs are sized for the worst case
+// and the totals stay on the device (new_cu_seqlens).  Four launches:
+//   k_block_mass     one wave per block: its mass
+//   k_top_p_blocks   one work-group per sequence: ranks, threshold, keep flags
+//                    and in-sequence output offsets of the blocks
+//   k_top_p_offsets  prefix sum of the per-sequence totals
+//   k_top_p_emit     one work-group per block: kept token ids, ascending
+//
+// Arithmetic that decides integers is fixed so that it can be matched bit for
+// bit: a block's mass is the double sum of its float scores in index order,
+// rounded to float; the running sum over the ordered blocks is a double sum in
+// that order; the threshold is (double)p times the total.
+#include "up_common.h"
+#include "up_kernels.h"
+#include "up_select.h"
+
+namespace up {
+
+constexpr int kTopPThreads = 1024;
+
+struct TopPSmem {
+  unsigned long long key[kMaxTopPBlocks];
+  float sorted_mass[kMaxTopPBlocks];
+  int rank[kMaxTopPBlocks];
+  double run[kMaxTopPBlocks];     // running sum over the ordered blocks
+  int wave_tot[16];
+  int kstar_part[16];
+  double thr;
+};
+
+// Mass of one block per wave: the lanes fetch the block's scores in one coalesced access
+// each, then every lane adds them in index order (lane after lane, through broadcasts), so
+// the sum is the same sequence of double additions as a plain loop over the block.
+__global__ __launch_bounds__(256) void k_block_mass(TopPArgs a) {
+  const int G = a.G;
+  const int slot = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (slot >= a.T / G + a.R) return;
+  const int lane = threadIdx.x & 63;
+  const int r = locate_slot(a.cu, a.R, G, slot);
+  const int c0 = a.cu[r];
+  const int N = a.cu[r + 1] - c0;
+  const int g = slot - slot_base(c0, r, G);
+  if (g * G >= N) return;   // slack slot (also every slot of an empty sequence)
+  const int L = imin(G, N - g * G);
+  const float* s = a.scores + c0 + (long long)g * G;
+  const float v0 = lane < L ? s[lane] : 0.0f;            // (+0 leaves a sum of non-negative terms as it is)
+  const float v1 = 64 + lane < L ? s[64 + lane] : 0.0f;
+  double acc = 0.0;
+#pragma unroll
+  for (int i = 0; i < 64; ++i) acc += (double)__shfl(v0, i);
+  if (G > 64) {
+#pragma unroll
+    for (int i = 0; i < 64; ++i) acc += (double)__shfl(v1, i);
+  }
+  if (lane == 0) a.blk_mass[slot] = (float)acc;
+}
+
+__global__ __launch_bounds__(kTopPThreads) void k_top_p_blocks(TopPArgs a) {
+  __shared__ TopPSmem sm;
+  const int r = blockIdx.x;
+  const int c0 = a.cu[r];
+  const int N = a.cu[r + 1] - c0;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (N == 0) {
+    if (tid == 0) a.seq_kept[r] = 0;
+    return;
+  }
+  const int G = a.G;
+  const int nb = ceil_div(N, G);
+  const int slot0 = slot_base(c0, r, G);
+
+  // 1. ordering keys from the block masses
+  for (int g = tid; g < nb; g += kTopPThreads) {
+    const float m = a.blk_mass[slot0 + g];
+    sm.key[g] = ((unsigned long long)phi(m) << 32) | (unsigned)(nb - 1 - g);
+  }
+  __syncthreads();
+  // 2. keys into descending order (bitonic network over the next power of two, padded with
+  // zero keys, which sort behind every real key); a key names its block and carries its mass
+  int n2 = 64;
+  while (n2 < nb) n2 <<= 1;
+  for (int i = nb + tid; i < n2; i += kTopPThreads) sm.key[i] = 0ull;
+  __syncthreads();
+  for (int k = 2; k <= n2; k <<= 1) {
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      for (int i = tid; i < n2; i += kTopPThreads) {
+        const int other = i ^ j;
+        if (other > i) {
+          const unsigned long long x = sm.key[i], y = sm.key[other];
+          const bool first_larger = (i & k) == 0;        // this stretch is being put in descending order
+          if (first_larger ? x < y : x > y) {
+            sm.key[i] = y;
+            sm.key[other] = x;
+          }
+        }
+      }
+      __syncthreads();
+    }
+  }
+  for (int k = tid; k < nb; k += kTopPThreads) {
+    const unsigned long long key = sm.key[k];
+    const int g = nb - 1 - (int)(unsigned)(key & 0xFFFFFFFFull);
+    const unsigned hi = (unsigned)(key >> 32);
+    sm.rank[g] = k;
+    sm.sorted_mass[k] = __uint_as_float((hi & 0x80000000u) ? (hi ^ 0x80000000u) : ~hi);   // inverse of phi
+  }
+  __syncthreads();
+  // 3. running sum in that order, one addition after the other
+  if (tid == 0) {
+    double acc = 0.0;
+    for (int k0 = 0; k0 < nb; k0 += 16) {
+      float v[16];     // sixteen reads in flight, then the additions in order
+#pragma unroll
+      for (int j = 0; j < 16; ++j) v[j] = k0 + j < nb ? sm.sorted_mass[k0 + j] : 0.0f;
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        acc += (double)v[j];
+        if (k0 + j < nb) sm.run[k0 + j] = acc;
+      }
+    }
+    sm.thr = (double)a.top_p[r] * acc;
+  }
+  __syncthreads();
+  // 4. k* = 1 + number of prefixes still below the threshold (the running sum never decreases)
+  const double thr = sm.thr;
+  int below = 0;
+  for (int k = tid; k < nb; k += kTopPThreads) below += sm.run[k] < thr ? 1 : 0;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) below += __shfl_xor(below, o);
+  if (lane == 0) sm.kstar_part[wave] = below;
+  __syncthreads();
+  int kstar = 1;
+  for (int w2 = 0; w2 < kTopPThreads / 64; ++w2) kstar += sm.kstar_part[w2];
+  kstar = imin(kstar, nb);
+  // 5. tokens kept per block and their exclusive prefix inside the sequence
+  SeqGeom sg{N, G, a.n_obs, a.n_sink, 1.0};
+  int carry = 0;
+  for (int base = 0; base < nb; base += kTopPThreads) {
+    const int g = base + tid;
+    int cnt = 0, keep = 0;
+    if (g < nb) {
+      const int lo = g * G, hi = imin(N, lo + G);
+      keep = sm.rank[g] < kstar ? 1 : 0;
+      cnt = keep ? hi - lo : forced_in(sg, lo, hi);
+    }
+    int incl = cnt;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int up_v = __shfl_up(incl, o);
+      if (lane >= o) incl += up_v;
+    }
+    if (lane == 63) sm.wave_tot[wave] = incl;
+    __syncthreads();
+    int before = carry;
+    for (int w2 = 0; w2 < wave; ++w2) before += sm.wave_tot[w2];
+    if (g < nb) {
+      a.blk_keep[slot0 + g] = keep;
+      a.blk_off[slot0 + g] = before + incl - cnt;
+    }
+    int total = carry;
+    for (int w2 = 0; w2 < kTopPThreads / 64; ++w2) total += sm.wave_tot[w2];
+    carry = total;
+    __syncthreads();
+  }
+  if (tid == 0) a.seq_kept[r] = carry;
+}
+
+// Exclusive prefix of the per-sequence totals: the compacted stream's sequence offsets.
+__global__ __launch_bounds__(1024) void k_top_p_offsets(const int32_t* __restrict__ seq_kept, int R,
+                                                        int32_t* __restrict__ new_cu) {
+  __shared__ int wave_tot[16];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int carry = 0;
+  if (tid == 0) new_cu[0] = 0;
+  for (int base = 0; base < R; base += 1024) {
+    const int r = base + tid;
+    const int v = r < R ? seq_kept[r] : 0;
+    int incl = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int up_v = __shfl_up(incl, o);
+      if (lane >= o) incl += up_v;
+    }
+    if (lane == 63) wave_tot[wave] = incl;
+    __syncthreads();
+    int before = carry;
+    for (int w2 = 0; w2 < wave; ++w2) before += wave_tot[w2];
+    if (r < R) new_cu[r + 1] = before + incl;
+    int total = carry;
+    for (int w2 = 0; w2 < 16; ++w2) total += wave_tot[w2];
+    carry = total;
+    __syncthreads();
+  }
+}
+
+// Expansion to tokens: block g of sequence r keeps all its tokens if the block was chosen,
+// otherwise only its sinks / window tokens; ids are written in ascending order.
+__global__ __launch_bounds__(128) void k_top_p_emit(TopPArgs a) {
+  __shared__ int cnt0;
+  const int G = a.G;
+  const int slot = blockIdx.x;
+  const int r = locate_slot(a.cu, a.R, G, slot);
+  const int c0 = a.cu[r];
+  const int N = a.cu[r + 1] - c0;
+  const int g = slot - slot_base(c0, r, G);
+  if (g * G >= N) return;   // slack slot (also every slot of an empty sequence)
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int i = g * G + tid;
+  const bool in_block = tid < G && i < N;
+  const bool keep = in_block && (a.blk_keep[slot] != 0 || i < a.n_sink || i >= N - a.n_obs);
+  const unsigned long long bal = __ballot(keep);
+  const int before = __popcll(bal & ((1ull << lane) - 1ull));
+  if (wave == 0 && lane == 0) cnt0 = __popcll(bal);
+  __syncthreads();
+  if (keep) a.kept_idx[a.new_cu[r] + a.blk_off[slot] + before + (wave == 1 ? cnt0 : 0)] = c0 + i;
+}
+
+hipError_t launch_top_p(const Problem& pb, const float* scores, const int32_t* cu, const float* top_p,
+                        int32_t* kept_idx, int32_t* new_cu, void* workspace, hipStream_t s) {
+  const Workspace w = workspace_layout(pb);
+  char* ws = (char*)workspace;
+  TopPArgs a;
+  a.scores = scores; a.cu = cu; a.top_p = top_p; a.kept_idx = kept_idx; a.new_cu = new_cu;
+  a.blk_keep = (int32_t*)(ws + w.tp_keep_off);
+  a.blk_off = (int32_t*)(ws + w.tp_off_off);
+  a.seq_kept = (int32_t*)(ws + w.tp_seq_off);
+  a.blk_mass = (float*)(ws + w.tp_mass_off);
+  a.R = pb.R; a.T = pb.T; a.G = pb.G; a.n_obs = pb.n_obs; a.n_sink = pb.n_sink;
+  if (pb.T > 0)
+    hipLaunchKernelGGL(k_block_mass, dim3((unsigned)((pb.T / pb.G + pb.R + 3) / 4)), dim3(256), 0, s, a);
+  if (pb.R > 0)
+    hipLaunchKernelGGL(k_top_p_blocks, dim3((unsigned)pb.R), dim3(kTopPThreads), 0, s, a);
+  hipLaunchKernelGGL(k_top_p_offsets, dim3(1), dim3(1024), 0, s, a.seq_kept, pb.R, new_cu);
+  if (pb.T > 0)
+    hipLaunchKernelGGL(k_top_p_emit, dim3((unsigned)(pb.T / pb.G + pb.R)), dim3(128), 0, s, a);
+  return hipGetLastError();
+}
+
+}  // namespace up

@@ -386,3 +386,114 @@ def test_fused_full_size_configs_bit_exact(idx):
     _say("  gpu done; running oracle")
     ref = oracle_run(w)
     _assert_fused_exact(w, b, ref)
+
+
+# ----------------------------------------------------------------------------- block-level top-p (Eq. 4-6)
+def _top_p_buffers(w):
+    p = up.make_params(num_seqs=w.num_seqs, total_tokens=w.total_tokens, block_size=w.block_size, n_obs=w.n_obs,
+                       n_sink=w.n_sink, num_q_heads=w.num_q_heads, num_kv_heads=w.num_kv_heads,
+                       head_dim=w.head_dim, hidden_dim=w.hidden_dim)
+    cu_host = np.ascontiguousarray(w.cu_seqlens, dtype=np.int32)
+    _, _, _, ws_bytes = up.uniprefill_plan(p, cu_host, np.full(w.num_seqs, 0.5, np.float32))
+    T, pad = w.total_tokens, 64
+    return dict(p=p, cu_host=cu_host, cu=torch.from_numpy(cu_host).cuda(), ws_bytes=ws_bytes,
+                workspace=torch.empty(ws_bytes + 256, dtype=torch.uint8, device="cuda"),
+                kept_idx=torch.full((T + pad,), -77, dtype=torch.int32, device="cuda"),
+                new_cu=torch.full((w.num_seqs + 1 + pad,), -77, dtype=torch.int32, device="cuda"))
+
+
+@pytest.mark.parametrize("G", [32, 64, 128])
+@pytest.mark.parametrize("kind", ["random", "ties", "zeros", "heavy"])
+def test_select_top_p_is_bit_exact_on_given_scores(G, kind):
+    _say("top-p select", G, kind)
+    lengths = [1000, 0, 1, G, G + 1, 5000, 77, 3 * G - 1]
+    rng = np.random.default_rng(40 + G)
+    w = workloads.make_custom(name="tp", seed=5, lengths=lengths, keep_ratio=[0.5] * len(lengths), hidden_dim=8,
+                              num_q_heads=2, num_kv_heads=1, block_size=G, n_obs=48, n_sink=20)
+    T = w.total_tokens
+    if kind == "random":
+        s = rng.random(T).astype(np.float32)
+    elif kind == "ties":
+        s = rng.integers(0, 3, size=T).astype(np.float32) * np.float32(0.125)
+    elif kind == "zeros":
+        s = np.zeros(T, np.float32)
+    else:
+        s = (rng.random(T) ** 30).astype(np.float32)
+        s[rng.random(T) < 0.5] = 0.0
+    top_p = rng.choice(np.array([0.3, 0.9, 0.99, 1.0], np.float32), size=len(lengths)).astype(np.float32)
+    want_idx, want_cu = oracle.select_tokens_top_p(s, w.cu_seqlens, top_p, block_size=G, n_obs=w.n_obs, n_sink=w.n_sink)
+    b = _top_p_buffers(w)
+    up.uniprefill_select_top_p(b["p"], torch.from_numpy(s).cuda(), b["cu"], b["cu_host"], torch.from_numpy(top_p).cuda(),
+                               top_p, b["kept_idx"], b["new_cu"], b["workspace"], b["ws_bytes"])
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(b["new_cu"][:w.num_seqs + 1].cpu().numpy(), want_cu)
+    np.testing.assert_array_equal(b["kept_idx"][:len(want_idx)].cpu().numpy(), want_idx)
+    assert (b["kept_idx"][len(want_idx):] == -77).all() and (b["new_cu"][w.num_seqs + 1:] == -77).all()
+
+
+def test_select_top_p_long_sequence_and_many_sequences():
+    rng = np.random.default_rng(44)
+    lengths = [131072] + [int(x) for x in rng.integers(0, 300, size=300)]
+    _say("top-p select long + many, T", sum(lengths))
+    w = workloads.make_custom(name="tpl", seed=6, lengths=lengths, keep_ratio=[0.5] * len(lengths), hidden_dim=8,
+                              num_q_heads=2, num_kv_heads=1, block_size=32, n_obs=128, n_sink=128)
+    s = (rng.random(w.total_tokens) ** 20).astype(np.float32)
+    top_p = rng.uniform(0.5, 1.0, size=len(lengths)).astype(np.float32)
+    want_idx, want_cu = oracle.select_tokens_top_p(s, w.cu_seqlens, top_p, block_size=32, n_obs=128, n_sink=128)
+    b = _top_p_buffers(w)
+    up.uniprefill_select_top_p(b["p"], torch.from_numpy(s).cuda(), b["cu"], b["cu_host"], torch.from_numpy(top_p).cuda(),
+                               top_p, b["kept_idx"], b["new_cu"], b["workspace"], b["ws_bytes"])
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(b["new_cu"][:w.num_seqs + 1].cpu().numpy(), want_cu)
+    np.testing.assert_array_equal(b["kept_idx"][:len(want_idx)].cpu().numpy(), want_idx)
+    # one block too many for the in-LDS ordering: refused on the host, nothing launched
+    w2 = workloads.make_custom(name="tpx", seed=6, lengths=[32 * 4096 + 1], keep_ratio=[0.5], hidden_dim=8,
+                               num_q_heads=2, num_kv_heads=1, block_size=32, n_obs=128, n_sink=128)
+    b2 = _top_p_buffers(w2)
+    st = up.uniprefill_select_top_p(b2["p"], torch.zeros(w2.total_tokens, device="cuda"), b2["cu"], b2["cu_host"],
+                                    torch.ones(1, device="cuda"), np.ones(1, np.float32), b2["kept_idx"], b2["new_cu"],
+                                    b2["workspace"], b2["ws_bytes"], check=False)
+    assert st == up.UP_ERR_UNSUPPORTED
+
+
+def test_fused_top_p_matches_oracle_end_to_end():
+    _say("fused top-p")
+    w = workloads.make_custom(name="ftp", seed=14, lengths=[3000, 150, 0, 1111], keep_ratio=[0.5] * 4,
+                              hidden_dim=64, num_q_heads=8, num_kv_heads=2, block_size=64, n_obs=128)
+    top_p = np.array([0.9, 0.99, 0.5, 0.8], np.float32)
+    b = _top_p_buffers(w)
+    T, d = w.total_tokens, w.hidden_dim
+    q, k, hidden = dev_bf16(w.q), dev_bf16(w.k), dev_bf16(w.hidden)
+    pos = torch.from_numpy(w.pos).cuda()
+    hidden_out = torch.full((T + 8, d), -7.0, dtype=torch.bfloat16, device="cuda")
+    pos_out = torch.full((T + 8,), -77, dtype=torch.int32, device="cuda")
+    scores = torch.empty(T, dtype=torch.float32, device="cuda")
+    up.uniprefill_fused_top_p(b["p"], q, k, hidden, pos, b["cu"], b["cu_host"], torch.from_numpy(top_p).cuda(), top_p,
+                              hidden_out, pos_out, b["kept_idx"], b["new_cu"], scores, b["workspace"], b["ws_bytes"])
+    torch.cuda.synchronize()
+    got_scores = scores.cpu().numpy()
+    got_cu = b["new_cu"][:w.num_seqs + 1].cpu().numpy()
+    total = int(got_cu[-1])
+    got_idx = b["kept_idx"][:total].cpu().numpy()
+    # the selection is the oracle's rule applied to the scores the GPU produced (bit for bit) ...
+    want_idx, want_cu = oracle.select_tokens_top_p(got_scores, w.cu_seqlens, top_p, block_size=w.block_size,
+                                                   n_obs=w.n_obs, n_sink=w.n_sink)
+    np.testing.assert_array_equal(got_cu, want_cu)
+    np.testing.assert_array_equal(got_idx, want_idx)
+    # ... the scores are the oracle's within tolerance, and on this input so is the selection
+    ref_scores = oracle.quantise_scores(oracle.importance_scores(_q_f32(w), workloads.bf16_bits_to_f32(w.k),
+                                                                w.cu_seqlens, n_obs=w.n_obs))
+    ok, worst = _score_close(got_scores, ref_scores)
+    assert ok
+    ref_idx, ref_cu = oracle.select_tokens_top_p(ref_scores, w.cu_seqlens, top_p, block_size=w.block_size,
+                                                 n_obs=w.n_obs, n_sink=w.n_sink)
+    _say("  kept", total, "of", T, "worst score error", worst, "same set as the fp64-scored oracle:",
+         bool(np.array_equal(ref_idx, got_idx)))
+    np.testing.assert_array_equal(ref_cu, got_cu)
+    np.testing.assert_array_equal(ref_idx, got_idx)
+    # compaction with the count on the device
+    want_h, want_p = oracle.compact(w.hidden, w.pos, got_idx)
+    np.testing.assert_array_equal(host_bits(hidden_out[:total]), want_h)
+    np.testing.assert_array_equal(pos_out[:total].cpu().numpy(), want_p)
+    assert (hidden_out[total:] == -7.0).all() and (pos_out[total:] == -77).all()
+    assert (b["kept_idx"][total:] == -77).all()

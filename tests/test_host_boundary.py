@@ -154,3 +154,42 @@ def test_device_entries_reject_bad_arguments_before_any_launch():
     assert L.uniprefill_fused(B(p), *args) == up.UP_ERR_WORKSPACE
     args[0] = None
     assert L.uniprefill_fused(B(p), *args) == up.UP_ERR_NULL
+
+
+def test_top_p_entries_reject_bad_arguments_before_any_launch():
+    cu = np.array([0, 1000], np.int32)
+    top_p = np.array([0.9], np.float32)
+    fake, odd = 0x1000, 0x1008
+    p = _params()
+    L = up.lib()
+    B = ctypes.byref
+    v = ctypes.c_void_p
+    big = 1 << 30
+    sel = lambda *a: L.uniprefill_select_top_p(B(p), *a)
+    assert sel(None, v(fake), up.ptr(cu), v(fake), up.ptr(top_p), v(fake), v(fake), v(fake), big, None) == up.UP_ERR_NULL
+    assert sel(v(fake), v(fake), None, v(fake), up.ptr(top_p), v(fake), v(fake), v(fake), big, None) == up.UP_ERR_NULL
+    assert sel(v(fake), v(fake), up.ptr(cu), v(fake), None, v(fake), v(fake), v(fake), big, None) == up.UP_ERR_NULL
+    for bad in [0.0, 1.5, float("nan")]:
+        assert sel(v(fake), v(fake), up.ptr(cu), v(fake), up.ptr(np.array([bad], np.float32)), v(fake), v(fake),
+                   v(fake), big, None) == up.UP_ERR_RANGE
+    assert sel(v(fake), v(fake), up.ptr(cu), v(fake), up.ptr(top_p), v(fake), v(fake), None, 0, None) == up.UP_ERR_WORKSPACE
+    assert sel(v(fake), v(fake), up.ptr(cu), v(fake), up.ptr(top_p), v(fake), v(fake), v(fake), 8, None) == up.UP_ERR_WORKSPACE
+    assert sel(v(fake), v(fake), up.ptr(cu), v(fake), up.ptr(top_p), v(fake), v(fake), v(0x1010), big, None) == up.UP_ERR_ALIGN
+    # a sequence with more blocks than the kernel orders in LDS
+    p_long = _params(total_tokens=32 * 4096 + 1, block_size=32)
+    cu_long = np.array([0, 32 * 4096 + 1], np.int32)
+    assert L.uniprefill_select_top_p(B(p_long), v(fake), v(fake), up.ptr(cu_long), v(fake), up.ptr(top_p), v(fake),
+                                     v(fake), v(fake), big, None) == up.UP_ERR_UNSUPPORTED
+    # compact with the count on the device
+    cc = lambda *a: L.uniprefill_compact_counted(B(p), *a)
+    assert cc(v(fake), None, v(fake), None, 10, v(fake), None, None) == up.UP_ERR_NULL
+    assert cc(v(fake), None, v(fake), v(fake), 1001, v(fake), None, None) == up.UP_ERR_RANGE
+    assert cc(v(fake), None, v(fake), v(fake), -1, v(fake), None, None) == up.UP_ERR_RANGE
+    assert cc(v(odd), None, v(fake), v(fake), 10, v(fake), None, None) == up.UP_ERR_ALIGN
+    assert cc(v(fake), v(fake), v(fake), v(fake), 10, v(fake), None, None) == up.UP_ERR_NULL
+    assert cc(v(fake), None, v(fake), v(fake), 0, v(fake), None, None) == up.UP_OK
+    # fused: every check of the three steps before the first launch
+    args = [v(fake)] * 4 + [v(fake), up.ptr(cu), v(fake), up.ptr(top_p)] + [v(fake)] * 4 + [v(fake), v(fake), 16, None]
+    assert L.uniprefill_fused_top_p(B(p), *args) == up.UP_ERR_WORKSPACE
+    args[12] = None          # the score buffer is required here
+    assert L.uniprefill_fused_top_p(B(p), *args) == up.UP_ERR_NULL
