@@ -154,12 +154,6 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem<NW, F3
     for (int kk = 0; kk < KREG; ++kk)
       kf[kk] = *(const u32x4*)(k_lane + (long long)g * SRCB + kk * (F32 ? 16 : 32));
   };
-  // pulls the two cache lines of the (bf16) key row of head g towards the CU well before
-  // load_keys(g) needs them (the values are only summed so that the loads stay alive)
-  int touched = 0, touch_val = 0;
-  auto touch_keys = [&](int g) {
-    if (!F32) touch_val = *(const int*)(k_lane - half * 16 + (long long)g * 256 + half * 128);
-  };
 
   // ---- staging of one unit of query rows: 2048 pieces of 16 bytes (128 rows x 16), PIECES per
   // thread: column t%16 of rows t/16 + ROWSTEP*i.  Fetched into registers at the start of the
@@ -310,13 +304,21 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem<NW, F3
   // pass 1: merge the waves' statistics of the 128 rows of unit `uc` (tables tb) and write the
   // key block's partial.  Every wave takes 128/NW rows; the NW partials of a row sit two per
   // lane on neighbouring lanes and are reduced with lane permutes in a fixed order.
-  auto merge_unit = [&](const UnitCursor& uc, int tb) {
-    constexpr int RPW = kUnit / NW;      // rows per wave: 8 or 16
-    constexpr int LPR = 64 / RPW;        // lanes per row: 8 or 4  (LPR * 2 == NW)
+  // The two halves (LDS reads; arithmetic and store) are issued a tile apart inside the next
+  // unit's matrix work, where their latency disappears.
+  constexpr int RPW = kUnit / NW;      // rows per wave: 8 or 16
+  constexpr int LPR = 64 / RPW;        // lanes per row: 8 or 4  (LPR * 2 == NW)
+  float2 mp0 = make_float2(0.0f, 0.0f), mp1 = mp0;
+  auto merge_load = [&](int tb) {
     const int row = wave * RPW + lane / LPR;
     const int sub = lane % LPR;
-    const float2 p0 = sm.wstat[tb][sub][row];
-    const float2 p1 = sm.wstat[tb][sub + LPR][row];
+    mp0 = sm.wstat[tb][sub][row];
+    mp1 = sm.wstat[tb][sub + LPR][row];
+  };
+  auto merge_finish = [&](const UnitCursor& uc) {
+    const int row = wave * RPW + lane / LPR;
+    const int sub = lane % LPR;
+    const float2 p0 = mp0, p1 = mp1;
     float mm = fmaxf(p0.x, p1.x);
     mm = fmaxf(mm, dpp<0xB1>(mm));
     mm = fmaxf(mm, dpp<0x4E>(mm));
@@ -334,6 +336,7 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem<NW, F3
   // ---- prologue: unit 0 staged and visible
   UnitCursor cur{g0, 0, 0, 0};     // unit being processed
   UnitCursor nxt = cur;            // unit being staged
+  UnitCursor prev = cur;           // unit whose statistics are still to be merged (pass 1)
   fetch_unit(cur);
   fetch_meta(cur);
   load_keys(g0);
@@ -350,9 +353,12 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem<NW, F3
     // last unit the cursor stays where it is and the loads repeat: the same loads on every path)
     fetch_unit(nxt);
     fetch_meta(nxt);
-    if (head_ends) touch_keys(cur.g + 1);
 #pragma unroll
     for (int rt = 0; rt < 4; ++rt) {
+      // pass 1: the previous unit's statistics are merged in passing (its table slot is free
+      // for unit f+1 only after the barrier below, which every wave reaches after its merge)
+      if (PASS == 1 && f > 0 && rt == 1) merge_load(buf ^ 1);
+      if (PASS == 1 && f > 0 && rt == 2) merge_finish(prev);
       if (!EDGE) {
         tile(std::false_type{}, buf, buf, rt);
       } else {
@@ -381,21 +387,23 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem<NW, F3
       __builtin_amdgcn_sched_barrier(0);
     }
     if (more) { stash_unit(buf ^ 1); stash_meta(buf ^ 1); }
-    touched += touch_val;
     if (head_ends) load_keys(cur.g + 1);                    // this head's last MFMA has been issued
     __syncthreads();     // unit f+1 is visible; every read of unit f's rows and tables has completed
-    if (PASS == 1) merge_unit(cur, buf);                    // next to the other waves' work on unit f+1
+    prev = cur;
     cur = nxt;
     if (f + 2 < n_flat) nxt.advance(n_units, n_eff);
   }
 
+  if (PASS == 1) {   // statistics of the last unit (its barrier has passed)
+    merge_load((n_flat - 1) & 1);
+    merge_finish(prev);
+  }
   if (PASS == 2) {
     // (a barrier has passed since the last read of the staged rows: their space is reused)
     // the two lane halves hold the same keys over different rows: add them (fixed order)
     const double other = __shfl_xor(col64, 32);
     if (half == 0) sm.tail.o64[wave * 32 + l32] = col64 + other;
   }
-  if (touched == 0x7fffffff) sm.rowpos[0][0] = touched;   // never true for real data; keeps the touch loads
 }
 
 template <int PASS, int NW, bool F32>
