@@ -70,13 +70,14 @@ hipError_t launch_compact_counted(const Problem& pb, const void* hidden, const i
                                   void* hidden_out, int32_t* pos_out, hipStream_t s);
 
 // --- scoring (Eq. 2-3)
-// pass 1: softmax statistics of every window row per 256-key block (into the workspace)
+// pass 1: softmax statistics of every window row per key block (into the workspace)
 hipError_t launch_row_stats(const Problem& pb, const void* q, const void* k, const int32_t* cu,
                             void* workspace, hipStream_t s);
 // merge of the per-block statistics into one (reference, 1/sum) per row
 hipError_t launch_merge_stats(const Problem& pb, const int32_t* cu, void* workspace, hipStream_t s);
 // pass 2: normalised weights summed per token; optional scores_out; sel != nullptr runs the
-// block-local top-k (and the gather when sel->hidden is set) in the same kernel
+// block-local top-k (and the gather when sel->hidden is set): in the same kernel when every key
+// block has one work-group, otherwise in k_finish and a gather launch
 // (total_kept: rows the selection keeps, from the closed form; used when the gather runs as a
 // launch of its own)
 hipError_t launch_column_sums(const Problem& pb, const void* q, const void* k, const int32_t* cu,

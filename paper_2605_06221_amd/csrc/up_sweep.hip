@@ -11,24 +11,29 @@
 //           key block; k_combine merges the key blocks of a sequence.
 //   pass 2 (column sums)  S = Q K^T tiles: a lane owns one key and 16 query
 //           rows per tile; it applies each row's final (reference, 1/sum) and
-//           adds the normalised weights.  One wave sees every row of every head
-//           for its keys, so the per-token score is complete inside the wave:
-//           no partial planes, no atomics, fixed summation order.
+//           adds the normalised weights (fp32 inside a tile, fp64 across tiles).
+//           A wave sees every row of every head it sweeps for its keys, so no
+//           atomics are needed and the summation order is fixed.
 //
 // Work decomposition ("key-stationary"): one work-group = 512 or 256 consecutive
 // keys of one sequence, NW = 16 or 8 waves of 32 keys each.  A wave keeps its
 // keys of the current kv head in registers as MFMA operands and sweeps all
 // query rows of that head's GQA group; the rows stream through LDS in units of
 // 128 (coalesced 128-bit loads, padded rows, read back in operand layout),
-// shared by all waves.  Sixteen waves put four on every SIMD: the matrix work
-// of one wave runs next to the vector work (scale, exponential, sums) of the
-// others, which is what hides the latencies -- the program order inside a wave
-// is the plain one (operands, 8 MFMAs, vector work on the 16 results).
-// v_mfma_f32_32x32x16_bf16: bf16 products are exact in fp32 and accumulate in fp32.
+// shared by all waves.  Sixteen waves put four on every SIMD, which covers the
+// LDS, barrier and dependency latencies of one another; the program order
+// inside a wave is the plain one (operands, 8 MFMAs, vector work on the 16
+// results).  v_mfma_f32_32x32x16_bf16: bf16 products are exact in fp32 and
+// accumulate in fp32; fp32 operands take v_mfma_f32_32x32x2_f32.
 //
-// Because a pass-2 work-group ends with the final scores of its consecutive
-// tokens, it owns whole selection blocks (G divides 256) and goes straight on
-// to the block-local top-k and the gather of the kept rows.
+// When a batch has too few key blocks to fill the chip, `split` work-groups
+// share a key block, each sweeping Hkv / split kv heads.  Pass 1 is unaffected
+// (its statistics are per head); pass 2 then leaves partial column sums in the
+// workspace and k_finish adds them, forms the scores and selects.
+//
+// With split == 1 a pass-2 work-group ends with the final scores of its
+// consecutive tokens: it owns whole selection blocks (G divides 256) and goes
+// straight on to the block-local top-k and the gather of the kept rows.
 //
 // Logits are handled in log2 units: x = s_raw * c + negref, c = scale*log2(e),
 // so the exponential is a bare v_exp_f32.
@@ -155,8 +160,8 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem<NW, F3
       kf[kk] = *(const u32x4*)(k_lane + (long long)g * SRCB + kk * (F32 ? 16 : 32));
   };
 
-  // ---- staging of one unit of query rows: 2048 pieces of 16 bytes (128 rows x 16), PIECES per
-  // thread: column t%16 of rows t/16 + ROWSTEP*i.  Fetched into registers at the start of the
+  // ---- staging of one unit of query rows: 128 rows x PPR pieces of 16 bytes, PIECES per thread:
+  // piece t%PPR of rows t/PPR + ROWSTEP*i.  Fetched into registers at the start of the
   // previous unit's matrix work, written to LDS just before the barrier that ends it.
   const int my_row = tid / PPR, my_col = tid % PPR;
   const char* q_seq = a.q + (long long)(c0 + first_q) * a.q_stride_b + my_col * 16;
