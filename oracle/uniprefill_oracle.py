@@ -305,3 +305,22 @@ def select_tokens_top_p(scores_f32, cu_seqlens, top_p, *, block_size, n_obs, n_s
         new_cu[r + 1] = new_cu[r] + len(idx)
     kept_idx = np.concatenate(kept) if kept else np.zeros(0, dtype=np.int32)
     return kept_idx.astype(np.int32), new_cu
+
+
+# --------------------------------------------------------------------------- #
+# index maps across drop layers ("Sparsity Propagation Across All Layers")
+# --------------------------------------------------------------------------- #
+def compose_index(outer_idx, inner_idx):
+    """Index map of two successive drops: inner_idx selects rows of the stream that
+    outer_idx had compacted, so row t of the twice-compacted stream is packed row
+    outer_idx[inner_idx[t]] of the original batch (retained sets are nested: a token
+    dropped at one layer stays out of every later layer)."""
+    outer = np.asarray(outer_idx, dtype=np.int64)
+    inner = np.asarray(inner_idx, dtype=np.int64)
+    return outer[inner].astype(np.int32)
+
+
+def retained_lengths(new_cu_seqlens):
+    """Per-request retained length after a drop (the s_k^r of the drop history used for the
+    per-layer KV length during decode)."""
+    return np.diff(np.asarray(new_cu_seqlens, dtype=np.int64)).astype(np.int32)

@@ -362,3 +362,31 @@ def test_select_tokens_top_p_shape_forced_and_consistency_with_fp64_rule():
             blk = slice(cu[r] + lo, cu[r] + min(N, lo + G))
             if s32[blk].sum() > 0:
                 assert m1[blk].all()
+
+
+# ----------------------------------------------------------------------------- index maps across drop layers
+def test_compose_index_identities_and_two_level_round_trip():
+    rng = np.random.default_rng(11)
+    T, d = 500, 6
+    H = rng.standard_normal((T, d)).astype(np.float32)
+    idx1 = np.sort(rng.choice(T, size=300, replace=False)).astype(np.int32)        # first drop
+    idx2 = np.sort(rng.choice(300, size=120, replace=False)).astype(np.int32)      # second drop, on the compacted stream
+    idx3 = np.sort(rng.choice(120, size=50, replace=False)).astype(np.int32)
+    c12 = oracle.compose_index(idx1, idx2)
+    assert c12.dtype == np.int32 and (np.diff(c12) > 0).all() and set(c12) <= set(idx1)   # nested, still ascending
+    np.testing.assert_array_equal(oracle.compose_index(np.arange(T), idx1), idx1)          # identity on the left
+    np.testing.assert_array_equal(oracle.compose_index(idx1, np.arange(300)), idx1)        # ... and on the right
+    np.testing.assert_array_equal(oracle.compose_index(oracle.compose_index(idx1, idx2), idx3),
+                                  oracle.compose_index(idx1, oracle.compose_index(idx2, idx3)))   # associative
+    # compacting twice == compacting once through the composed map
+    h1, _ = oracle.compact(H, np.arange(T), idx1)
+    h2, _ = oracle.compact(h1, np.arange(300), idx2)
+    h12, _ = oracle.compact(H, np.arange(T), c12)
+    np.testing.assert_array_equal(h2, h12)
+    # reconstitution through two levels == one scatter through the composed map (dropped rows keep their state)
+    new2 = h2 + 1.0
+    lvl1 = oracle.scatter(new2, idx2, h1)
+    full_two_step = oracle.scatter(lvl1, idx1, H)
+    full_direct = oracle.scatter(new2, c12, H)
+    np.testing.assert_array_equal(full_two_step, full_direct)
+    np.testing.assert_array_equal(oracle.retained_lengths([0, 5, 5, 12]), [5, 0, 7])
