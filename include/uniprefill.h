@@ -194,6 +194,20 @@ int uniprefill_fused_top_p(const up_params* p, const void* q, const void* k, con
                            int32_t* kept_idx, int32_t* new_cu_seqlens_dev, float* scores,
                            void* workspace, size_t workspace_bytes, void* stream);
 
+/* Index map of two successive drops ("Sparsity Propagation Across All Layers":
+ * a token dropped at one layer stays out of all later layers, so retained sets
+ * are nested).  outer_idx [n_outer] maps the rows of a compacted stream to packed
+ * rows of the original batch; inner_idx selects rows of that compacted stream
+ * (a second selection run on it); composed_idx[t] = outer_idx[inner_idx[t]] maps
+ * the twice-compacted stream to the original batch, so that one
+ * uniprefill_scatter through composed_idx reconstitutes the full sequence (Eq. 8)
+ * from the innermost stream.  All three device int32.  Entries t < n_inner are
+ * written, or t < n_inner_dev[0] when n_inner_dev is given (then n_inner is the
+ * capacity); inner_idx values must lie in [0, n_outer). */
+int uniprefill_compose_index(const int32_t* outer_idx, int64_t n_outer, const int32_t* inner_idx,
+                             const int32_t* n_inner_dev, int64_t n_inner, int32_t* composed_idx,
+                             void* stream);
+
 /* The kernels behind uniprefill_fused, in stream order.  Measurement aid: a
  * caller that wants to time one kernel enqueues the phases one by one. */
 enum {

@@ -20,7 +20,8 @@ UP_BF16, UP_F32 = 0, 1
 
 EXPORTS = ["uniprefill_plan", "uniprefill_score", "uniprefill_select", "uniprefill_compact",
            "uniprefill_scatter", "uniprefill_fused", "uniprefill_fused_phases", "uniprefill_select_top_p",
-           "uniprefill_compact_counted", "uniprefill_fused_top_p", "uniprefill_status_string"]
+           "uniprefill_compact_counted", "uniprefill_fused_top_p", "uniprefill_compose_index",
+           "uniprefill_status_string"]
 
 UP_PHASE_PLAN, UP_PHASE_ROW_STATS, UP_PHASE_MERGE_STATS, UP_PHASE_SWEEP_SELECT_COMPACT = 1, 2, 4, 8
 UP_PHASE_ALL = 15
@@ -63,6 +64,7 @@ def _load():
     lib.uniprefill_select_top_p.argtypes = [P, f32p, i32p, i32p, f32p, f32p, i32p, i32p, vp, ctypes.c_size_t, vp]
     lib.uniprefill_compact_counted.argtypes = [P, vp, i32p, i32p, i32p, ctypes.c_int64, vp, i32p, vp]
     lib.uniprefill_fused_top_p.argtypes = lib.uniprefill_fused.argtypes
+    lib.uniprefill_compose_index.argtypes = [i32p, ctypes.c_int64, i32p, i32p, ctypes.c_int64, i32p, vp]
     for name in EXPORTS[:-1]:
         getattr(lib, name).restype = ctypes.c_int
     lib.uniprefill_status_string.argtypes = [ctypes.c_int]
@@ -204,3 +206,10 @@ def uniprefill_fused_top_p(p, q, k, hidden, pos, cu_seqlens_dev, cu_seqlens_host
                                      ptr(new_cu_seqlens_dev), ptr(scores), ptr(workspace), workspace_bytes,
                                      _stream(stream))
     return _check(st, "uniprefill_fused_top_p", check)
+
+
+def uniprefill_compose_index(outer_idx, n_outer, inner_idx, n_inner_dev, n_inner, composed_idx, stream=None,
+                             check=True):
+    st = _lib.uniprefill_compose_index(ptr(outer_idx), int(n_outer), ptr(inner_idx), ptr(n_inner_dev),
+                                       int(n_inner), ptr(composed_idx), _stream(stream))
+    return _check(st, "uniprefill_compose_index", check)

@@ -287,6 +287,18 @@ int uniprefill_scatter(const up_params* p, const void* hidden_compact, const int
   return UP_OK;
 }
 
+int uniprefill_compose_index(const int32_t* outer_idx, int64_t n_outer, const int32_t* inner_idx,
+                             const int32_t* n_inner_dev, int64_t n_inner, int32_t* composed_idx,
+                             void* stream) {
+  if (n_outer < 0 || n_inner < 0 || n_inner > n_outer) return UP_ERR_RANGE;
+  if (n_inner == 0) return UP_OK;
+  if (!outer_idx || !inner_idx || !composed_idx) return UP_ERR_NULL;
+  if (launch_compose(outer_idx, inner_idx, n_inner, n_inner_dev, composed_idx, (hipStream_t)stream) !=
+      hipSuccess)
+    return UP_ERR_HIP;
+  return UP_OK;
+}
+
 int uniprefill_fused_phases(const up_params* p, const void* q, const void* k, const void* hidden,
                             const int32_t* pos, const int32_t* cu_seqlens_dev,
                             const int32_t* cu_seqlens_host, const float* keep_ratio_dev,

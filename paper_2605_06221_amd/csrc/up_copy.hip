@@ -30,6 +30,23 @@ __global__ __launch_bounds__(256) void k_rows(const char* __restrict__ src, char
   }
 }
 
+// Index map of two successive drops: out[t] = outer[inner[t]].
+__global__ __launch_bounds__(256) void k_compose(const int32_t* __restrict__ outer,
+                                                 const int32_t* __restrict__ inner, long long n,
+                                                 const int32_t* __restrict__ count_dev,
+                                                 int32_t* __restrict__ out) {
+  const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (t >= (count_dev != nullptr ? (long long)count_dev[0] : n)) return;
+  out[t] = outer[inner[t]];
+}
+
+hipError_t launch_compose(const int32_t* outer, const int32_t* inner, long long n,
+                          const int32_t* count_dev, int32_t* out, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_compose, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, outer, inner, n, count_dev, out);
+  return hipGetLastError();
+}
+
 hipError_t launch_compact(const Problem& pb, const void* hidden, const int32_t* pos,
                           const int32_t* kept_idx, long long total_kept, void* hidden_out,
                           int32_t* pos_out, hipStream_t s) {

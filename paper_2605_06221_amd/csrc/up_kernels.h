@@ -40,6 +40,10 @@ hipError_t launch_compact(const Problem& pb, const void* hidden, const int32_t* 
 hipError_t launch_scatter(const Problem& pb, const void* hidden_compact, const int32_t* kept_idx,
                           long long total_kept, void* hidden_full, hipStream_t s);
 
+// index map of two successive drops: out[t] = outer[inner[t]], t < n (or < count_dev[0] <= n)
+hipError_t launch_compose(const int32_t* outer, const int32_t* inner, long long n,
+                          const int32_t* count_dev, int32_t* out, hipStream_t s);
+
 // --- selection
 hipError_t launch_plan(const Problem& pb, const int32_t* cu, const float* ratio, int32_t* new_cu,
                        hipStream_t s);

@@ -497,3 +497,48 @@ def test_fused_top_p_matches_oracle_end_to_end():
     np.testing.assert_array_equal(pos_out[:total].cpu().numpy(), want_p)
     assert (hidden_out[total:] == -7.0).all() and (pos_out[total:] == -77).all()
     assert (b["kept_idx"][total:] == -77).all()
+
+
+# ----------------------------------------------------------------------------- two drops in a row
+def test_second_drop_on_the_compacted_stream_and_composed_scatter():
+    """Drop twice (top-k, then top-p on the compacted stream), compose the index maps on the device
+    and reconstitute the full batch with one scatter: all bit-exact against the oracle."""
+    _say("two drops")
+    rng = np.random.default_rng(50)
+    w = workloads.make_custom(name="two", seed=15, lengths=[2000, 300, 900], keep_ratio=[0.5, 0.6, 0.4],
+                              hidden_dim=64, num_q_heads=4, num_kv_heads=2, block_size=64, n_obs=128)
+    T = w.total_tokens
+    s1 = rng.random(T).astype(np.float32)
+    idx1, cu1 = oracle.select_tokens(s1, w.cu_seqlens, w.keep_ratio, block_size=64, n_obs=128, n_sink=128)
+    n1 = len(idx1)
+    s2 = (rng.random(n1) ** 8).astype(np.float32)                 # scores of the next drop layer, on the compacted stream
+    top_p = np.array([0.7, 0.9, 0.8], np.float32)
+    idx2, cu2 = oracle.select_tokens_top_p(s2, cu1, top_p, block_size=64, n_obs=128, n_sink=128)
+    want = oracle.compose_index(idx1, idx2)
+    # device: second selection on the compacted geometry (cu1), then the composition with the count on the device
+    p2 = up.make_params(num_seqs=w.num_seqs, total_tokens=n1, block_size=64, n_obs=128, n_sink=128, num_q_heads=4,
+                        num_kv_heads=2, head_dim=128, hidden_dim=64)
+    cu1_host = np.ascontiguousarray(cu1, dtype=np.int32)
+    _, _, _, ws_bytes = up.uniprefill_plan(p2, cu1_host, np.full(3, 0.5, np.float32))
+    workspace = torch.empty(ws_bytes + 256, dtype=torch.uint8, device="cuda")
+    idx1_dev = torch.from_numpy(idx1).cuda()
+    idx2_dev = torch.full((n1,), -1, dtype=torch.int32, device="cuda")
+    cu2_dev = torch.empty(4, dtype=torch.int32, device="cuda")
+    up.uniprefill_select_top_p(p2, torch.from_numpy(s2).cuda(), torch.from_numpy(cu1_host).cuda(), cu1_host,
+                               torch.from_numpy(top_p).cuda(), top_p, idx2_dev, cu2_dev, workspace, ws_bytes)
+    composed = torch.full((n1 + 16,), -77, dtype=torch.int32, device="cuda")
+    up.uniprefill_compose_index(idx1_dev, n1, idx2_dev, cu2_dev[3:], n1, composed)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(cu2_dev.cpu().numpy(), cu2)
+    n2 = int(cu2[-1])
+    np.testing.assert_array_equal(composed[:n2].cpu().numpy(), want)
+    assert (composed[n2:] == -77).all()
+    # reconstitution (Eq. 8) straight from the innermost stream
+    hidden = dev_bf16(w.hidden)
+    inner_rows = torch.from_numpy(rng.standard_normal((n2, 64)).astype(np.float32)).cuda().to(torch.bfloat16)
+    p1 = up.make_params(num_seqs=w.num_seqs, total_tokens=T, block_size=64, hidden_dim=64)
+    full = hidden.clone()
+    up.uniprefill_scatter(p1, inner_rows, composed, n2, full)
+    torch.cuda.synchronize()
+    want_full = oracle.scatter(host_bits(inner_rows), want, w.hidden)
+    np.testing.assert_array_equal(host_bits(full), want_full)

@@ -193,3 +193,11 @@ def test_top_p_entries_reject_bad_arguments_before_any_launch():
     assert L.uniprefill_fused_top_p(B(p), *args) == up.UP_ERR_WORKSPACE
     args[12] = None          # the score buffer is required here
     assert L.uniprefill_fused_top_p(B(p), *args) == up.UP_ERR_NULL
+
+
+def test_compose_index_rejects_bad_arguments():
+    L, v, fake = up.lib(), ctypes.c_void_p, 0x1000
+    assert L.uniprefill_compose_index(None, 10, v(fake), None, 5, v(fake), None) == up.UP_ERR_NULL
+    assert L.uniprefill_compose_index(v(fake), 10, v(fake), None, 11, v(fake), None) == up.UP_ERR_RANGE
+    assert L.uniprefill_compose_index(v(fake), -1, v(fake), None, 0, v(fake), None) == up.UP_ERR_RANGE
+    assert L.uniprefill_compose_index(v(fake), 10, v(fake), None, 0, v(fake), None) == up.UP_OK
