@@ -101,7 +101,9 @@ struct SweepSmem {
     } tail;
   };
   union {
-    float2 wstat[2][NW][kUnit];                        // pass 1: per-wave (reference, sum) per staged row
+    // pass 1: (reference, sum) per staged row from every wave -- from each lane half of every wave
+    // when there is room for it (bf16 operands), which spares the tiles a lane exchange
+    float2 wstat[2][NW * (F32 ? 1 : 2)][kUnit];
     __align__(16) float2 cst[2][kUnit];                // pass 2: (negative reference, 1/sum) per staged row
   };
   __align__(16) int rowpos[2][kUnit];                  // local position of each staged row, -1 = no such row
@@ -275,17 +277,22 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem<NW, F3
         l1 += exp2_hw(fmaf(acc[e + 1], c, negref));
       }
       l0 += l1;                                         // 0 when every key was masked (exp2(-inf))
-      // the other lane half holds the same row over the other 16 keys
-      const float ref_o = __shfl_xor(ref, 32);
-      const float l_o = __shfl_xor(l0, 32);
-      const float mm = fmaxf(ref, ref_o);
-      float s_a = l0 * exp2_hw(ref - mm);
-      float s_b = l_o * exp2_hw(ref_o - mm);
-      if (MASK) {
-        if (ref == -INFINITY) s_a = 0.0f;
-        if (ref_o == -INFINITY) s_b = 0.0f;
+      if (!F32) {
+        // each lane half leaves its own pair (the same row over its 16 keys); the unit merge adds them
+        sm.wstat[tb][2 * wave + half][rt * 32 + l32] = make_float2(ref, l0);
+      } else {
+        // the other lane half holds the same row over the other 16 keys
+        const float ref_o = __shfl_xor(ref, 32);
+        const float l_o = __shfl_xor(l0, 32);
+        const float mm = fmaxf(ref, ref_o);
+        float s_a = l0 * exp2_hw(ref - mm);
+        float s_b = l_o * exp2_hw(ref_o - mm);
+        if (MASK) {
+          if (ref == -INFINITY) s_a = 0.0f;
+          if (ref_o == -INFINITY) s_b = 0.0f;
+        }
+        if (half == 0) sm.wstat[tb][wave][rt * 32 + l32] = make_float2(mm, s_a + s_b);
       }
-      if (half == 0) sm.wstat[tb][wave][rt * 32 + l32] = make_float2(mm, s_a + s_b);
     } else {
       // element e = query row rt*32 + 8*(e/4) + 4*half + e%4, key l32
       float cs0 = 0.0f, cs1 = 0.0f;
@@ -306,30 +313,35 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem<NW, F3
     }
   };
 
-  // pass 1: merge the waves' statistics of the 128 rows of unit `uc` (tables tb) and write the
-  // key block's partial.  Every wave takes 128/NW rows; the NW partials of a row sit two per
-  // lane on neighbouring lanes and are reduced with lane permutes in a fixed order.
-  // The two halves (LDS reads; arithmetic and store) are issued a tile apart inside the next
-  // unit's matrix work, where their latency disappears.
-  constexpr int RPW = kUnit / NW;      // rows per wave: 8 or 16
-  constexpr int LPR = 64 / RPW;        // lanes per row: 8 or 4  (LPR * 2 == NW)
-  float2 mp0 = make_float2(0.0f, 0.0f), mp1 = mp0;
+  // pass 1: merge the statistics of the 128 rows of unit `uc` (tables tb) and write the key
+  // block's partial.  Every wave takes 128/NW rows; the partials of a row (one per wave, or one per
+  // lane half of every wave) sit PPL per lane on neighbouring lanes and are reduced with lane
+  // permutes in a fixed order.  The two halves (LDS reads; arithmetic and store) are issued a tile
+  // apart inside the next unit's matrix work, where their latency disappears.
+  constexpr int RPW = kUnit / NW;                 // rows per wave: 8 or 16
+  constexpr int LPR = 64 / RPW;                   // lanes per row: 8 or 4
+  constexpr int PPL = (F32 ? NW : 2 * NW) / LPR;  // partials per lane: 2 or 4
+  float2 mp[PPL];
+#pragma unroll
+  for (int i = 0; i < PPL; ++i) mp[i] = make_float2(0.0f, 0.0f);
   auto merge_load = [&](int tb) {
     const int row = wave * RPW + lane / LPR;
     const int sub = lane % LPR;
-    mp0 = sm.wstat[tb][sub][row];
-    mp1 = sm.wstat[tb][sub + LPR][row];
+#pragma unroll
+    for (int i = 0; i < PPL; ++i) mp[i] = sm.wstat[tb][sub + LPR * i][row];
   };
   auto merge_finish = [&](const UnitCursor& uc) {
     const int row = wave * RPW + lane / LPR;
     const int sub = lane % LPR;
-    const float2 p0 = mp0, p1 = mp1;
-    float mm = fmaxf(p0.x, p1.x);
+    float mm = mp[0].x;
+#pragma unroll
+    for (int i = 1; i < PPL; ++i) mm = fmaxf(mm, mp[i].x);
     mm = fmaxf(mm, dpp<0xB1>(mm));
     mm = fmaxf(mm, dpp<0x4E>(mm));
     if (LPR == 8) mm = fmaxf(mm, dpp<0x141>(mm));
-    float l = (p0.x == -INFINITY ? 0.0f : p0.y * exp2_hw(p0.x - mm)) +
-              (p1.x == -INFINITY ? 0.0f : p1.y * exp2_hw(p1.x - mm));
+    float l = 0.0f;
+#pragma unroll
+    for (int i = 0; i < PPL; ++i) l += mp[i].x == -INFINITY ? 0.0f : mp[i].y * exp2_hw(mp[i].x - mm);
     l += dpp<0xB1>(l);
     l += dpp<0x4E>(l);
     if (LPR == 8) l += dpp<0x141>(l);
@@ -379,7 +391,10 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem<NW, F3
           mixed = key_base + 31 > first_q;
         }
         if (none) {
-          if (PASS == 1 && half == 0) sm.wstat[buf][wave][rt * 32 + l32] = make_float2(-INFINITY, 0.0f);
+          if (PASS == 1) {
+            if (!F32) sm.wstat[buf][2 * wave + half][rt * 32 + l32] = make_float2(-INFINITY, 0.0f);
+            else if (half == 0) sm.wstat[buf][wave][rt * 32 + l32] = make_float2(-INFINITY, 0.0f);
+          }
         } else if (mixed) {
           tile(std::true_type{}, buf, buf, rt);
         } else {
