@@ -542,3 +542,27 @@ def test_second_drop_on_the_compacted_stream_and_composed_scatter():
     torch.cuda.synchronize()
     want_full = oracle.scatter(host_bits(inner_rows), want, w.hidden)
     np.testing.assert_array_equal(host_bits(full), want_full)
+
+
+# ----------------------------------------------------------------------------- seeded random geometries
+@pytest.mark.parametrize("seed", range(10))
+def test_fused_random_geometries_bit_exact(seed):
+    """Random batch shapes, head layouts, block sizes, window and sink sizes: the launch geometry
+    (key-block size, head split, edge classes) must never show in the result."""
+    rng = np.random.default_rng(1000 + seed)
+    R = int(rng.integers(1, 9))
+    lengths = [int(x) for x in rng.choice([0, 1, 17, 64, 129, 300, 512, 777, 1500, 2600, 4100], size=R)]
+    if sum(lengths) == 0:
+        lengths[0] = 333
+    Hkv = int(rng.choice([1, 2, 4, 8]))
+    Hq = Hkv * int(rng.choice([1, 2, 4, 5]))
+    G = int(rng.choice([32, 64, 128]))
+    n_obs = int(rng.choice([16, 100, 128, 256, 384]))
+    n_sink = int(rng.choice([0, 4, 128, 200]))
+    ratios = [float(x) for x in rng.uniform(0.05, 1.0, size=R)]
+    _say("random geometry", seed, dict(lengths=lengths, Hq=Hq, Hkv=Hkv, G=G, n_obs=n_obs, n_sink=n_sink))
+    w = workloads.make_custom(name=f"rnd{seed}", seed=2000 + seed, lengths=lengths, keep_ratio=ratios, hidden_dim=32,
+                              num_q_heads=Hq, num_kv_heads=Hkv, block_size=G, n_obs=n_obs, n_sink=n_sink)
+    b = DeviceBatch(w)
+    b.fused()
+    _assert_fused_exact(w, b, oracle_run(w))
