@@ -284,6 +284,10 @@ def main():
         "algorithmic_bytes": int(alg_bytes),
         "hbm_frac_fused": round(alg_bytes / (elapsed / args.steps) / 1e9 / HBM_PEAK_GBS, 4),
         "product_flops_per_pass": int(flops),
+        # the larger of (algorithmic bytes at HBM peak, the two product passes at the dense bf16 MFMA
+        # peak) over the measured step time
+        "binding_roofline_frac": round(max(alg_bytes / (HBM_PEAK_GBS * 1e9), 2.0 * flops / (MFMA_BF16_PEAK_TFLOPS * 1e12))
+                                       / (elapsed / args.steps), 4),
         "roofline": roofline,
         "kernels": kernels,
         "entry_points": entry_points,
