@@ -125,13 +125,20 @@ def main():
     for i in range(args.warmup):
         up.uniprefill_fused(*call_args(i), stream=stream)
     torch.cuda.synchronize()
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     t_start = time.perf_counter()
+    marks[0].record(stream)
     for i in range(args.steps):
         up.uniprefill_fused(*call_args(args.warmup + i), stream=stream)
+        marks[i + 1].record(stream)      # spread of the single steps (the headline is the wall clock below)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
     ms_per_step = elapsed / args.steps * 1e3
     tokens_per_s = w.total_tokens / (elapsed / args.steps)
+
+    per_step_us = sorted(marks[i].elapsed_time(marks[i + 1]) * 1e3 for i in range(args.steps))
+    pick = lambda f: round(per_step_us[min(len(per_step_us) - 1, int(f * len(per_step_us)))], 2)
+    step_us = {"median": pick(0.5), "p10": pick(0.1), "p90": pick(0.9)}
 
     alg_bytes = algorithmic_bytes(w, total_kept)
     flops = product_flops(w)
@@ -272,6 +279,7 @@ def main():
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4),
+        "step_us": step_us,
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
