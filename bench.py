@@ -76,7 +76,10 @@ def main():
     import numpy as np
     import torch
 
-    import paper_2605_06221_amd as up      # fails loudly if the HIP library is missing
+    if not os.path.exists(os.path.join(ROOT, "paper_2605_06221_amd", "libuniprefill.so")):
+        import __graft_entry__              # nothing built yet: build, never fall back
+        __graft_entry__.build()
+    import paper_2605_06221_amd as up      # fails loudly if the HIP library is missing or broken
     import workloads
 
     if not torch.cuda.is_available():

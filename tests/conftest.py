@@ -10,6 +10,10 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run on the GPU box)")
+    # the tests load the library that is built; only when none is there do they build it
+    if not os.path.exists(os.path.join(ROOT, "paper_2605_06221_amd", "libuniprefill.so")):
+        import __graft_entry__
+        __graft_entry__.build()
 
 
 def pytest_collection_modifyitems(config, items):
