@@ -28,7 +28,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 # what the same counter reads for an identity gather of known size in the same run; the summaries
 # with the commands are under profiles/.  Keyed by (workload, kernel); absent = not measured.
 MEASURED_TRAFFIC_BYTES = {
-    ("c4_128k_d5120_h40x8_G128_r0.25_heavytail", "sweep_select_compact"): 952340522,
+    ("c4_128k_d5120_h40x8_G128_r0.25_heavytail", "sweep_select"): None,
     ("c4_128k_d5120_h40x8_G128_r0.25_heavytail", "row_stats"): 299147116,
 }
 
@@ -149,7 +149,7 @@ def main():
     # ---- per-kernel durations: the same five launches, each bracketed by events on the stream
     phases = [("plan", up.UP_PHASE_PLAN), ("row_stats", up.UP_PHASE_ROW_STATS),
               ("merge_stats", up.UP_PHASE_MERGE_STATS),
-              ("sweep_select_compact", up.UP_PHASE_SWEEP_SELECT_COMPACT)]
+              ("sweep_select", up.UP_PHASE_SWEEP_SELECT), ("gather", up.UP_PHASE_GATHER)]
     kernels = {}
     if not args.no_phases:
         acc = {name: 0.0 for name, _ in phases}
@@ -162,17 +162,23 @@ def main():
             torch.cuda.synchronize()
             for i, (name, _) in enumerate(phases):
                 acc[name] += evs[i].elapsed_time(evs[i + 1])
-        kept_bytes = total_kept * (2 * w.hidden_dim * 2 + 12) + w.total_tokens * 4
+        gather_only_bytes = total_kept * (2 * w.hidden_dim * 2 + 12)      # rows in and out, pos in/out, index
+        score_bytes = w.total_tokens * 4 + total_kept * 4
         k_bytes = w.total_tokens * w.num_kv_heads * w.head_dim * 2
         for name, _ in phases:
             us = acc[name] / args.steps * 1e3
             ent = {"avg_us": round(us, 2)}
-            if name in ("row_stats", "sweep_select_compact"):
+            if name in ("row_stats", "sweep_select"):
+                # one Q.K^T pass each: the product's flops against the dense bf16 MFMA peak, and the
+                # bytes the pass has to move (K once; pass 2 also the scores and kept ids)
                 ent.update(bound="mfma", tflops=round(flops / (us * 1e-6) / 1e12, 1),
                            frac_mfma=round(flops / (us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4))
-                moved = k_bytes + (kept_bytes if name == "sweep_select_compact" else 0)
+                moved = k_bytes + (score_bytes if name == "sweep_select" else 0)
                 ent.update(gbs=round(moved / (us * 1e-6) / 1e9, 1),
                            frac_hbm=round(moved / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4))
+            if name == "gather":
+                ent.update(bound="hbm", gbs=round(gather_only_bytes / (us * 1e-6) / 1e9, 1),
+                           frac_hbm=round(gather_only_bytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4))
             kernels[name] = ent
         # the dominant kernel against the roofline it gets closest to (its algorithmic bytes
         # against HBM peak, or its product flops against the dense bf16 MFMA peak)

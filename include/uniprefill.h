@@ -214,9 +214,10 @@ enum {
   UP_PHASE_PLAN = 1,                 /* new_cu_seqlens_dev */
   UP_PHASE_ROW_STATS = 2,            /* pass 1 of the two-pass softmax: row statistics per key block */
   UP_PHASE_MERGE_STATS = 4,          /* merge of the per-block statistics */
-  UP_PHASE_SWEEP_SELECT_COMPACT = 8, /* pass 2 (normalised weights summed per token), block-local
-                                        top-k and gather of the kept rows, one kernel */
-  UP_PHASE_ALL = 15
+  UP_PHASE_SWEEP_SELECT = 8,         /* pass 2 (normalised weights summed per token) with the
+                                        block-local top-k: scores, kept_idx */
+  UP_PHASE_GATHER = 16,              /* gather of the kept rows and position ids */
+  UP_PHASE_ALL = 31
 };
 
 
@@ -224,7 +225,7 @@ enum {
  * same checks; UP_ERR_RANGE for unknown bits).  A phase reads what the earlier
  * phases left in the workspace and outputs, so the phases of one call sequence
  * must be enqueued in order on one stream with unchanged arguments; enqueuing
- * all four one by one is exactly uniprefill_fused. */
+ * all five one by one is exactly uniprefill_fused. */
 int uniprefill_fused_phases(const up_params* p, const void* q, const void* k, const void* hidden,
                             const int32_t* pos, const int32_t* cu_seqlens_dev,
                             const int32_t* cu_seqlens_host, const float* keep_ratio_dev,

@@ -23,8 +23,8 @@ EXPORTS = ["uniprefill_plan", "uniprefill_score", "uniprefill_select", "uniprefi
            "uniprefill_compact_counted", "uniprefill_fused_top_p", "uniprefill_compose_index",
            "uniprefill_status_string"]
 
-UP_PHASE_PLAN, UP_PHASE_ROW_STATS, UP_PHASE_MERGE_STATS, UP_PHASE_SWEEP_SELECT_COMPACT = 1, 2, 4, 8
-UP_PHASE_ALL = 15
+UP_PHASE_PLAN, UP_PHASE_ROW_STATS, UP_PHASE_MERGE_STATS, UP_PHASE_SWEEP_SELECT, UP_PHASE_GATHER = 1, 2, 4, 8, 16
+UP_PHASE_ALL = 31
 
 
 class up_params(ctypes.Structure):

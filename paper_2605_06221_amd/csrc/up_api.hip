@@ -160,7 +160,7 @@ int uniprefill_score(const up_params* p, const void* q, const void* k, const int
   hipStream_t s = (hipStream_t)stream;
   if (launch_row_stats(pb, q, k, cu_seqlens_dev, workspace, s) != hipSuccess) return UP_ERR_HIP;
   if (launch_merge_stats(pb, cu_seqlens_dev, workspace, s) != hipSuccess) return UP_ERR_HIP;
-  if (launch_column_sums(pb, q, k, cu_seqlens_dev, workspace, scores_out, nullptr, 0, s) != hipSuccess)
+  if (launch_column_sums(pb, q, k, cu_seqlens_dev, workspace, scores_out, nullptr, s) != hipSuccess)
     return UP_ERR_HIP;
   return UP_OK;
 }
@@ -180,7 +180,7 @@ int uniprefill_select(const up_params* p, const float* scores, const int32_t* cu
   if (launch_plan(pb, cu_seqlens_dev, keep_ratio_dev, new_cu_seqlens_dev, s) != hipSuccess)
     return UP_ERR_HIP;
   const SelectArgs sa = make_select_args(pb, scores, cu_seqlens_dev, keep_ratio_dev, new_cu_seqlens_dev,
-                                         kept_idx, nullptr, nullptr, nullptr, nullptr);
+                                         kept_idx);
   if (launch_select(pb, sa, s) != hipSuccess) return UP_ERR_HIP;
   return UP_OK;
 }
@@ -331,12 +331,17 @@ int uniprefill_fused_phases(const up_params* p, const void* q, const void* k, co
   if ((phase_mask & UP_PHASE_MERGE_STATS) &&
       launch_merge_stats(pb, cu_seqlens_dev, workspace, s) != hipSuccess)
     return UP_ERR_HIP;
-  if (phase_mask & UP_PHASE_SWEEP_SELECT_COMPACT) {
+  if (phase_mask & UP_PHASE_SWEEP_SELECT) {
     const SelectArgs sa = make_select_args(pb, nullptr, cu_seqlens_dev, keep_ratio_dev,
-                                           new_cu_seqlens_dev, kept_idx, hidden, pos, hidden_out,
-                                           pos_out);
+                                           new_cu_seqlens_dev, kept_idx);
+    if (launch_column_sums(pb, q, k, cu_seqlens_dev, workspace, scores_out, &sa, s) != hipSuccess)
+      return UP_ERR_HIP;
+  }
+  if (phase_mask & UP_PHASE_GATHER) {
+    // one wave per kept row: measured faster than gathering inside the scoring kernel, whose
+    // work-groups all reach their gather at the same moment
     const long long total_kept = host_total_kept(pb, cu_seqlens_host, keep_ratio_host, nullptr);
-    if (launch_column_sums(pb, q, k, cu_seqlens_dev, workspace, scores_out, &sa, total_kept, s) != hipSuccess)
+    if (launch_compact(pb, hidden, pos, kept_idx, total_kept, hidden_out, pos_out, s) != hipSuccess)
       return UP_ERR_HIP;
   }
   return UP_OK;

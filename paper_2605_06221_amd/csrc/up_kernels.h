@@ -48,8 +48,7 @@ hipError_t launch_compose(const int32_t* outer, const int32_t* inner, long long 
 hipError_t launch_plan(const Problem& pb, const int32_t* cu, const float* ratio, int32_t* new_cu,
                        hipStream_t s);
 SelectArgs make_select_args(const Problem& pb, const float* scores, const int32_t* cu, const float* ratio,
-                            const int32_t* new_cu, int32_t* kept_idx, const void* hidden,
-                            const int32_t* pos, void* hidden_out, int32_t* pos_out);
+                            const int32_t* new_cu, int32_t* kept_idx);
 hipError_t launch_select(const Problem& pb, const SelectArgs& a, hipStream_t s);
 
 // --- block-level top-p selection (Eq. 4-6); kept_idx needs room for T entries
@@ -80,12 +79,9 @@ hipError_t launch_row_stats(const Problem& pb, const void* q, const void* k, con
 // merge of the per-block statistics into one (reference, 1/sum) per row
 hipError_t launch_merge_stats(const Problem& pb, const int32_t* cu, void* workspace, hipStream_t s);
 // pass 2: normalised weights summed per token; optional scores_out; sel != nullptr runs the
-// block-local top-k (and the gather when sel->hidden is set): in the same kernel when every key
-// block has one work-group, otherwise in k_finish and a gather launch
-// (total_kept: rows the selection keeps, from the closed form; used when the gather runs as a
-// launch of its own)
+// block-local top-k (in the same kernel when every key block has one work-group, otherwise in
+// k_finish)
 hipError_t launch_column_sums(const Problem& pb, const void* q, const void* k, const int32_t* cu,
-                              void* workspace, float* scores_out, const SelectArgs* sel,
-                              long long total_kept, hipStream_t s);
+                              void* workspace, float* scores_out, const SelectArgs* sel, hipStream_t s);
 
 }  // namespace up

@@ -1,6 +1,6 @@
-// Block-local top-k selection with forced retention, and the gather of the kept
-// rows: device code shared by the stand-alone selection kernel and the fused
-// score+select+compact kernel.
+// Block-local top-k selection with forced retention (device code shared by the
+// stand-alone selection kernel and the scoring kernels that go on to select),
+// and the row copy of the gather / scatter kernels.
 //
 // One selection block is G <= 128 consecutive tokens of one sequence.  Each
 // token builds the 64-bit ordering key of Eq. 14 -- the order-preserving
@@ -25,17 +25,11 @@ struct SelectArgs {
   const float* ratio;
   const int32_t* new_cu;
   int32_t* kept_idx;
-  const char* hidden;       // nullptr => selection only
-  const int32_t* pos;
-  char* hidden_out;
-  int32_t* pos_out;
-  long long row_bytes, stride_bytes;
   int R, T, G, n_obs, n_sink;
 };
 
 struct SelectSmem {
   unsigned long long keys[128];
-  int kept_local[128];
   float score[kMaxKeyBlock];
   int cnt0, base;
 };
@@ -73,7 +67,7 @@ __device__ __forceinline__ void copy_row_wave(const char* __restrict__ src, char
   else copy_row_rounds<16>(src, dst, row_bytes, lane);
 }
 
-// Select (and, if a.hidden is set, gather) block g of sequence r.  Called by all
+// Select block g of sequence r: writes the kept packed row ids, ascending.  Called by all
 // threads of the work-group (at least 128; whole waves); `block_scores` points at the block's scores
 // (LDS or global), indexed by the token's position inside the block.
 __device__ __forceinline__ void select_block(const SelectArgs& a, SelectSmem& sm, int r, int c0, int N,
@@ -109,22 +103,7 @@ __device__ __forceinline__ void select_block(const SelectArgs& a, SelectSmem& sm
   const int before = __popcll(bal & ((1ull << lane) - 1ull));
   if (wave == 0 && lane == 0) sm.cnt0 = __popcll(bal);
   __syncthreads();
-  const int base = sm.base;
-  if (keep) {
-    const int at = before + (wave == 1 ? sm.cnt0 : 0);
-    sm.kept_local[at] = tid;
-    a.kept_idx[base + at] = c0 + lo + tid;
-  }
-  __syncthreads();
-  if (a.hidden != nullptr) {
-    const int n_waves = blockDim.x >> 6;
-    for (int j = wave; j < kg; j += n_waves) {
-      const long long srow = c0 + lo + sm.kept_local[j];
-      copy_row_wave(a.hidden + srow * a.stride_bytes, a.hidden_out + (long long)(base + j) * a.stride_bytes,
-                    a.row_bytes, lane);
-    }
-    if (a.pos != nullptr && tid < kg) a.pos_out[base + tid] = a.pos[c0 + lo + sm.kept_local[tid]];
-  }
+  if (keep) a.kept_idx[sm.base + before + (wave == 1 ? sm.cnt0 : 0)] = c0 + lo + tid;
   __syncthreads();   // the shared arrays are reused by the next block
 }
 

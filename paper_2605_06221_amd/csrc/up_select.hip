@@ -54,13 +54,9 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
 }
 
 SelectArgs make_select_args(const Problem& pb, const float* scores, const int32_t* cu, const float* ratio,
-                            const int32_t* new_cu, int32_t* kept_idx, const void* hidden,
-                            const int32_t* pos, void* hidden_out, int32_t* pos_out) {
+                            const int32_t* new_cu, int32_t* kept_idx) {
   SelectArgs a;
   a.scores = scores; a.cu = cu; a.ratio = ratio; a.new_cu = new_cu; a.kept_idx = kept_idx;
-  a.hidden = (const char*)hidden; a.pos = pos; a.hidden_out = (char*)hidden_out; a.pos_out = pos_out;
-  a.row_bytes = (long long)pb.d * pb.hidden_elem_bytes;
-  a.stride_bytes = pb.h_stride * pb.hidden_elem_bytes;
   a.R = pb.R; a.T = pb.T; a.G = pb.G; a.n_obs = pb.n_obs; a.n_sink = pb.n_sink;
   return a;
 }

@@ -1,5 +1,5 @@
-// Token-importance scoring (Eq. 2-3) on the gfx950 matrix cores, and the fused
-// score -> select -> compact kernel.
+// Token-importance scoring (Eq. 2-3) on the gfx950 matrix cores, with the
+// block-local selection attached to the second pass.
 //
 // The softmax of a query row is normalised over *all* visible keys, so the
 // Q.K^T product runs twice:
@@ -33,7 +33,8 @@
 //
 // With split == 1 a pass-2 work-group ends with the final scores of its
 // consecutive tokens: it owns whole selection blocks (G divides 256) and goes
-// straight on to the block-local top-k and the gather of the kept rows.
+// straight on to their block-local top-k.  The gather of the kept rows is a
+// launch of its own.
 //
 // Logits are handled in log2 units: x = s_raw * c + negref, c = scale*log2(e),
 // so the exponential is a bare v_exp_f32.
@@ -65,7 +66,7 @@ struct SweepArgs {
   float c;             // scale * log2(e)
   int R, T, Hq, Hkv, Gq, n_obs, row_slots;
   int split;           // work-groups per key block; each sweeps Hkv / split kv heads
-  int do_select;       // pass 2: run the block-local top-k (+ gather if sel.hidden != nullptr)
+  int do_select;       // pass 2: run the block-local top-k
   SelectArgs sel;
 };
 
@@ -464,7 +465,7 @@ __global__ __launch_bounds__(64 * NW) void k_sweep(SweepArgs a) {
     }
     if (!a.do_select) return;
     __syncthreads();
-    // the block-local top-k and the gather, one selection block after the other
+    // the block-local top-k, one selection block after the other
     const int G = a.sel.G;
     const int nb = imin(KB / G, ceil_div(N - kblock * KB, G));
     for (int b = 0; b < nb; ++b)
@@ -474,8 +475,7 @@ __global__ __launch_bounds__(64 * NW) void k_sweep(SweepArgs a) {
 
 // When the kv heads of a key block were shared by several work-groups (split > 1): one
 // work-group per selection block adds the parts' column sums in a fixed order, forms the
-// scores (mean, floor) and runs the block-local top-k; the gather follows as a launch of
-// its own (one wave per kept row fills the chip, four waves per block would not).
+// scores (mean, floor) and runs the block-local top-k.
 __global__ __launch_bounds__(256) void k_finish(SweepArgs a, int key_block) {
   __shared__ SelectSmem sm;
   const int G = a.sel.G;
@@ -645,27 +645,22 @@ hipError_t launch_merge_stats(const Problem& pb, const int32_t* cu, void* worksp
 }
 
 hipError_t launch_column_sums(const Problem& pb, const void* q, const void* k, const int32_t* cu,
-                              void* workspace, float* scores_out, const SelectArgs* sel,
-                              long long total_kept, hipStream_t s) {
+                              void* workspace, float* scores_out, const SelectArgs* sel, hipStream_t s) {
   if (pb.T == 0) return hipSuccess;
   SweepArgs a = make_sweep_args(pb, q, k, cu, workspace);
   a.scores_out = scores_out;
   if (sel != nullptr) { a.sel = *sel; a.do_select = 1; }
   else { a.sel.G = pb.G; }
-  const bool gather_apart = pb.split > 1 && sel != nullptr && sel->hidden != nullptr;
-  if (gather_apart) a.sel.hidden = nullptr;     // k_finish selects only
+  const dim3 grid((unsigned)(pb.key_block_slots * pb.split));
   if (pb.qk_is_f32)
-    hipLaunchKernelGGL((k_sweep<2, 8, true>), dim3((unsigned)(pb.key_block_slots * pb.split)), dim3(512), 0, s, a);
+    hipLaunchKernelGGL((k_sweep<2, 8, true>), grid, dim3(512), 0, s, a);
   else if (pb.key_block == 512)
-    hipLaunchKernelGGL((k_sweep<2, 16, false>), dim3((unsigned)(pb.key_block_slots * pb.split)), dim3(1024), 0, s, a);
+    hipLaunchKernelGGL((k_sweep<2, 16, false>), grid, dim3(1024), 0, s, a);
   else
-    hipLaunchKernelGGL((k_sweep<2, 8, false>), dim3((unsigned)(pb.key_block_slots * pb.split)), dim3(512), 0, s, a);
+    hipLaunchKernelGGL((k_sweep<2, 8, false>), grid, dim3(512), 0, s, a);
   if (pb.split > 1)
     hipLaunchKernelGGL(k_finish, dim3((unsigned)(pb.T / pb.G + pb.R)), dim3(256), 0, s, a, pb.key_block);
-  if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
-  if (gather_apart)
-    return launch_compact(pb, sel->hidden, sel->pos, sel->kept_idx, total_kept, sel->hidden_out, sel->pos_out, s);
-  return hipSuccess;
+  return hipGetLastError();
 }
 
 }  // namespace up

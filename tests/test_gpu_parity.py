@@ -566,3 +566,27 @@ def test_fused_random_geometries_bit_exact(seed):
     b = DeviceBatch(w)
     b.fused()
     _assert_fused_exact(w, b, oracle_run(w))
+
+
+# ----------------------------------------------------------------------------- the fused call, phase by phase
+@pytest.mark.parametrize("lengths", [[3000, 40, 777], [40000]])
+def test_fused_phases_one_by_one_equal_the_fused_call(lengths):
+    """Enqueuing the five phases separately is exactly uniprefill_fused (both launch geometries:
+    shared key blocks for the small batch, one work-group per key block for the long sequence)."""
+    _say("phases", lengths)
+    w = workloads.make_custom(name="ph", seed=16, lengths=lengths, keep_ratio=[0.3] * len(lengths), hidden_dim=64,
+                              num_q_heads=4, num_kv_heads=2, block_size=64, n_obs=128)
+    a = DeviceBatch(w)
+    a.fused()
+    want = a.results()
+    b = DeviceBatch(w)
+    args = (b.p, b.q, b.k, b.hidden, b.pos, b.cu, b.cu_host, b.ratio, b.ratio_host, b.hidden_out, b.pos_out,
+            b.kept_idx, b.new_cu, b.scores, b.workspace, b.ws_bytes)
+    for mask in (up.UP_PHASE_PLAN, up.UP_PHASE_ROW_STATS, up.UP_PHASE_MERGE_STATS, up.UP_PHASE_SWEEP_SELECT,
+                 up.UP_PHASE_GATHER):
+        up.uniprefill_fused_phases(*args, mask)
+    got = b.results()
+    for key in want:
+        np.testing.assert_array_equal(got[key], want[key], err_msg=key)
+    assert b.canaries_intact()
+    assert up.uniprefill_fused_phases(*args, 64, check=False) == up.UP_ERR_RANGE
