@@ -28,8 +28,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 # what the same counter reads for an identity gather of known size in the same run; the summaries
 # with the commands are under profiles/.  Keyed by (workload, kernel); absent = not measured.
 MEASURED_TRAFFIC_BYTES = {
-    ("c4_128k_d5120_h40x8_G128_r0.25_heavytail", "sweep_select"): None,
-    ("c4_128k_d5120_h40x8_G128_r0.25_heavytail", "row_stats"): 299147116,
+    ("c4_128k_d5120_h40x8_G128_r0.25_heavytail", "sweep_select"): 278641119,
+    ("c4_128k_d5120_h40x8_G128_r0.25_heavytail", "gather"): 675674297,
+    ("c4_128k_d5120_h40x8_G128_r0.25_heavytail", "row_stats"): 299183924,
 }
 
 
