@@ -1,6 +1,5 @@
 // Block-local top-k selection with forced retention (device code shared by the
-// stand-alone selection kernel and the scoring kernels that go on to select),
-// and the row copy of the gather / scatter kernels.
+// stand-alone selection kernel and the scoring kernels that go on to select).
 //
 // One selection block is G <= 128 consecutive tokens of one sequence.  Each
 // token builds the 64-bit ordering key of Eq. 14 -- the order-preserving
@@ -38,33 +37,6 @@ struct SelectSmem {
 __device__ __forceinline__ unsigned phi(float x) {
   const unsigned b = __float_as_uint(x);
   return (b & 0x80000000u) ? ~b : (b ^ 0x80000000u);
-}
-
-// One wave copies one row with 128-bit non-temporal accesses.  All loads of a round are issued
-// before the first store; the round length is matched to the row (rows of up to 16 KB move in one
-// round trip), which is worth a few percent of the gather's bandwidth over a fixed short round.
-template <int U>
-__device__ __forceinline__ void copy_row_rounds(const char* __restrict__ src, char* __restrict__ dst,
-                                                long long row_bytes, int lane) {
-  for (long long off = (long long)lane * 16; off < row_bytes; off += U * 1024) {
-    u32x4 v[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u)
-      if (off + u * 1024 < row_bytes) v[u] = __builtin_nontemporal_load((const u32x4*)(src + off + u * 1024));
-#pragma unroll
-    for (int u = 0; u < U; ++u)
-      if (off + u * 1024 < row_bytes) __builtin_nontemporal_store(v[u], (u32x4*)(dst + off + u * 1024));
-  }
-}
-
-__device__ __forceinline__ void copy_row_wave(const char* __restrict__ src, char* __restrict__ dst,
-                                              long long row_bytes, int lane) {
-  const long long chunks = (row_bytes + 1023) >> 10;     // the same for every lane of the wave
-  if (chunks <= 4) copy_row_rounds<4>(src, dst, row_bytes, lane);
-  else if (chunks <= 8) copy_row_rounds<8>(src, dst, row_bytes, lane);
-  else if (chunks <= 10) copy_row_rounds<10>(src, dst, row_bytes, lane);
-  else if (chunks <= 12) copy_row_rounds<12>(src, dst, row_bytes, lane);
-  else copy_row_rounds<16>(src, dst, row_bytes, lane);
 }
 
 // Select block g of sequence r: writes the kept packed row ids, ascending.  Called by all
