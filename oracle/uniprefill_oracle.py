@@ -324,3 +324,28 @@ def retained_lengths(new_cu_seqlens):
     """Per-request retained length after a drop (the s_k^r of the drop history used for the
     per-layer KV length during decode)."""
     return np.diff(np.asarray(new_cu_seqlens, dtype=np.int64)).astype(np.int32)
+
+
+# --------------------------------------------------------------------------- #
+# serving-side metadata of a compacted stream ("vLLM scheduler integration")
+# --------------------------------------------------------------------------- #
+def kv_slot_mapping(pos_kept, new_cu_seqlens, block_table, kv_block_size):
+    """Physical KV-cache slot of every retained token (Eq. 16): token i of request r at
+    logical position p goes to block_table[r, p // B] * B + p % B."""
+    pos = np.asarray(pos_kept, dtype=np.int64)
+    cu = np.asarray(new_cu_seqlens, dtype=np.int64)
+    bt = np.asarray(block_table, dtype=np.int64)
+    B = int(kv_block_size)
+    out = np.zeros(pos.shape[0], dtype=np.int64)
+    for r in range(len(cu) - 1):
+        for i in range(int(cu[r]), int(cu[r + 1])):
+            p = int(pos[i])
+            out[i] = bt[r, p // B] * B + p % B
+    return out
+
+
+def seqused(retained_len_at_last_drop, kv_len, orig_len):
+    """KV length a layer sees during decode (Eq. 17): the length retained by the last drop
+    before that layer plus the tokens appended since prefill."""
+    s = np.asarray(retained_len_at_last_drop, dtype=np.int64)
+    return (s + (np.asarray(kv_len, dtype=np.int64) - np.asarray(orig_len, dtype=np.int64))).astype(np.int32)

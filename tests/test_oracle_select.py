@@ -390,3 +390,22 @@ def test_compose_index_identities_and_two_level_round_trip():
     full_direct = oracle.scatter(new2, c12, H)
     np.testing.assert_array_equal(full_two_step, full_direct)
     np.testing.assert_array_equal(oracle.retained_lengths([0, 5, 5, 12]), [5, 0, 7])
+
+
+# ----------------------------------------------------------------------------- serving-side metadata
+def test_kv_slot_mapping_and_seqused_small_cases():
+    # two requests, KV blocks of 4 slots; request 0 kept positions 0,1,5,6; request 1 kept 2,9
+    bt = np.array([[7, 3, 0], [2, 5, 9]], dtype=np.int32)
+    slots = oracle.kv_slot_mapping([0, 1, 5, 6, 2, 9], [0, 4, 6], bt, 4)
+    np.testing.assert_array_equal(slots, [28, 29, 13, 14, 10, 37])   # 7*4+0, 7*4+1, 3*4+1, 3*4+2, 2*4+2, 9*4+1
+    # identity block table and no drop: slot == position offset by the request's base
+    N = 37
+    bt = np.arange(10, dtype=np.int32)[None, :]
+    np.testing.assert_array_equal(oracle.kv_slot_mapping(np.arange(N), [0, N], bt, 4), np.arange(N))
+    # distinct tokens of a request never share a slot when its block table has distinct blocks
+    rng = np.random.default_rng(12)
+    bt = rng.permutation(64).astype(np.int32).reshape(2, 32)
+    pos = np.concatenate([np.sort(rng.choice(500, 200, replace=False)), np.sort(rng.choice(500, 123, replace=False))])
+    s = oracle.kv_slot_mapping(pos, [0, 200, 323], bt, 16)
+    assert len(set(s.tolist())) == 323
+    np.testing.assert_array_equal(oracle.seqused([100, 7], [1030, 9], [1024, 8]), [106, 8])
