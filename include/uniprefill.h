@@ -208,6 +208,19 @@ int uniprefill_compose_index(const int32_t* outer_idx, int64_t n_outer, const in
                              const int32_t* n_inner_dev, int64_t n_inner, int32_t* composed_idx,
                              void* stream);
 
+/* Physical KV-cache slots of the retained tokens after a drop (Eq. 16 of "vLLM
+ * scheduler integration"): for token t of the compacted stream, in sequence r
+ * (new_cu_seqlens_dev[r] <= t < new_cu_seqlens_dev[r+1]) at logical position
+ * p = pos_kept[t],
+ *     slots[t] = block_table[r * block_table_stride + p / kv_block_size] * kv_block_size
+ *                + p % kv_block_size.
+ * All device pointers; slots is int64.  t runs to new_cu_seqlens_dev[num_seqs]
+ * (read on the device), at most capacity.  Positions must address existing
+ * entries of the sequence's block-table row. */
+int uniprefill_slot_mapping(const int32_t* pos_kept, const int32_t* new_cu_seqlens_dev, int32_t num_seqs,
+                            const int32_t* block_table, int64_t block_table_stride, int32_t kv_block_size,
+                            int64_t capacity, int64_t* slots, void* stream);
+
 /* The kernels behind uniprefill_fused, in stream order.  Measurement aid: a
  * caller that wants to time one kernel enqueues the phases one by one. */
 enum {

@@ -4,7 +4,7 @@ from .binding import (  # noqa: F401
     UP_ERR_HIP, UP_BF16, UP_F32, EXPORTS, LIB_PATH, UniPrefillError, up_params, make_params, lib, ptr,
     status_string, uniprefill_plan, uniprefill_score, uniprefill_select, uniprefill_compact,
     uniprefill_scatter, uniprefill_fused, uniprefill_fused_phases, uniprefill_select_top_p,
-    uniprefill_compact_counted, uniprefill_fused_top_p, uniprefill_compose_index,
+    uniprefill_compact_counted, uniprefill_fused_top_p, uniprefill_compose_index, uniprefill_slot_mapping,
     UP_PHASE_PLAN, UP_PHASE_ROW_STATS, UP_PHASE_MERGE_STATS, UP_PHASE_SWEEP_SELECT, UP_PHASE_GATHER,
     UP_PHASE_ALL,
 )

@@ -21,7 +21,7 @@ UP_BF16, UP_F32 = 0, 1
 EXPORTS = ["uniprefill_plan", "uniprefill_score", "uniprefill_select", "uniprefill_compact",
            "uniprefill_scatter", "uniprefill_fused", "uniprefill_fused_phases", "uniprefill_select_top_p",
            "uniprefill_compact_counted", "uniprefill_fused_top_p", "uniprefill_compose_index",
-           "uniprefill_status_string"]
+           "uniprefill_slot_mapping", "uniprefill_status_string"]
 
 UP_PHASE_PLAN, UP_PHASE_ROW_STATS, UP_PHASE_MERGE_STATS, UP_PHASE_SWEEP_SELECT, UP_PHASE_GATHER = 1, 2, 4, 8, 16
 UP_PHASE_ALL = 31
@@ -65,6 +65,8 @@ def _load():
     lib.uniprefill_compact_counted.argtypes = [P, vp, i32p, i32p, i32p, ctypes.c_int64, vp, i32p, vp]
     lib.uniprefill_fused_top_p.argtypes = lib.uniprefill_fused.argtypes
     lib.uniprefill_compose_index.argtypes = [i32p, ctypes.c_int64, i32p, i32p, ctypes.c_int64, i32p, vp]
+    lib.uniprefill_slot_mapping.argtypes = [i32p, i32p, ctypes.c_int32, i32p, ctypes.c_int64, ctypes.c_int32,
+                                            ctypes.c_int64, vp, vp]
     for name in EXPORTS[:-1]:
         getattr(lib, name).restype = ctypes.c_int
     lib.uniprefill_status_string.argtypes = [ctypes.c_int]
@@ -213,3 +215,11 @@ def uniprefill_compose_index(outer_idx, n_outer, inner_idx, n_inner_dev, n_inner
     st = _lib.uniprefill_compose_index(ptr(outer_idx), int(n_outer), ptr(inner_idx), ptr(n_inner_dev),
                                        int(n_inner), ptr(composed_idx), _stream(stream))
     return _check(st, "uniprefill_compose_index", check)
+
+
+def uniprefill_slot_mapping(pos_kept, new_cu_seqlens_dev, num_seqs, block_table, block_table_stride,
+                            kv_block_size, capacity, slots, stream=None, check=True):
+    st = _lib.uniprefill_slot_mapping(ptr(pos_kept), ptr(new_cu_seqlens_dev), int(num_seqs), ptr(block_table),
+                                      int(block_table_stride), int(kv_block_size), int(capacity), ptr(slots),
+                                      _stream(stream))
+    return _check(st, "uniprefill_slot_mapping", check)

@@ -299,6 +299,18 @@ int uniprefill_compose_index(const int32_t* outer_idx, int64_t n_outer, const in
   return UP_OK;
 }
 
+int uniprefill_slot_mapping(const int32_t* pos_kept, const int32_t* new_cu_seqlens_dev, int32_t num_seqs,
+                            const int32_t* block_table, int64_t block_table_stride, int32_t kv_block_size,
+                            int64_t capacity, int64_t* slots, void* stream) {
+  if (num_seqs < 0 || capacity < 0 || kv_block_size < 1 || block_table_stride < 0) return UP_ERR_RANGE;
+  if (capacity == 0 || num_seqs == 0) return UP_OK;
+  if (!pos_kept || !new_cu_seqlens_dev || !block_table || !slots) return UP_ERR_NULL;
+  if (launch_slot_mapping(pos_kept, new_cu_seqlens_dev, num_seqs, block_table, block_table_stride,
+                          kv_block_size, capacity, slots, (hipStream_t)stream) != hipSuccess)
+    return UP_ERR_HIP;
+  return UP_OK;
+}
+
 int uniprefill_fused_phases(const up_params* p, const void* q, const void* k, const void* hidden,
                             const int32_t* pos, const int32_t* cu_seqlens_dev,
                             const int32_t* cu_seqlens_host, const float* keep_ratio_dev,

@@ -67,6 +67,29 @@ __global__ __launch_bounds__(256) void k_compose(const int32_t* __restrict__ out
   out[t] = outer[inner[t]];
 }
 
+// Physical KV-cache slot of every retained token (Eq. 16): token t of sequence r (found from
+// the compacted stream's offsets) at logical position p goes to block_table[r][p / B] * B + p % B.
+__global__ __launch_bounds__(256) void k_slot_mapping(const int32_t* __restrict__ pos_kept,
+                                                      const int32_t* __restrict__ new_cu, int R,
+                                                      const int32_t* __restrict__ block_table,
+                                                      long long table_stride, int kv_block,
+                                                      long long capacity, int64_t* __restrict__ slots) {
+  const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (t >= capacity || t >= (long long)new_cu[R]) return;
+  const int r = locate_token(new_cu, R, (int)t);
+  const int p = pos_kept[t];
+  slots[t] = (int64_t)block_table[(long long)r * table_stride + p / kv_block] * kv_block + p % kv_block;
+}
+
+hipError_t launch_slot_mapping(const int32_t* pos_kept, const int32_t* new_cu, int R,
+                               const int32_t* block_table, long long table_stride, int kv_block,
+                               long long capacity, int64_t* slots, hipStream_t s) {
+  if (capacity == 0 || R == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_slot_mapping, dim3((unsigned)((capacity + 255) / 256)), dim3(256), 0, s, pos_kept, new_cu,
+                     R, block_table, table_stride, kv_block, capacity, slots);
+  return hipGetLastError();
+}
+
 hipError_t launch_compose(const int32_t* outer, const int32_t* inner, long long n,
                           const int32_t* count_dev, int32_t* out, hipStream_t s) {
   if (n == 0) return hipSuccess;

@@ -44,6 +44,11 @@ hipError_t launch_scatter(const Problem& pb, const void* hidden_compact, const i
 hipError_t launch_compose(const int32_t* outer, const int32_t* inner, long long n,
                           const int32_t* count_dev, int32_t* out, hipStream_t s);
 
+// physical KV-cache slots of the retained tokens (Eq. 16); the token count is new_cu[R] on the device
+hipError_t launch_slot_mapping(const int32_t* pos_kept, const int32_t* new_cu, int R,
+                               const int32_t* block_table, long long table_stride, int kv_block,
+                               long long capacity, int64_t* slots, hipStream_t s);
+
 // --- selection
 hipError_t launch_plan(const Problem& pb, const int32_t* cu, const float* ratio, int32_t* new_cu,
                        hipStream_t s);

@@ -590,3 +590,24 @@ def test_fused_phases_one_by_one_equal_the_fused_call(lengths):
         np.testing.assert_array_equal(got[key], want[key], err_msg=key)
     assert b.canaries_intact()
     assert up.uniprefill_fused_phases(*args, 64, check=False) == up.UP_ERR_RANGE
+
+
+def test_slot_mapping_of_a_compacted_stream():
+    _say("slot mapping")
+    rng = np.random.default_rng(60)
+    w = workloads.make_custom(name="slots", seed=17, lengths=[1000, 0, 333, 64], keep_ratio=[0.3, 0.5, 0.6, 1.0],
+                              hidden_dim=8, num_q_heads=2, num_kv_heads=1, block_size=64, n_obs=32, n_sink=8,
+                              pos_offsets=[0, 0, 5, 100])
+    scores = rng.random(w.total_tokens).astype(np.float32)
+    idx, new_cu = oracle.select_tokens(scores, w.cu_seqlens, w.keep_ratio, block_size=64, n_obs=32, n_sink=8)
+    _, pos_kept = oracle.compact(w.hidden, w.pos, idx)
+    B, max_blocks = 16, 80
+    block_table = rng.permutation(4 * max_blocks).astype(np.int32).reshape(4, max_blocks)
+    want = oracle.kv_slot_mapping(pos_kept, new_cu, block_table, B)
+    n = len(idx)
+    slots = torch.full((n + 8,), -77, dtype=torch.int64, device="cuda")
+    up.uniprefill_slot_mapping(torch.from_numpy(pos_kept).cuda(), torch.from_numpy(new_cu).cuda(), 4,
+                               torch.from_numpy(block_table).cuda(), max_blocks, B, n + 8, slots)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(slots[:n].cpu().numpy(), want)
+    assert (slots[n:] == -77).all()

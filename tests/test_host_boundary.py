@@ -201,3 +201,11 @@ def test_compose_index_rejects_bad_arguments():
     assert L.uniprefill_compose_index(v(fake), 10, v(fake), None, 11, v(fake), None) == up.UP_ERR_RANGE
     assert L.uniprefill_compose_index(v(fake), -1, v(fake), None, 0, v(fake), None) == up.UP_ERR_RANGE
     assert L.uniprefill_compose_index(v(fake), 10, v(fake), None, 0, v(fake), None) == up.UP_OK
+
+
+def test_slot_mapping_rejects_bad_arguments():
+    L, v, fake = up.lib(), ctypes.c_void_p, 0x1000
+    assert L.uniprefill_slot_mapping(None, v(fake), 2, v(fake), 8, 16, 10, v(fake), None) == up.UP_ERR_NULL
+    assert L.uniprefill_slot_mapping(v(fake), v(fake), 2, v(fake), 8, 0, 10, v(fake), None) == up.UP_ERR_RANGE
+    assert L.uniprefill_slot_mapping(v(fake), v(fake), -1, v(fake), 8, 16, 10, v(fake), None) == up.UP_ERR_RANGE
+    assert L.uniprefill_slot_mapping(v(fake), v(fake), 2, v(fake), 8, 16, 0, v(fake), None) == up.UP_OK
