@@ -85,8 +85,7 @@ int check_ratio(const up_params* p, const float* ratio_host) {
 // block (512 keys with 16 waves; 256 with 8 waves for fp32 operands, or when even a full head
 // split leaves most of the chip idle) and `split` work-groups share a key block, each sweeping
 // Hkv / split kv heads.  The split grows (powers of two dividing Hkv) until the launch has about
-// one work-group per CU, and a launch of a few uneven rounds is split once more so that its last
-// round is fuller.
+// one work-group per CU; launches of a few rounds are split further (below).
 void choose_geometry(Problem* pb, const int32_t* cu) {
   constexpr int kCUs = 256, kEnough = 224;
   auto blocks = [&](int kb) {
@@ -103,9 +102,14 @@ void choose_geometry(Problem* pb, const int32_t* cu) {
     kb = 256;
     nb = blocks(kb);
   }
-  const long long wgs = nb * split;
-  const long long rounds = (wgs + kCUs - 1) / kCUs;
-  if (rounds >= 2 && rounds <= 4 && wgs * 100 < rounds * kCUs * 85 && can_double()) split *= 2;
+  // A launch of a few rounds balances better with shorter work-groups (their durations differ:
+  // edge blocks, ragged sequences): keep halving the heads per work-group up to about six rounds,
+  // as long as a work-group still sweeps eight staging units or more.
+  int longest_n = 0;
+  for (int r = 0; r < pb->R; ++r) longest_n = cu[r + 1] - cu[r] > longest_n ? cu[r + 1] - cu[r] : longest_n;
+  const long long units_per_head = ((long long)(longest_n < pb->n_obs ? longest_n : pb->n_obs) * pb->Gq + 127) / 128;
+  if (nb * split > kCUs)
+    while (can_double() && nb * split < 6 * kCUs && (pb->Hkv / (2 * split)) * units_per_head >= 8) split *= 2;
   pb->key_block = kb;
   pb->key_block_slots = pb->T / kb + pb->R;
   pb->split = split;
