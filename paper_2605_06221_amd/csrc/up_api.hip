@@ -108,7 +108,13 @@ void choose_geometry(Problem* pb, const int32_t* cu) {
   int longest_n = 0;
   for (int r = 0; r < pb->R; ++r) longest_n = cu[r + 1] - cu[r] > longest_n ? cu[r + 1] - cu[r] : longest_n;
   const long long units_per_head = ((long long)(longest_n < pb->n_obs ? longest_n : pb->n_obs) * pb->Gq + 127) / 128;
-  if (nb * split > kCUs)
+  // The grid has one slot per key block plus one spare per sequence (T / kb + R); the spares
+  // exit at once, but they sit between the live work-groups, and a grid of more than one
+  // work-group per CU then runs as two rounds even when the live ones alone would fit in one.
+  // So it is the grid that is compared with the CU count (one sequence: its spare is the last
+  // slot and does no harm).
+  const long long slots = pb->R == 1 ? nb : (long long)pb->T / kb + pb->R;
+  if (slots * split > kCUs)
     while (can_double() && nb * split < 6 * kCUs && (pb->Hkv / (2 * split)) * units_per_head >= 8) split *= 2;
   pb->key_block = kb;
   pb->key_block_slots = pb->T / kb + pb->R;
