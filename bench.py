@@ -63,6 +63,7 @@ def main():
                     help="instead of --config: a Llama-3-8B-shaped batch (hidden 4096, 32/8 heads x 128, block "
                          "128) with these comma-separated sequence lengths, e.g. 8192,8192")
     ap.add_argument("--keep-ratio", type=float, default=0.3, help="keep ratio of a --lengths batch")
+    ap.add_argument("--head-dim", type=int, default=128, help="head dimension of a --lengths batch (64, 128, 256)")
     ap.add_argument("--input-sets", type=int, default=3,
                     help="copies of (q, k, hidden) in HBM that the steps rotate over, so that no step "
                          "finds its inputs in the 256 MB last-level cache (1 = warm)")
@@ -94,9 +95,9 @@ def main():
     t0 = time.time()
     if args.lengths:
         lengths = [int(x) for x in args.lengths.split(",")]
-        w = workloads.make_custom(name=f"llama8b_shape_{len(lengths)}x{max(lengths)}_r{args.keep_ratio}", seed=100,
+        w = workloads.make_custom(name=f"llama8b_shape_{len(lengths)}x{max(lengths)}_r{args.keep_ratio}_hd{args.head_dim}", seed=100,
                                   lengths=lengths, keep_ratio=[args.keep_ratio] * len(lengths), hidden_dim=4096,
-                                  num_q_heads=32, num_kv_heads=8, block_size=128)
+                                  num_q_heads=32, num_kv_heads=8, block_size=128, head_dim=args.head_dim)
     else:
         w = workloads.make_config(args.config)
     print(f"[bench] generated {w.name}: T={w.total_tokens} R={w.num_seqs} in {time.time() - t0:.1f}s",

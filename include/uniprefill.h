@@ -26,8 +26,9 @@
  *       UP_ERR_RANGE       keep ratio not in (0,1] or NaN; block_size not in
  *                          {32,64,128}; n_obs < 1 or > 1024; n_sink < 0;
  *                          total_kept inconsistent with the plan
- *       UP_ERR_UNSUPPORTED head_dim != 128; num_q_heads % num_kv_heads != 0;
- *                          more than 64 query heads per kv head; unknown dtype
+ *       UP_ERR_UNSUPPORTED head_dim not in {64,128,256}, or 256 with UP_F32
+ *                          operands; num_q_heads % num_kv_heads != 0; more than
+ *                          64 query heads per kv head; unknown dtype
  *       UP_ERR_ALIGN       a base pointer is not 16-byte aligned or a row stride
  *                          in bytes is not a multiple of 16
  *       UP_ERR_WORKSPACE   workspace is NULL or smaller than uniprefill_plan says
@@ -76,7 +77,7 @@ typedef struct {
   int32_t n_sink;            /* A >= 0 */
   int32_t num_q_heads;
   int32_t num_kv_heads;
-  int32_t head_dim;          /* 128 */
+  int32_t head_dim;          /* 64, 128 or 256 (256: UP_BF16 operands only) */
   int32_t hidden_dim;        /* d */
   int64_t q_row_stride;      /* elements between consecutive tokens of q */
   int64_t k_row_stride;      /* elements between consecutive tokens of k */

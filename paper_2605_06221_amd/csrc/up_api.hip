@@ -17,6 +17,9 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 int elem_bytes(int dt) { return dt == UP_BF16 ? 2 : 4; }
 
+// head rows of 512 bytes (fp32 operands, or 256 bf16 elements) only fit the 8-wave work-group
+bool narrow_only(const Problem& pb) { return pb.qk_is_f32 || pb.head_dim > 128; }
+
 // Checks that need only the parameter block.
 int check_params(const up_params* p, bool need_qk, bool need_hidden, Problem* pb) {
   if (p == nullptr) return UP_ERR_NULL;
@@ -30,7 +33,8 @@ int check_params(const up_params* p, bool need_qk, bool need_hidden, Problem* pb
   q.q_stride = p->q_row_stride; q.k_stride = p->k_row_stride; q.h_stride = p->hidden_row_stride;
   q.Gq = 1;
   if (need_qk) {
-    if (p->head_dim != 128) return UP_ERR_UNSUPPORTED;
+    if (p->head_dim != 64 && p->head_dim != 128 && p->head_dim != 256) return UP_ERR_UNSUPPORTED;
+    if (p->head_dim == 256 && p->qk_dtype == UP_F32) return UP_ERR_UNSUPPORTED;
     if (p->num_q_heads < 1 || p->num_kv_heads < 1) return UP_ERR_SHAPE;
     if (p->num_q_heads % p->num_kv_heads != 0) return UP_ERR_UNSUPPORTED;
     if (p->num_q_heads / p->num_kv_heads > 64) return UP_ERR_UNSUPPORTED;
@@ -43,6 +47,7 @@ int check_params(const up_params* p, bool need_qk, bool need_hidden, Problem* pb
     if ((p->q_row_stride * eb) % 16 != 0 || (p->k_row_stride * eb) % 16 != 0) return UP_ERR_ALIGN;
     q.Gq = p->num_q_heads / p->num_kv_heads;
     q.qk_is_f32 = p->qk_dtype == UP_F32;
+    q.head_dim = p->head_dim;
     q.scale = p->softmax_scale > 0.0f ? p->softmax_scale : 1.0f / sqrtf((float)p->head_dim);
   }
   if (need_hidden) {
@@ -55,7 +60,7 @@ int check_params(const up_params* p, bool need_qk, bool need_hidden, Problem* pb
       return UP_ERR_ALIGN;
   }
   // launch geometry of the scoring sweeps: provisional until choose_geometry has seen the lengths
-  q.key_block = q.qk_is_f32 ? 256 : 512;
+  q.key_block = narrow_only(q) ? 256 : 512;
   q.key_block_slots = q.T / q.key_block + q.R;
   q.split = 1;
   q.max_key_blocks = q.key_block_slots;
@@ -82,7 +87,7 @@ int check_ratio(const up_params* p, const float* ratio_host) {
 }
 
 // Launch geometry of the scoring sweeps from the sequence lengths.  A work-group owns one key
-// block (512 keys with 16 waves; 256 with 8 waves for fp32 operands, or when even a full head
+// block (512 keys with 16 waves; 256 with 8 waves for head rows of 512 bytes, or when even a full head
 // split leaves most of the chip idle) and `split` work-groups share a key block, each sweeping
 // Hkv / split kv heads.  The split grows (powers of two dividing Hkv) until the launch has about
 // one work-group per CU; launches of a few rounds are split further (below).
@@ -93,7 +98,7 @@ void choose_geometry(Problem* pb, const int32_t* cu) {
     for (int r = 0; r < pb->R; ++r) n += (cu[r + 1] - cu[r] + kb - 1) / kb;
     return n;
   };
-  int kb = pb->qk_is_f32 ? 256 : 512;
+  int kb = narrow_only(*pb) ? 256 : 512;
   long long nb = blocks(kb);
   int split = 1;
   auto can_double = [&]() { return 2 * split <= pb->Hkv && pb->Hkv % (2 * split) == 0; };

@@ -18,6 +18,7 @@ struct Problem {
   long long q_stride, k_stride, h_stride;  // elements
   int hidden_elem_bytes;      // 2 (bf16) or 4 (f32)
   int qk_is_f32;
+  int head_dim;               // 64, 128 or 256 (256: bf16 only)
   float scale;                // softmax scale (resolved, > 0)
   int key_block;              // keys per work-group of the scoring sweeps: 256 or 512
   int key_block_slots;        // T / key_block + R: key blocks of all sequences (an upper bound)

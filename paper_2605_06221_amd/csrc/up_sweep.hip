@@ -47,10 +47,13 @@
 namespace up {
 
 constexpr int kUnit = 128;           // query rows per LDS staging unit (4 MFMA row tiles)
-// bytes of one head row (128 elements) in global memory, and in LDS with a 16-byte pad that makes
+// bytes of one head row (D elements) in global memory, and in LDS with a 16-byte pad that makes
 // the 128-bit operand reads conflict-free
-template <bool F32> constexpr int kHeadRowBytes = F32 ? 512 : 256;
-template <bool F32> constexpr int kQRow = kHeadRowBytes<F32> + 16;
+template <bool F32, int D> constexpr int kHeadRowBytes = D * (F32 ? 4 : 2);
+template <bool F32, int D> constexpr int kQRow = kHeadRowBytes<F32, D> + 16;
+// pass 1 leaves one pair of statistics per lane half of every wave when LDS has room for it
+// (head rows of up to 256 bytes), which spares the tiles a lane exchange; otherwise one per wave
+template <bool F32, int D> constexpr bool kHalfStats = kHeadRowBytes<F32, D> <= 256;
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
@@ -92,19 +95,18 @@ __device__ __forceinline__ void divmod(unsigned x, unsigned d, unsigned magic, i
 // LDS of one work-group of NW waves.  The staged query rows are dead once the sweep is over,
 // so the selection state reuses their space.  The per-unit tables are double-buffered like
 // the rows: the tables of unit f+1 are written while unit f is being read.
-template <int NW, bool F32>
+template <int NW, bool F32, int D>
 struct SweepSmem {
   union {
-    __align__(16) unsigned char q[2][kUnit * kQRow<F32>];   // staged query rows, double-buffered
+    __align__(16) unsigned char q[2][kUnit * kQRow<F32, D>];   // staged query rows, double-buffered
     struct {
       double o64[32 * NW];                             // pass 2: column sums of the block's keys
       SelectSmem sel;
     } tail;
   };
   union {
-    // pass 1: (reference, sum) per staged row from every wave -- from each lane half of every wave
-    // when there is room for it (bf16 operands), which spares the tiles a lane exchange
-    float2 wstat[2][NW * (F32 ? 1 : 2)][kUnit];
+    // pass 1: (reference, sum) per staged row from every wave, or from each lane half of every wave
+    float2 wstat[2][NW * (kHalfStats<F32, D> ? 2 : 1)][kUnit];
     __align__(16) float2 cst[2][kUnit];                // pass 2: (negative reference, 1/sum) per staged row
   };
   __align__(16) int rowpos[2][kUnit];                  // local position of each staged row, -1 = no such row
@@ -123,16 +125,19 @@ struct UnitCursor {
   }
 };
 
-template <int PASS, bool EDGE, int NW, bool F32>
-__device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem<NW, F32>& sm, int r, int c0, int N,
+template <int PASS, bool EDGE, int NW, bool F32, int D>
+__device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem<NW, F32, D>& sm, int r, int c0, int N,
                                             int kblock, int slot, int g0, int n_heads) {
   constexpr int KB = 32 * NW;                               // keys per work-group
   constexpr int THREADS = 64 * NW;
-  constexpr int SRCB = kHeadRowBytes<F32>;                  // bytes of a head row in global memory
-  constexpr int ROWB = kQRow<F32>;                          // ... and in LDS
+  constexpr int SRCB = kHeadRowBytes<F32, D>;               // bytes of a head row in global memory
+  constexpr int ROWB = kQRow<F32, D>;                       // ... and in LDS
+  constexpr bool HS = kHalfStats<F32, D>;
   constexpr int PPR = SRCB / 16;                            // 16-byte pieces per row
   constexpr int PIECES = kUnit * PPR / THREADS;             // pieces of a unit per thread
   constexpr int ROWSTEP = THREADS / PPR;                    // rows between a thread's pieces
+  static_assert(THREADS % PPR == 0 && (kUnit * PPR) % THREADS == 0 && PIECES >= 1, "staging split");
+  static_assert(sizeof(SweepSmem<NW, F32, D>) <= 160 * 1024, "LDS of one CU");
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
   const int l32 = lane & 31, half = lane >> 5;
@@ -150,17 +155,19 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem<NW, F3
   // ---- key operands of one kv head: 32 keys, lane = (key l32, half of the contraction).
   // bf16: MFMA step kk contracts elements 16*kk .. 16*kk+15, lane half h supplies 8*h .. 8*h+7 of
   // them (one 128-bit register group per step).  fp32 (v_mfma_f32_32x32x2_f32, two elements per
-  // step): step t contracts elements t and 64+t, so that a lane half owns 64 consecutive
+  // step): step t contracts elements t and D/2+t, so that a lane half owns D/2 consecutive
   // elements and loads them with 128-bit accesses; queries use the same order.
   // Keys past the end of the sequence re-read the last key (finite values): pass 1 masks
   // them (such a block is always an edge block), pass 2 never emits their scores.
-  constexpr int KREG = F32 ? 16 : 8;
+  constexpr int KREG = SRCB / 32;                 // 128-bit register groups of a lane's half row
+  constexpr int HOFF = F32 ? SRCB / 2 : 16;       // byte offset of the second lane half
+  constexpr int KSTEP = F32 ? 16 : 32;            // bytes between a lane's register groups
   u32x4 kf[KREG];
-  const char* k_lane = a.k + (long long)(c0 + imin(key_base + l32, N - 1)) * a.k_stride_b + half * (F32 ? 256 : 16);
+  const char* k_lane = a.k + (long long)(c0 + imin(key_base + l32, N - 1)) * a.k_stride_b + half * HOFF;
   auto load_keys = [&](int g) {
 #pragma unroll
     for (int kk = 0; kk < KREG; ++kk)
-      kf[kk] = *(const u32x4*)(k_lane + (long long)g * SRCB + kk * (F32 ? 16 : 32));
+      kf[kk] = *(const u32x4*)(k_lane + (long long)g * SRCB + kk * KSTEP);
   };
 
   // ---- staging of one unit of query rows: 128 rows x PPR pieces of 16 bytes, PIECES per thread:
@@ -231,7 +238,7 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem<NW, F3
     u32x4 qv[KREG];
 #pragma unroll
     for (int kk = 0; kk < KREG; ++kk)
-      qv[kk] = *(const u32x4*)(&sm.q[buf][(rt * 32 + l32) * ROWB + half * (F32 ? 256 : 16) + kk * (F32 ? 16 : 32)]);
+      qv[kk] = *(const u32x4*)(&sm.q[buf][(rt * 32 + l32) * ROWB + half * HOFF + kk * KSTEP]);
     f32x16 acc;
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[e] = 0.0f;
@@ -243,7 +250,7 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem<NW, F3
                         : __builtin_amdgcn_mfma_f32_32x32x2f32(qx, kx, acc, 0, 0, 0);
       };
 #pragma unroll
-      for (int kk = 0; kk < 16; ++kk) {
+      for (int kk = 0; kk < KREG; ++kk) {
         const u32x4 k4 = kf[kk], q4 = qv[kk];
         step(k4.x, q4.x);
         step(k4.y, q4.y);
@@ -252,7 +259,7 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem<NW, F3
       }
     } else {
 #pragma unroll
-      for (int kk = 0; kk < 8; ++kk)
+      for (int kk = 0; kk < KREG; ++kk)
         acc = PASS == 1 ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kf[kk]), as_bf16x8(qv[kk]), acc, 0, 0, 0)
                         : __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(qv[kk]), as_bf16x8(kf[kk]), acc, 0, 0, 0);
     }
@@ -278,7 +285,7 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem<NW, F3
         l1 += exp2_hw(fmaf(acc[e + 1], c, negref));
       }
       l0 += l1;                                         // 0 when every key was masked (exp2(-inf))
-      if (!F32) {
+      if (HS) {
         // each lane half leaves its own pair (the same row over its 16 keys); the unit merge adds them
         sm.wstat[tb][2 * wave + half][rt * 32 + l32] = make_float2(ref, l0);
       } else {
@@ -321,7 +328,7 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem<NW, F3
   // apart inside the next unit's matrix work, where their latency disappears.
   constexpr int RPW = kUnit / NW;                 // rows per wave: 8 or 16
   constexpr int LPR = 64 / RPW;                   // lanes per row: 8 or 4
-  constexpr int PPL = (F32 ? NW : 2 * NW) / LPR;  // partials per lane: 2 or 4
+  constexpr int PPL = (HS ? 2 * NW : NW) / LPR;   // partials per lane: 2 or 4
   float2 mp[PPL];
 #pragma unroll
   for (int i = 0; i < PPL; ++i) mp[i] = make_float2(0.0f, 0.0f);
@@ -393,7 +400,7 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem<NW, F3
         }
         if (none) {
           if (PASS == 1) {
-            if (!F32) sm.wstat[buf][2 * wave + half][rt * 32 + l32] = make_float2(-INFINITY, 0.0f);
+            if (HS) sm.wstat[buf][2 * wave + half][rt * 32 + l32] = make_float2(-INFINITY, 0.0f);
             else if (half == 0) sm.wstat[buf][wave][rt * 32 + l32] = make_float2(-INFINITY, 0.0f);
           }
         } else if (mixed) {
@@ -427,10 +434,10 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem<NW, F3
   }
 }
 
-template <int PASS, int NW, bool F32>
+template <int PASS, int NW, bool F32, int D>
 __global__ __launch_bounds__(64 * NW) void k_sweep(SweepArgs a) {
   constexpr int KB = 32 * NW;
-  __shared__ SweepSmem<NW, F32> sm;
+  __shared__ SweepSmem<NW, F32, D> sm;
   const int slot = blockIdx.x / a.split, part = blockIdx.x % a.split;
   const int r = locate_slot(a.cu, a.R, KB, slot);
   const int c0 = a.cu[r];
@@ -441,8 +448,8 @@ __global__ __launch_bounds__(64 * NW) void k_sweep(SweepArgs a) {
   // causal masking and the ragged end only matter where keys reach the query window
   const bool edge = (kblock + 1) * KB - 1 > N - n_eff;
   const int n_heads = a.Hkv / a.split;
-  if (edge) sweep_block<PASS, true, NW, F32>(a, sm, r, c0, N, kblock, slot, part * n_heads, n_heads);
-  else sweep_block<PASS, false, NW, F32>(a, sm, r, c0, N, kblock, slot, part * n_heads, n_heads);
+  if (edge) sweep_block<PASS, true, NW, F32, D>(a, sm, r, c0, N, kblock, slot, part * n_heads, n_heads);
+  else sweep_block<PASS, false, NW, F32, D>(a, sm, r, c0, N, kblock, slot, part * n_heads, n_heads);
 
   if (PASS == 2) {
     __syncthreads();
@@ -618,17 +625,38 @@ static SweepArgs make_sweep_args(const Problem& pb, const void* q, const void* k
   return a;
 }
 
+// One instantiation per (operand type, head dimension, waves per work-group) that is offered:
+// 16 waves (512 keys) only where a wave's registers hold its operands within 128 VGPRs, i.e. for
+// head rows of up to 256 bytes in bf16.
+template <int PASS>
+static hipError_t launch_sweep(const Problem& pb, const SweepArgs& a, hipStream_t s) {
+  const dim3 grid((unsigned)(pb.key_block_slots * pb.split));
+  const bool wide = pb.key_block == 512;
+#define UP_SWEEP(NW_, F32_, D_) hipLaunchKernelGGL((k_sweep<PASS, NW_, F32_, D_>), grid, dim3(64 * NW_), 0, s, a)
+  if (pb.qk_is_f32) {
+    if (wide) return hipErrorInvalidValue;
+    if (pb.head_dim == 64) UP_SWEEP(8, true, 64);
+    else if (pb.head_dim == 128) UP_SWEEP(8, true, 128);
+    else return hipErrorInvalidValue;
+  } else if (pb.head_dim == 64) {
+    if (wide) UP_SWEEP(16, false, 64); else UP_SWEEP(8, false, 64);
+  } else if (pb.head_dim == 128) {
+    if (wide) UP_SWEEP(16, false, 128); else UP_SWEEP(8, false, 128);
+  } else if (pb.head_dim == 256) {
+    if (wide) return hipErrorInvalidValue;
+    UP_SWEEP(8, false, 256);
+  } else {
+    return hipErrorInvalidValue;
+  }
+#undef UP_SWEEP
+  return hipGetLastError();
+}
+
 hipError_t launch_row_stats(const Problem& pb, const void* q, const void* k, const int32_t* cu,
                             void* workspace, hipStream_t s) {
   if (pb.T == 0) return hipSuccess;
   const SweepArgs a = make_sweep_args(pb, q, k, cu, workspace);
-  if (pb.qk_is_f32)
-    hipLaunchKernelGGL((k_sweep<1, 8, true>), dim3((unsigned)(pb.key_block_slots * pb.split)), dim3(512), 0, s, a);
-  else if (pb.key_block == 512)
-    hipLaunchKernelGGL((k_sweep<1, 16, false>), dim3((unsigned)(pb.key_block_slots * pb.split)), dim3(1024), 0, s, a);
-  else
-    hipLaunchKernelGGL((k_sweep<1, 8, false>), dim3((unsigned)(pb.key_block_slots * pb.split)), dim3(512), 0, s, a);
-  return hipGetLastError();
+  return launch_sweep<1>(pb, a, s);
 }
 
 hipError_t launch_merge_stats(const Problem& pb, const int32_t* cu, void* workspace, hipStream_t s) {
@@ -651,13 +679,8 @@ hipError_t launch_column_sums(const Problem& pb, const void* q, const void* k, c
   a.scores_out = scores_out;
   if (sel != nullptr) { a.sel = *sel; a.do_select = 1; }
   else { a.sel.G = pb.G; }
-  const dim3 grid((unsigned)(pb.key_block_slots * pb.split));
-  if (pb.qk_is_f32)
-    hipLaunchKernelGGL((k_sweep<2, 8, true>), grid, dim3(512), 0, s, a);
-  else if (pb.key_block == 512)
-    hipLaunchKernelGGL((k_sweep<2, 16, false>), grid, dim3(1024), 0, s, a);
-  else
-    hipLaunchKernelGGL((k_sweep<2, 8, false>), grid, dim3(512), 0, s, a);
+  const hipError_t e = launch_sweep<2>(pb, a, s);
+  if (e != hipSuccess) return e;
   if (pb.split > 1)
     hipLaunchKernelGGL(k_finish, dim3((unsigned)(pb.T / pb.G + pb.R)), dim3(256), 0, s, a, pb.key_block);
   return hipGetLastError();

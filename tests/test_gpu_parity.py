@@ -278,6 +278,66 @@ def test_fused_from_fp32_operands_bit_exact():
     assert b.canaries_intact()
 
 
+def _many_lengths(seed, count):
+    special = [0, 1, 2, 31, 32, 33, 127, 128, 129, 255, 256, 257, 511, 512, 513, 1023, 1025, 1500]
+    rng = np.random.default_rng(seed)
+    lengths = special + [int(x) for x in rng.integers(1, 700, size=count - len(special))]
+    rng.shuffle(lengths)
+    return lengths
+
+
+@pytest.mark.parametrize("head_dim", [64, 256])
+@pytest.mark.parametrize("case", [
+    dict(lengths=[1, 5, 130, 0, 257, 1000, 64], Hq=8, Hkv=2, n_obs=128),
+    dict(lengths=[2100, 300], Hq=12, Hkv=4, n_obs=200),
+    dict(lengths=[5000], Hq=4, Hkv=1, n_obs=32),
+    dict(lengths="many", Hq=8, Hkv=2, n_obs=128),
+])
+def test_scores_head_dims_64_and_256_match_oracle(head_dim, case):
+    """Head dimensions other than 128: four (64) or sixteen (256) matrix steps per tile, the
+    latter in 256-key work-groups only; "many" reaches the 512-key work-groups for 64."""
+    lengths = _many_lengths(7, 230) if case["lengths"] == "many" else case["lengths"]
+    _say("score head_dim", head_dim, case if case["lengths"] != "many" else "many sequences")
+    w = workloads.make_custom(name="hd", seed=14, lengths=lengths, keep_ratio=[0.5] * len(lengths),
+                              hidden_dim=8, num_q_heads=case["Hq"], num_kv_heads=case["Hkv"], block_size=64,
+                              n_obs=case["n_obs"], head_dim=head_dim)
+    b = DeviceBatch(w)
+    b.score()
+    got = b.results()["scores"]
+    want = oracle.quantise_scores(oracle.importance_scores(
+        _q_f32(w), workloads.bf16_bits_to_f32(w.k), w.cu_seqlens, n_obs=w.n_obs))
+    ok, worst = _score_close(got, want)
+    _say("  worst relative score error", worst)
+    assert ok
+    assert b.canaries_intact()
+
+
+@pytest.mark.parametrize("head_dim", [64, 256])
+def test_fused_head_dims_64_and_256_bit_exact(head_dim):
+    _say("fused head_dim", head_dim)
+    w = workloads.make_custom(name="hdf", seed=15, lengths=[3000, 40, 777, 9000], keep_ratio=[0.3, 0.5, 0.7, 0.25],
+                              hidden_dim=64, num_q_heads=8, num_kv_heads=2, block_size=64, n_obs=128,
+                              head_dim=head_dim)
+    b = DeviceBatch(w)
+    b.fused()
+    _assert_fused_exact(w, b, oracle_run(w))
+
+
+def test_scores_from_fp32_operands_head_dim_64():
+    _say("score fp32 head_dim 64")
+    w = workloads.make_custom(name="f32hd", seed=16, lengths=[1, 130, 0, 700, 2100], keep_ratio=[0.5] * 5,
+                              hidden_dim=8, num_q_heads=8, num_kv_heads=2, block_size=64, n_obs=128, head_dim=64)
+    q32, k32 = _f32_operands(w, 33)
+    b = DeviceBatch(w, qk_f32=(q32, k32))
+    b.score()
+    got = b.results()["scores"].astype(np.float64)
+    want = oracle.quantise_scores(oracle.importance_scores(q32, k32, w.cu_seqlens, n_obs=w.n_obs)).astype(np.float64)
+    err = np.abs(got - want)
+    _say("  worst relative score error", (err / np.maximum(want, 1e-300))[want > 0].max())
+    assert (err <= SCORE_RTOL_F32 * want + SCORE_ATOL).all()
+    assert b.canaries_intact()
+
+
 def test_scores_custom_scale_and_heavy_tail():
     _say("score heavy tail")
     w = workloads.make_custom(name="ht", seed=3, lengths=[4000], keep_ratio=[0.25], hidden_dim=8,

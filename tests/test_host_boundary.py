@@ -86,7 +86,10 @@ def test_plan_rejects_bad_arguments():
     assert plan(_params(n_obs=0)) == up.UP_ERR_RANGE
     assert plan(_params(n_obs=4096)) == up.UP_ERR_RANGE
     assert plan(_params(n_sink=-1)) == up.UP_ERR_RANGE
-    assert plan(_params(head_dim=64)) == up.UP_ERR_UNSUPPORTED
+    assert plan(_params(head_dim=64)) == up.UP_OK
+    assert plan(_params(head_dim=256)) == up.UP_OK
+    assert plan(_params(head_dim=96)) == up.UP_ERR_UNSUPPORTED
+    assert plan(_params(head_dim=256, qk_dtype=up.UP_F32)) == up.UP_ERR_UNSUPPORTED
     assert plan(_params(num_q_heads=6, num_kv_heads=4)) == up.UP_ERR_UNSUPPORTED
     assert plan(_params(qk_dtype=up.UP_F32)) == up.UP_OK
     assert plan(_params(qk_dtype=7)) == up.UP_ERR_UNSUPPORTED
