@@ -28,6 +28,12 @@ What is computed, step by step (paper section / equation in brackets):
 5. compaction of hidden states / position ids onto the kept rows [Sparsity
    Propagation, Eq. 7] and the inverse scatter [Eq. 8].
 
+6. chunks that follow earlier context (chunked prefill, keys of earlier tokens
+   cached): ``importance_scores_with_context`` and the selection with the sinks
+   that fall inside the chunk; pinned by hand-worked rationals, the harmonic
+   closed form, a library softmax, and by being the tail of the whole-sequence
+   scores (tests/test_oracle_context.py).
+
 Pins (see tests/test_oracle_*.py): softmax row sums, harmonic closed form for
 Q = 0, a library attention routine with V = I, shift/permutation invariances,
 exact kept counts, brute-force subset enumeration, identity at ratio 1,
@@ -349,3 +355,93 @@ def seqused(retained_len_at_last_drop, kv_len, orig_len):
     before that layer plus the tokens appended since prefill."""
     s = np.asarray(retained_len_at_last_drop, dtype=np.int64)
     return (s + (np.asarray(kv_len, dtype=np.int64) - np.asarray(orig_len, dtype=np.int64))).astype(np.int32)
+
+
+# --------------------------------------------------------------------------- #
+# chunks that follow earlier context  (chunked prefill: keys of earlier tokens are cached)
+# --------------------------------------------------------------------------- #
+# The paper scores whole prompts; its serving integration (Fused Kernel and vLLM Integration)
+# runs under continuous batching, where a long prompt arrives in chunks and the keys of the
+# earlier chunks sit in the KV cache.  The reading taken here: the tokens of a chunk get the
+# scores they would get if the sequence so far (earlier tokens + chunk) were scored with the
+# window taken from the chunk's last min(n, N) tokens; selection blocks start at the chunk's
+# first token; a chunk token is a sink when its position in the sequence so far is below A.
+def importance_scores_with_context(q, k, cu_seqlens_q, cu_seqlens_k, *, n_obs, scale=None):
+    """Per-token importance (float64) of the chunk tokens of every request.
+
+    q : [T, Hq, D], the chunk tokens (only the last min(n_obs, N_r) rows of each request are
+    read); k : [Tk, Hkv, D], for request r the keys of its P_r earlier tokens followed by the
+    keys of its N_r chunk tokens (P_r + N_r = cu_seqlens_k[r+1] - cu_seqlens_k[r]).
+    Chunk row j sits at position P_r + j and sees keys 0 .. P_r + j; the softmax runs over all
+    of them (Eq. 2); chunk token i receives the mean weight of key P_r + i (Eq. 3)."""
+    k = np.asarray(k)
+    cq = np.asarray(cu_seqlens_q, dtype=np.int64)
+    ck = np.asarray(cu_seqlens_k, dtype=np.int64)
+    T, Hq, D = q.shape
+    Hkv = k.shape[1]
+    assert k.shape[2] == D and Hq % Hkv == 0 and len(cq) == len(ck)
+    group = Hq // Hkv
+    if scale is None:
+        scale = 1.0 / math.sqrt(D)
+    o = np.zeros(T, dtype=np.float64)
+    for r in range(len(cq) - 1):
+        c0, c1 = int(cq[r]), int(cq[r + 1])
+        k0, k1 = int(ck[r]), int(ck[r + 1])
+        N, L = c1 - c0, k1 - k0
+        P = L - N
+        assert P >= 0
+        if N == 0:
+            continue
+        n_eff = min(int(n_obs), N)
+        Kr = k[k0:k1].astype(np.float64)                       # [L, Hkv, D]
+        Qw = np.asarray(q[c1 - n_eff:c1], dtype=np.float64)    # [n_eff, Hq, D]
+        qpos = np.arange(L - n_eff, L)                         # position of each window row
+        visible = np.arange(L)[None, :] <= qpos[:, None]
+        colsum = np.zeros(L, dtype=np.float64)
+        for h in range(Hq):
+            S = scale * (Qw[:, h, :] @ Kr[:, h // group, :].T)   # [n_eff, L]
+            S[~visible] = -np.inf
+            S -= S.max(axis=1, keepdims=True)
+            W = np.exp(S)
+            W /= W.sum(axis=1, keepdims=True)                  # over earlier and chunk keys alike
+            colsum += W.sum(axis=0)
+        o[c0:c1] = colsum[P:] / (n_eff * Hq)
+    return o
+
+
+def sinks_in_chunk(cu_seqlens_q, cu_seqlens_k, n_sink):
+    """Number of sink tokens inside each request's chunk: max(0, A - P_r)."""
+    cq = np.asarray(cu_seqlens_q, dtype=np.int64)
+    ck = np.asarray(cu_seqlens_k, dtype=np.int64)
+    P = (ck[1:] - ck[:-1]) - (cq[1:] - cq[:-1])
+    return np.maximum(0, int(n_sink) - P)
+
+
+def select_tokens_with_context(scores_f32, cu_seqlens_q, cu_seqlens_k, keep_ratio, *, block_size, n_obs, n_sink):
+    """Block-local top-k over the chunk tokens: ``select_tokens`` request by request, with the
+    sinks that fall inside the chunk."""
+    s = np.asarray(scores_f32, dtype=np.float32)
+    cq = np.asarray(cu_seqlens_q, dtype=np.int64)
+    A = sinks_in_chunk(cu_seqlens_q, cu_seqlens_k, n_sink)
+    kept = []
+    new_cu = np.zeros(len(cq), dtype=np.int32)
+    for r in range(len(cq) - 1):
+        c0, c1 = int(cq[r]), int(cq[r + 1])
+        idx, ncu = select_tokens(s[c0:c1], [0, c1 - c0], [keep_ratio[r]], block_size=block_size,
+                                 n_obs=n_obs, n_sink=int(A[r]))
+        kept.append(idx.astype(np.int64) + c0)
+        new_cu[r + 1] = new_cu[r] + ncu[1]
+    kept_idx = np.concatenate(kept) if kept else np.zeros(0, dtype=np.int64)
+    return kept_idx.astype(np.int32), new_cu
+
+
+def sparsify_with_context(q, k, hidden, pos, cu_seqlens_q, cu_seqlens_k, keep_ratio, *, block_size, n_obs,
+                          n_sink, scale=None):
+    """score -> quantise -> select -> compact for chunks that follow earlier context."""
+    o = importance_scores_with_context(q, k, cu_seqlens_q, cu_seqlens_k, n_obs=n_obs, scale=scale)
+    s32 = quantise_scores(o)
+    kept_idx, new_cu = select_tokens_with_context(s32, cu_seqlens_q, cu_seqlens_k, keep_ratio,
+                                                  block_size=block_size, n_obs=n_obs, n_sink=n_sink)
+    h_out, p_out = compact(hidden, pos, kept_idx)
+    return {"scores64": o, "scores": s32, "kept_idx": kept_idx, "new_cu_seqlens": new_cu,
+            "hidden_out": h_out, "pos_out": p_out}

@@ -1,0 +1,135 @@
+"""Pins of the oracle's functions for chunks that follow earlier context (no GPU)."""
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "hand_worked_scores_with_context.txt")
+
+
+def _parse_num(tok):
+    if tok.startswith("ln"):
+        return math.log(float(tok[2:]))
+    return float(Fraction(tok))
+
+
+def test_golden_hand_worked_examples_with_context():
+    n_cases = 0
+    for line in open(GOLDEN):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        head, ks, exp = [p.strip() for p in line.split("|")]
+        _, P, N, n, qv = head.split()
+        P, N, n, qv = int(P), int(N), int(n), float(qv)
+        k = np.array([_parse_num(t) for t in ks.split()]).reshape(P + N, 1, 1)
+        q = np.full((N, 1, 1), qv)
+        want = np.array([_parse_num(t) for t in exp.split()])
+        got = oracle.importance_scores_with_context(q, k, [0, N], [0, P + N], n_obs=n, scale=1.0)
+        np.testing.assert_allclose(got, want, rtol=1e-14, atol=0)
+        n_cases += 1
+    assert n_cases == 5
+
+
+def _batch(rng, Ps, Ns, Hq=4, Hkv=2, D=8):
+    cq = np.concatenate([[0], np.cumsum(Ns)])
+    ck = np.concatenate([[0], np.cumsum(np.add(Ps, Ns))])
+    q = rng.standard_normal((cq[-1], Hq, D))
+    k = rng.standard_normal((ck[-1], Hkv, D))
+    return q, k, cq, ck
+
+
+def test_without_earlier_tokens_it_is_the_plain_score():
+    rng = np.random.default_rng(0)
+    Ns = [1, 17, 0, 300, 64]
+    q, k, cq, ck = _batch(rng, [0] * len(Ns), Ns)
+    got = oracle.importance_scores_with_context(q, k, cq, ck, n_obs=32)
+    want = oracle.importance_scores(q, k, cq, n_obs=32)
+    np.testing.assert_array_equal(got, want)
+
+
+@pytest.mark.parametrize("P,N,n", [(100, 50, 16), (7, 300, 128), (513, 1, 128), (64, 64, 200), (1000, 130, 128)])
+def test_chunk_scores_are_the_tail_of_the_whole_sequence_scores(P, N, n):
+    """A chunk of N tokens after P earlier ones, window n <= N or n > N: the scores are those of
+    the sequence so far, scored as one sequence with the window min(n, N), at the chunk's tokens."""
+    rng = np.random.default_rng(P + N)
+    Hq, Hkv, D = 6, 2, 16
+    k = rng.standard_normal((P + N, Hkv, D))
+    q_chunk = rng.standard_normal((N, Hq, D))
+    q_whole = np.concatenate([np.full((P, Hq, D), np.nan), q_chunk])     # earlier queries are never read
+    whole = oracle.importance_scores(q_whole, k, [0, P + N], n_obs=min(n, N))
+    got = oracle.importance_scores_with_context(q_chunk, k, [0, N], [0, P + N], n_obs=n)
+    np.testing.assert_allclose(got, whole[P:], rtol=1e-13, atol=0)
+    # the chunk's share of the attention mass plus the earlier tokens' share is the whole
+    assert abs(got.sum() + whole[:P].sum() - 1.0) < 1e-12
+
+
+@pytest.mark.parametrize("P,N,n", [(5, 3, 2), (200, 128, 128), (1000, 40, 128), (3, 700, 64)])
+def test_harmonic_closed_form_with_context(P, N, n):
+    """Q = 0: the row at position p spreads 1/(p+1) over keys 0..p, so chunk token i gets
+    (1/n_eff) * sum over window positions p >= P+i of 1/(p+1)."""
+    rng = np.random.default_rng(3)
+    Hq, Hkv, D = 4, 2, 8
+    q = np.zeros((N, Hq, D))
+    k = rng.standard_normal((P + N, Hkv, D))
+    got = oracle.importance_scores_with_context(q, k, [0, N], [0, P + N], n_obs=n)
+    n_eff, L = min(n, N), P + N
+    want = [float(sum(Fraction(1, p + 1) for p in range(max(P + i, L - n_eff), L)) / n_eff) for i in range(N)]
+    np.testing.assert_allclose(got, want, rtol=1e-13)
+
+
+def test_softmax_library_routine_single_row():
+    """n = 1, one head: the chunk scores are the tail of scipy's softmax of the last row's logits."""
+    from scipy.special import softmax
+    rng = np.random.default_rng(4)
+    P, N, D = 37, 20, 8
+    q = rng.standard_normal((N, 1, D))
+    k = rng.standard_normal((P + N, 1, D))
+    got = oracle.importance_scores_with_context(q, k, [0, N], [0, P + N], n_obs=1)
+    want = softmax((k[:, 0, :] @ q[-1, 0, :]) / math.sqrt(D))[P:]
+    np.testing.assert_allclose(got, want, rtol=1e-13)
+
+
+def test_batch_is_the_concatenation_of_its_requests():
+    rng = np.random.default_rng(5)
+    Ps, Ns = [0, 40, 300, 5, 129], [64, 1, 200, 0, 77]
+    q, k, cq, ck = _batch(rng, Ps, Ns)
+    got = oracle.importance_scores_with_context(q, k, cq, ck, n_obs=64)
+    for r in range(len(Ns)):
+        one = oracle.importance_scores_with_context(q[cq[r]:cq[r + 1]], k[ck[r]:ck[r + 1]], [0, Ns[r]],
+                                                    [0, Ps[r] + Ns[r]], n_obs=64)
+        np.testing.assert_array_equal(got[cq[r]:cq[r + 1]], one)
+
+
+def test_sinks_inside_the_chunk():
+    assert list(oracle.sinks_in_chunk([0, 10, 20, 30], [0, 10, 25, 200], 8)) == [8, 3, 0]
+
+
+def test_selection_with_context_forces_only_the_sinks_that_fall_in_the_chunk():
+    rng = np.random.default_rng(6)
+    Ps, Ns = [0, 100, 1000], [700, 700, 700]
+    cq = np.concatenate([[0], np.cumsum(Ns)])
+    ck = np.concatenate([[0], np.cumsum(np.add(Ps, Ns))])
+    s = rng.random(cq[-1]).astype(np.float32)
+    s[cq[1]:cq[1] + 128] = 0.0          # would-be sinks of request 1: only the first 28 are forced
+    s[cq[2]:cq[2] + 128] = 0.0          # request 2 has no sink in its chunk
+    kept, new_cu = oracle.select_tokens_with_context(s, cq, ck, [0.25] * 3, block_size=64, n_obs=128, n_sink=128)
+    kept = set(int(x) for x in kept)
+    assert all(cq[0] + i in kept for i in range(128))
+    assert all(cq[1] + i in kept for i in range(28))
+    # block 0 of request 1 (64 tokens, 28 forced, k = max(16, 28) = 28): nothing but the sinks
+    assert sum(1 for i in range(64) if cq[1] + i in kept) == 28
+    # request 2, block 0: 16 kept by the index rule among all-zero scores
+    assert [i for i in range(64) if cq[2] + i in kept] == list(range(16))
+    # the last n tokens of every chunk are kept
+    for r in range(3):
+        assert all(cq[r + 1] - 1 - i in kept for i in range(128))
+    # per request it is select_tokens with the reduced sink count
+    for r, A in enumerate([128, 28, 0]):
+        idx, ncu = oracle.select_tokens(s[cq[r]:cq[r + 1]], [0, Ns[r]], [0.25], block_size=64, n_obs=128, n_sink=A)
+        assert ncu[1] == new_cu[r + 1] - new_cu[r]
+        assert set(int(x) + int(cq[r]) for x in idx) <= kept
