@@ -247,6 +247,47 @@ int uniprefill_fused_phases(const up_params* p, const void* q, const void* k, co
                             int32_t* kept_idx, int32_t* new_cu_seqlens_dev, float* scores_out,
                             void* workspace, size_t workspace_bytes, int phase_mask, void* stream);
 
+/* ---- Tokens that follow earlier context (chunked prefill) -----------------
+ *
+ * The paper scores whole prompts (Token Importance Estimation, Eq. 2-3) and runs
+ * under continuous batching (Fused Kernel and vLLM Integration), where a long
+ * prompt arrives in chunks and the keys of its earlier chunks are cached.  These
+ * variants take the keys of every sequence as its earlier tokens' keys followed
+ * by the keys of its own tokens: k is [Tk, num_kv_heads, head_dim] packed by
+ * cu_seqlens_k (int32 [R+1], device and host copies like cu_seqlens;
+ * cu_seqlens_k[0] = 0 and every sequence has at least as many keys as tokens,
+ * else UP_ERR_SHAPE), while q, hidden, pos, scores and every output stay packed
+ * by cu_seqlens over the T = total_tokens tokens.  With P_r earlier tokens, token
+ * i of sequence r sits at position P_r + i: window row j (one of the last
+ * min(n_obs, N_r) tokens) sees keys 0 .. P_r + j, its softmax runs over all of
+ * them, and token i receives the mean weight of key P_r + i -- the scores the
+ * tokens would get if the sequence so far were scored in one piece.  Selection
+ * blocks start at the sequence's first token; a token is a sink when its position
+ * P_r + i is below n_sink.  Everything else (errors, ownership, streams,
+ * workspace from the matching plan call) is as for the plain entry points; with
+ * cu_seqlens_k equal to cu_seqlens the results are those of the plain ones. */
+int uniprefill_plan_chunked(const up_params* p, const int32_t* cu_seqlens_host,
+                            const int32_t* cu_seqlens_k_host, const float* keep_ratio_host,
+                            int32_t* new_cu_seqlens_host, int64_t* total_kept,
+                            size_t* workspace_bytes);
+int uniprefill_score_chunked(const up_params* p, const void* q, const void* k,
+                             const int32_t* cu_seqlens_dev, const int32_t* cu_seqlens_host,
+                             const int32_t* cu_seqlens_k_dev, const int32_t* cu_seqlens_k_host,
+                             float* scores_out, void* workspace, size_t workspace_bytes,
+                             void* stream);
+int uniprefill_select_chunked(const up_params* p, const float* scores,
+                              const int32_t* cu_seqlens_dev, const int32_t* cu_seqlens_host,
+                              const int32_t* cu_seqlens_k_dev, const int32_t* cu_seqlens_k_host,
+                              const float* keep_ratio_dev, const float* keep_ratio_host,
+                              int32_t* kept_idx, int32_t* new_cu_seqlens_dev, void* stream);
+int uniprefill_fused_chunked(const up_params* p, const void* q, const void* k, const void* hidden,
+                             const int32_t* pos, const int32_t* cu_seqlens_dev,
+                             const int32_t* cu_seqlens_host, const int32_t* cu_seqlens_k_dev,
+                             const int32_t* cu_seqlens_k_host, const float* keep_ratio_dev,
+                             const float* keep_ratio_host, void* hidden_out, int32_t* pos_out,
+                             int32_t* kept_idx, int32_t* new_cu_seqlens_dev, float* scores_out,
+                             void* workspace, size_t workspace_bytes, void* stream);
+
 /* Static, never NULL. */
 const char* uniprefill_status_string(int status);
 

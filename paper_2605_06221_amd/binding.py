@@ -21,7 +21,8 @@ UP_BF16, UP_F32 = 0, 1
 EXPORTS = ["uniprefill_plan", "uniprefill_score", "uniprefill_select", "uniprefill_compact",
            "uniprefill_scatter", "uniprefill_fused", "uniprefill_fused_phases", "uniprefill_select_top_p",
            "uniprefill_compact_counted", "uniprefill_fused_top_p", "uniprefill_compose_index",
-           "uniprefill_slot_mapping", "uniprefill_status_string"]
+           "uniprefill_slot_mapping", "uniprefill_plan_chunked", "uniprefill_score_chunked",
+           "uniprefill_select_chunked", "uniprefill_fused_chunked", "uniprefill_status_string"]
 
 UP_PHASE_PLAN, UP_PHASE_ROW_STATS, UP_PHASE_MERGE_STATS, UP_PHASE_SWEEP_SELECT, UP_PHASE_GATHER = 1, 2, 4, 8, 16
 UP_PHASE_ALL = 31
@@ -170,6 +171,48 @@ def uniprefill_fused(p, q, k, hidden, pos, cu_seqlens_dev, cu_seqlens_host, keep
                                ptr(hidden_out), ptr(pos_out), ptr(kept_idx), ptr(new_cu_seqlens_dev),
                                ptr(scores_out), ptr(workspace), workspace_bytes, _stream(stream))
     return _check(st, "uniprefill_fused", check)
+
+
+def uniprefill_plan_chunked(p: up_params, cu_seqlens_host: np.ndarray, cu_seqlens_k_host: np.ndarray,
+                            keep_ratio_host: np.ndarray, *, want_workspace: bool = True, check: bool = True):
+    """Returns (status, new_cu_seqlens_host, total_kept, workspace_bytes)."""
+    new_cu = np.zeros(p.num_seqs + 1, dtype=np.int32)
+    total = ctypes.c_int64(0)
+    ws = ctypes.c_size_t(0)
+    st = _lib.uniprefill_plan_chunked(ctypes.byref(p), ptr(cu_seqlens_host), ptr(cu_seqlens_k_host),
+                                      ptr(keep_ratio_host), ptr(new_cu), ctypes.byref(total),
+                                      ctypes.byref(ws) if want_workspace else None)
+    _check(st, "uniprefill_plan_chunked", check)
+    return st, new_cu, int(total.value), int(ws.value)
+
+
+def uniprefill_score_chunked(p, q, k, cu_seqlens_dev, cu_seqlens_host, cu_seqlens_k_dev, cu_seqlens_k_host,
+                             scores_out, workspace, workspace_bytes, stream=None, check=True):
+    st = _lib.uniprefill_score_chunked(ctypes.byref(p), ptr(q), ptr(k), ptr(cu_seqlens_dev),
+                                       ptr(cu_seqlens_host), ptr(cu_seqlens_k_dev), ptr(cu_seqlens_k_host),
+                                       ptr(scores_out), ptr(workspace), workspace_bytes, _stream(stream))
+    return _check(st, "uniprefill_score_chunked", check)
+
+
+def uniprefill_select_chunked(p, scores, cu_seqlens_dev, cu_seqlens_host, cu_seqlens_k_dev, cu_seqlens_k_host,
+                              keep_ratio_dev, keep_ratio_host, kept_idx, new_cu_seqlens_dev, stream=None,
+                              check=True):
+    st = _lib.uniprefill_select_chunked(ctypes.byref(p), ptr(scores), ptr(cu_seqlens_dev), ptr(cu_seqlens_host),
+                                        ptr(cu_seqlens_k_dev), ptr(cu_seqlens_k_host), ptr(keep_ratio_dev),
+                                        ptr(keep_ratio_host), ptr(kept_idx), ptr(new_cu_seqlens_dev),
+                                        _stream(stream))
+    return _check(st, "uniprefill_select_chunked", check)
+
+
+def uniprefill_fused_chunked(p, q, k, hidden, pos, cu_seqlens_dev, cu_seqlens_host, cu_seqlens_k_dev,
+                             cu_seqlens_k_host, keep_ratio_dev, keep_ratio_host, hidden_out, pos_out, kept_idx,
+                             new_cu_seqlens_dev, scores_out, workspace, workspace_bytes, stream=None, check=True):
+    st = _lib.uniprefill_fused_chunked(ctypes.byref(p), ptr(q), ptr(k), ptr(hidden), ptr(pos),
+                                       ptr(cu_seqlens_dev), ptr(cu_seqlens_host), ptr(cu_seqlens_k_dev),
+                                       ptr(cu_seqlens_k_host), ptr(keep_ratio_dev), ptr(keep_ratio_host),
+                                       ptr(hidden_out), ptr(pos_out), ptr(kept_idx), ptr(new_cu_seqlens_dev),
+                                       ptr(scores_out), ptr(workspace), workspace_bytes, _stream(stream))
+    return _check(st, "uniprefill_fused_chunked", check)
 
 
 def uniprefill_fused_phases(p, q, k, hidden, pos, cu_seqlens_dev, cu_seqlens_host, keep_ratio_dev,

@@ -27,7 +27,7 @@ int check_params(const up_params* p, bool need_qk, bool need_hidden, Problem* pb
   if (p->block_size != 32 && p->block_size != 64 && p->block_size != 128) return UP_ERR_RANGE;
   if (p->n_obs < 1 || p->n_obs > kMaxNObs || p->n_sink < 0) return UP_ERR_RANGE;
   Problem q{};
-  q.R = p->num_seqs; q.T = p->total_tokens;
+  q.R = p->num_seqs; q.T = p->total_tokens; q.Tk = q.T;
   q.G = p->block_size; q.n_obs = p->n_obs; q.n_sink = p->n_sink;
   q.Hq = p->num_q_heads; q.Hkv = p->num_kv_heads; q.d = p->hidden_dim;
   q.q_stride = p->q_row_stride; q.k_stride = p->k_row_stride; q.h_stride = p->hidden_row_stride;
@@ -63,6 +63,8 @@ int check_params(const up_params* p, bool need_qk, bool need_hidden, Problem* pb
   q.key_block = narrow_only(q) ? 256 : 512;
   q.key_block_slots = q.T / q.key_block + q.R;
   q.split = 1;
+  q.key_block2 = q.key_block; q.split2 = 1; q.spare2 = 1; q.key_block_slots2 = q.key_block_slots;
+  q.via_finish = 0;
   q.max_key_blocks = q.key_block_slots;
   const long long rs = (long long)q.R * q.n_obs;
   q.row_slots = rs < q.T ? (int)rs : q.T;
@@ -79,6 +81,16 @@ int check_cu(const up_params* p, const int32_t* cu_host) {
   return UP_OK;
 }
 
+// Key-side offsets of tokens that follow earlier context: every sequence has at least as many
+// keys as tokens.
+int check_cu_k(const up_params* p, const int32_t* cu_host, const int32_t* cu_k_host) {
+  if (cu_k_host == nullptr) return UP_ERR_NULL;
+  if (cu_k_host[0] != 0) return UP_ERR_SHAPE;
+  for (int r = 0; r < p->num_seqs; ++r)
+    if (cu_k_host[r + 1] - cu_k_host[r] < cu_host[r + 1] - cu_host[r]) return UP_ERR_SHAPE;
+  return UP_OK;
+}
+
 int check_ratio(const up_params* p, const float* ratio_host) {
   if (ratio_host == nullptr) return UP_ERR_NULL;
   for (int r = 0; r < p->num_seqs; ++r)
@@ -91,50 +103,93 @@ int check_ratio(const up_params* p, const float* ratio_host) {
 // split leaves most of the chip idle) and `split` work-groups share a key block, each sweeping
 // Hkv / split kv heads.  The split grows (powers of two dividing Hkv) until the launch has about
 // one work-group per CU; launches of a few rounds are split further (below).
-void choose_geometry(Problem* pb, const int32_t* cu) {
+//   live(kb)  key blocks of kb keys that have work in this pass
+//   grid(kb)  slots of the launch (the live ones plus the spares that sit between them)
+struct PassGeometry { int kb, split; };
+template <class Live, class Grid>
+PassGeometry pass_geometry(const Problem& pb, long long units_per_head, Live live, Grid grid) {
   constexpr int kCUs = 256, kEnough = 224;
-  auto blocks = [&](int kb) {
-    long long n = 0;
-    for (int r = 0; r < pb->R; ++r) n += (cu[r + 1] - cu[r] + kb - 1) / kb;
-    return n;
-  };
-  int kb = narrow_only(*pb) ? 256 : 512;
-  long long nb = blocks(kb);
+  int kb = narrow_only(pb) ? 256 : 512;
+  long long nb = live(kb);
   int split = 1;
-  auto can_double = [&]() { return 2 * split <= pb->Hkv && pb->Hkv % (2 * split) == 0; };
+  auto can_double = [&]() { return 2 * split <= pb.Hkv && pb.Hkv % (2 * split) == 0; };
   while (nb * split < kEnough && can_double()) split *= 2;
   if (nb * split < kEnough && kb == 512) {
     kb = 256;
-    nb = blocks(kb);
+    nb = live(kb);
   }
   // A launch of a few rounds balances better with shorter work-groups (their durations differ:
   // edge blocks, ragged sequences): keep halving the heads per work-group up to about six rounds,
   // as long as a work-group still sweeps eight staging units or more.
-  int longest_n = 0;
-  for (int r = 0; r < pb->R; ++r) longest_n = cu[r + 1] - cu[r] > longest_n ? cu[r + 1] - cu[r] : longest_n;
-  const long long units_per_head = ((long long)(longest_n < pb->n_obs ? longest_n : pb->n_obs) * pb->Gq + 127) / 128;
-  // The grid has one slot per key block plus one spare per sequence (T / kb + R); the spares
-  // exit at once, but they sit between the live work-groups, and a grid of more than one
-  // work-group per CU then runs as two rounds even when the live ones alone would fit in one.
-  // So it is the grid that is compared with the CU count (one sequence: its spare is the last
-  // slot and does no harm).
-  const long long slots = pb->R == 1 ? nb : (long long)pb->T / kb + pb->R;
+  // The spare slots exit at once, but they sit between the live work-groups, and a grid of more
+  // than one work-group per CU then runs as two rounds even when the live ones alone would fit in
+  // one.  So it is the grid that is compared with the CU count (one sequence: its spares come
+  // last and do no harm).
+  const long long slots = pb.R == 1 ? nb : grid(kb);
   if (slots * split > kCUs)
-    while (can_double() && nb * split < 6 * kCUs && (pb->Hkv / (2 * split)) * units_per_head >= 8) split *= 2;
-  pb->key_block = kb;
-  pb->key_block_slots = pb->T / kb + pb->R;
-  pb->split = split;
-  int longest = 0;
-  for (int r = 0; r < pb->R; ++r) longest = cu[r + 1] - cu[r] > longest ? cu[r + 1] - cu[r] : longest;
-  pb->max_key_blocks = (longest + kb - 1) / kb;
+    while (can_double() && nb * split < 6 * kCUs && (pb.Hkv / (2 * split)) * units_per_head >= 8) split *= 2;
+  return PassGeometry{kb, split};
 }
 
-long long host_total_kept(const Problem& pb, const int32_t* cu, const float* ratio,
+void choose_geometry(Problem* pb, const int32_t* cu, const int32_t* cu_k = nullptr) {
+  const int32_t* ck = cu_k != nullptr ? cu_k : cu;     // pass 1 sweeps every key
+  pb->has_ctx = cu_k != nullptr;
+  pb->Tk = ck[pb->R];
+  int longest_n = 0, longest_k = 0;
+  for (int r = 0; r < pb->R; ++r) {
+    longest_n = cu[r + 1] - cu[r] > longest_n ? cu[r + 1] - cu[r] : longest_n;
+    longest_k = ck[r + 1] - ck[r] > longest_k ? ck[r + 1] - ck[r] : longest_k;
+  }
+  const long long units_per_head = ((long long)(longest_n < pb->n_obs ? longest_n : pb->n_obs) * pb->Gq + 127) / 128;
+  const PassGeometry g1 = pass_geometry(
+      *pb, units_per_head,
+      [&](int kb) {
+        long long n = 0;
+        for (int r = 0; r < pb->R; ++r)
+          if (cu[r + 1] > cu[r]) n += (ck[r + 1] - ck[r] + kb - 1) / kb;
+        return n;
+      },
+      [&](int kb) { return (long long)pb->Tk / kb + pb->R; });
+  pb->key_block = g1.kb;
+  pb->split = g1.split;
+  pb->key_block_slots = pb->Tk / g1.kb + pb->R;
+  pb->max_key_blocks = (longest_k + g1.kb - 1) / g1.kb;
+  if (!pb->has_ctx) {
+    pb->key_block2 = g1.kb;
+    pb->split2 = g1.split;
+    pb->spare2 = 1;
+    pb->key_block_slots2 = pb->key_block_slots;
+  } else {
+    // pass 2 sweeps only the key blocks that hold keys of the tokens: from the block of the
+    // first token's key (not aligned with the tokens: one more slot per sequence) to the last
+    pb->spare2 = 2;
+    const PassGeometry g2 = pass_geometry(
+        *pb, units_per_head,
+        [&](int kb) {
+          long long n = 0;
+          for (int r = 0; r < pb->R; ++r) {
+            const int N = cu[r + 1] - cu[r], L = ck[r + 1] - ck[r];
+            if (N > 0) n += (L + kb - 1) / kb - (L - N) / kb;
+          }
+          return n;
+        },
+        [&](int kb) { return (long long)pb->T / kb + 2 * pb->R; });
+    pb->key_block2 = g2.kb;
+    pb->split2 = g2.split;
+    pb->key_block_slots2 = pb->T / g2.kb + 2 * pb->R;
+  }
+  pb->via_finish = pb->split2 > 1 || pb->has_ctx;
+}
+
+long long host_total_kept(const Problem& pb, const int32_t* cu, const int32_t* cu_k, const float* ratio,
                           int32_t* new_cu_out) {
   long long total = 0;
   if (new_cu_out) new_cu_out[0] = 0;
   for (int r = 0; r < pb.R; ++r) {
-    SeqGeom sg{cu[r + 1] - cu[r], pb.G, pb.n_obs, pb.n_sink, (double)ratio[r]};
+    const int N = cu[r + 1] - cu[r];
+    // sinks are the first A tokens of the sequence so far; earlier context holds some or all of them
+    const int earlier = cu_k != nullptr ? (cu_k[r + 1] - cu_k[r]) - N : 0;
+    SeqGeom sg{N, pb.G, pb.n_obs, imax(0, pb.n_sink - earlier), (double)ratio[r]};
     total += seq_kept(sg);
     if (new_cu_out) new_cu_out[r + 1] = (int32_t)total;
   }
@@ -143,61 +198,158 @@ long long host_total_kept(const Problem& pb, const int32_t* cu, const float* rat
 
 }  // namespace
 
-extern "C" {
+// ---- the entry points that exist with and without earlier context share these bodies
+// (cu_k_dev / cu_k_host are nullptr for sequences whose keys are their own tokens' keys)
+namespace {
 
-int uniprefill_plan(const up_params* p, const int32_t* cu_seqlens_host, const float* keep_ratio_host,
-                    int32_t* new_cu_seqlens_host, int64_t* total_kept, size_t* workspace_bytes) {
+int plan_impl(const up_params* p, const int32_t* cu_host, const int32_t* cu_k_host, bool ctx,
+              const float* ratio_host, int32_t* new_cu_host, int64_t* total_kept, size_t* workspace_bytes) {
   Problem pb;
   const bool want_ws = workspace_bytes != nullptr;
   int st = check_params(p, want_ws, false, &pb);
   if (st != UP_OK) return st;
-  if ((st = check_cu(p, cu_seqlens_host)) != UP_OK) return st;
-  if ((st = check_ratio(p, keep_ratio_host)) != UP_OK) return st;
-  const long long total = host_total_kept(pb, cu_seqlens_host, keep_ratio_host, new_cu_seqlens_host);
+  if ((st = check_cu(p, cu_host)) != UP_OK) return st;
+  if (ctx && (st = check_cu_k(p, cu_host, cu_k_host)) != UP_OK) return st;
+  if ((st = check_ratio(p, ratio_host)) != UP_OK) return st;
+  const long long total = host_total_kept(pb, cu_host, cu_k_host, ratio_host, new_cu_host);
   if (total_kept) *total_kept = total;
-  if (want_ws) choose_geometry(&pb, cu_seqlens_host);
+  if (want_ws) choose_geometry(&pb, cu_host, cu_k_host);
   if (want_ws) *workspace_bytes = workspace_layout(pb).total;
   return UP_OK;
+}
+
+int score_impl(const up_params* p, const void* q, const void* k, const int32_t* cu_dev,
+               const int32_t* cu_host, const int32_t* cu_k_dev, const int32_t* cu_k_host, bool ctx,
+               float* scores_out, void* workspace, size_t workspace_bytes, void* stream) {
+  Problem pb;
+  int st = check_params(p, true, false, &pb);
+  if (st != UP_OK) return st;
+  if (!q || !k || !cu_dev || !scores_out || (ctx && !cu_k_dev)) return UP_ERR_NULL;
+  if ((st = check_cu(p, cu_host)) != UP_OK) return st;
+  if (ctx && (st = check_cu_k(p, cu_host, cu_k_host)) != UP_OK) return st;
+  if (!aligned16(q) || !aligned16(k)) return UP_ERR_ALIGN;
+  choose_geometry(&pb, cu_host, cu_k_host);
+  if (workspace == nullptr || workspace_bytes < workspace_layout(pb).total) return UP_ERR_WORKSPACE;
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return UP_ERR_ALIGN;
+  hipStream_t s = (hipStream_t)stream;
+  if (launch_row_stats(pb, q, k, cu_dev, cu_k_dev, workspace, s) != hipSuccess) return UP_ERR_HIP;
+  if (launch_merge_stats(pb, cu_dev, cu_k_dev, workspace, s) != hipSuccess) return UP_ERR_HIP;
+  if (launch_column_sums(pb, q, k, cu_dev, cu_k_dev, workspace, scores_out, nullptr, s) != hipSuccess)
+    return UP_ERR_HIP;
+  return UP_OK;
+}
+
+int select_impl(const up_params* p, const float* scores, const int32_t* cu_dev, const int32_t* cu_host,
+                const int32_t* cu_k_dev, const int32_t* cu_k_host, bool ctx, const float* ratio_dev,
+                const float* ratio_host, int32_t* kept_idx, int32_t* new_cu_dev, void* stream) {
+  Problem pb;
+  int st = check_params(p, false, false, &pb);
+  if (st != UP_OK) return st;
+  if (!scores || !cu_dev || !ratio_dev || !kept_idx || !new_cu_dev || (ctx && !cu_k_dev)) return UP_ERR_NULL;
+  if ((st = check_cu(p, cu_host)) != UP_OK) return st;
+  if (ctx && (st = check_cu_k(p, cu_host, cu_k_host)) != UP_OK) return st;
+  if ((st = check_ratio(p, ratio_host)) != UP_OK) return st;
+  hipStream_t s = (hipStream_t)stream;
+  if (launch_plan(pb, cu_dev, cu_k_dev, ratio_dev, new_cu_dev, s) != hipSuccess) return UP_ERR_HIP;
+  const SelectArgs sa = make_select_args(pb, scores, cu_dev, cu_k_dev, ratio_dev, new_cu_dev, kept_idx);
+  if (launch_select(pb, sa, s) != hipSuccess) return UP_ERR_HIP;
+  return UP_OK;
+}
+
+int fused_impl(const up_params* p, const void* q, const void* k, const void* hidden, const int32_t* pos,
+               const int32_t* cu_dev, const int32_t* cu_host, const int32_t* cu_k_dev,
+               const int32_t* cu_k_host, bool ctx, const float* ratio_dev, const float* ratio_host,
+               void* hidden_out, int32_t* pos_out, int32_t* kept_idx, int32_t* new_cu_dev,
+               float* scores_out, void* workspace, size_t workspace_bytes, int phase_mask, void* stream) {
+  Problem pb;
+  int st = check_params(p, true, true, &pb);
+  if (st != UP_OK) return st;
+  if (!q || !k || !hidden || !cu_dev || !ratio_dev || !hidden_out || !kept_idx || !new_cu_dev ||
+      (ctx && !cu_k_dev))
+    return UP_ERR_NULL;
+  if ((pos == nullptr) != (pos_out == nullptr)) return UP_ERR_NULL;
+  if ((st = check_cu(p, cu_host)) != UP_OK) return st;
+  if (ctx && (st = check_cu_k(p, cu_host, cu_k_host)) != UP_OK) return st;
+  if ((st = check_ratio(p, ratio_host)) != UP_OK) return st;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(hidden) || !aligned16(hidden_out))
+    return UP_ERR_ALIGN;
+  choose_geometry(&pb, cu_host, cu_k_host);
+  const Workspace w = workspace_layout(pb);
+  if (workspace == nullptr || workspace_bytes < w.total) return UP_ERR_WORKSPACE;
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return UP_ERR_ALIGN;
+  if (phase_mask & ~UP_PHASE_ALL) return UP_ERR_RANGE;
+  hipStream_t s = (hipStream_t)stream;
+  if ((phase_mask & UP_PHASE_PLAN) &&
+      launch_plan(pb, cu_dev, cu_k_dev, ratio_dev, new_cu_dev, s) != hipSuccess)
+    return UP_ERR_HIP;
+  if ((phase_mask & UP_PHASE_ROW_STATS) &&
+      launch_row_stats(pb, q, k, cu_dev, cu_k_dev, workspace, s) != hipSuccess)
+    return UP_ERR_HIP;
+  if ((phase_mask & UP_PHASE_MERGE_STATS) &&
+      launch_merge_stats(pb, cu_dev, cu_k_dev, workspace, s) != hipSuccess)
+    return UP_ERR_HIP;
+  if (phase_mask & UP_PHASE_SWEEP_SELECT) {
+    const SelectArgs sa = make_select_args(pb, nullptr, cu_dev, cu_k_dev, ratio_dev, new_cu_dev, kept_idx);
+    if (launch_column_sums(pb, q, k, cu_dev, cu_k_dev, workspace, scores_out, &sa, s) != hipSuccess)
+      return UP_ERR_HIP;
+  }
+  if (phase_mask & UP_PHASE_GATHER) {
+    // one wave per kept row: measured faster than gathering inside the scoring kernel, whose
+    // work-groups all reach their gather at the same moment
+    const long long total_kept = host_total_kept(pb, cu_host, cu_k_host, ratio_host, nullptr);
+    if (launch_compact(pb, hidden, pos, kept_idx, total_kept, hidden_out, pos_out, s) != hipSuccess)
+      return UP_ERR_HIP;
+  }
+  return UP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int uniprefill_plan(const up_params* p, const int32_t* cu_seqlens_host, const float* keep_ratio_host,
+                    int32_t* new_cu_seqlens_host, int64_t* total_kept, size_t* workspace_bytes) {
+  return plan_impl(p, cu_seqlens_host, nullptr, false, keep_ratio_host, new_cu_seqlens_host, total_kept,
+                   workspace_bytes);
+}
+
+int uniprefill_plan_chunked(const up_params* p, const int32_t* cu_seqlens_host,
+                            const int32_t* cu_seqlens_k_host, const float* keep_ratio_host,
+                            int32_t* new_cu_seqlens_host, int64_t* total_kept, size_t* workspace_bytes) {
+  return plan_impl(p, cu_seqlens_host, cu_seqlens_k_host, true, keep_ratio_host, new_cu_seqlens_host,
+                   total_kept, workspace_bytes);
 }
 
 int uniprefill_score(const up_params* p, const void* q, const void* k, const int32_t* cu_seqlens_dev,
                      const int32_t* cu_seqlens_host, float* scores_out, void* workspace,
                      size_t workspace_bytes, void* stream) {
-  Problem pb;
-  int st = check_params(p, true, false, &pb);
-  if (st != UP_OK) return st;
-  if (!q || !k || !cu_seqlens_dev || !scores_out) return UP_ERR_NULL;
-  if ((st = check_cu(p, cu_seqlens_host)) != UP_OK) return st;
-  if (!aligned16(q) || !aligned16(k)) return UP_ERR_ALIGN;
-  choose_geometry(&pb, cu_seqlens_host);
-  if (workspace == nullptr || workspace_bytes < workspace_layout(pb).total) return UP_ERR_WORKSPACE;
-  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return UP_ERR_ALIGN;
-  hipStream_t s = (hipStream_t)stream;
-  if (launch_row_stats(pb, q, k, cu_seqlens_dev, workspace, s) != hipSuccess) return UP_ERR_HIP;
-  if (launch_merge_stats(pb, cu_seqlens_dev, workspace, s) != hipSuccess) return UP_ERR_HIP;
-  if (launch_column_sums(pb, q, k, cu_seqlens_dev, workspace, scores_out, nullptr, s) != hipSuccess)
-    return UP_ERR_HIP;
-  return UP_OK;
+  return score_impl(p, q, k, cu_seqlens_dev, cu_seqlens_host, nullptr, nullptr, false, scores_out,
+                    workspace, workspace_bytes, stream);
+}
+
+int uniprefill_score_chunked(const up_params* p, const void* q, const void* k,
+                             const int32_t* cu_seqlens_dev, const int32_t* cu_seqlens_host,
+                             const int32_t* cu_seqlens_k_dev, const int32_t* cu_seqlens_k_host,
+                             float* scores_out, void* workspace, size_t workspace_bytes, void* stream) {
+  return score_impl(p, q, k, cu_seqlens_dev, cu_seqlens_host, cu_seqlens_k_dev, cu_seqlens_k_host, true,
+                    scores_out, workspace, workspace_bytes, stream);
 }
 
 int uniprefill_select(const up_params* p, const float* scores, const int32_t* cu_seqlens_dev,
                       const int32_t* cu_seqlens_host, const float* keep_ratio_dev,
                       const float* keep_ratio_host, int32_t* kept_idx, int32_t* new_cu_seqlens_dev,
                       void* stream) {
-  Problem pb;
-  int st = check_params(p, false, false, &pb);
-  if (st != UP_OK) return st;
-  if (!scores || !cu_seqlens_dev || !keep_ratio_dev || !kept_idx || !new_cu_seqlens_dev)
-    return UP_ERR_NULL;
-  if ((st = check_cu(p, cu_seqlens_host)) != UP_OK) return st;
-  if ((st = check_ratio(p, keep_ratio_host)) != UP_OK) return st;
-  hipStream_t s = (hipStream_t)stream;
-  if (launch_plan(pb, cu_seqlens_dev, keep_ratio_dev, new_cu_seqlens_dev, s) != hipSuccess)
-    return UP_ERR_HIP;
-  const SelectArgs sa = make_select_args(pb, scores, cu_seqlens_dev, keep_ratio_dev, new_cu_seqlens_dev,
-                                         kept_idx);
-  if (launch_select(pb, sa, s) != hipSuccess) return UP_ERR_HIP;
-  return UP_OK;
+  return select_impl(p, scores, cu_seqlens_dev, cu_seqlens_host, nullptr, nullptr, false, keep_ratio_dev,
+                     keep_ratio_host, kept_idx, new_cu_seqlens_dev, stream);
+}
+
+int uniprefill_select_chunked(const up_params* p, const float* scores, const int32_t* cu_seqlens_dev,
+                              const int32_t* cu_seqlens_host, const int32_t* cu_seqlens_k_dev,
+                              const int32_t* cu_seqlens_k_host, const float* keep_ratio_dev,
+                              const float* keep_ratio_host, int32_t* kept_idx,
+                              int32_t* new_cu_seqlens_dev, void* stream) {
+  return select_impl(p, scores, cu_seqlens_dev, cu_seqlens_host, cu_seqlens_k_dev, cu_seqlens_k_host, true,
+                     keep_ratio_dev, keep_ratio_host, kept_idx, new_cu_seqlens_dev, stream);
 }
 
 int uniprefill_select_top_p(const up_params* p, const float* scores, const int32_t* cu_seqlens_dev,
@@ -332,46 +484,21 @@ int uniprefill_fused_phases(const up_params* p, const void* q, const void* k, co
                             const float* keep_ratio_host, void* hidden_out, int32_t* pos_out,
                             int32_t* kept_idx, int32_t* new_cu_seqlens_dev, float* scores_out,
                             void* workspace, size_t workspace_bytes, int phase_mask, void* stream) {
-  Problem pb;
-  int st = check_params(p, true, true, &pb);
-  if (st != UP_OK) return st;
-  if (!q || !k || !hidden || !cu_seqlens_dev || !keep_ratio_dev || !hidden_out || !kept_idx ||
-      !new_cu_seqlens_dev)
-    return UP_ERR_NULL;
-  if ((pos == nullptr) != (pos_out == nullptr)) return UP_ERR_NULL;
-  if ((st = check_cu(p, cu_seqlens_host)) != UP_OK) return st;
-  if ((st = check_ratio(p, keep_ratio_host)) != UP_OK) return st;
-  if (!aligned16(q) || !aligned16(k) || !aligned16(hidden) || !aligned16(hidden_out))
-    return UP_ERR_ALIGN;
-  choose_geometry(&pb, cu_seqlens_host);
-  const Workspace w = workspace_layout(pb);
-  if (workspace == nullptr || workspace_bytes < w.total) return UP_ERR_WORKSPACE;
-  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return UP_ERR_ALIGN;
-  if (phase_mask & ~UP_PHASE_ALL) return UP_ERR_RANGE;
-  hipStream_t s = (hipStream_t)stream;
-  if ((phase_mask & UP_PHASE_PLAN) &&
-      launch_plan(pb, cu_seqlens_dev, keep_ratio_dev, new_cu_seqlens_dev, s) != hipSuccess)
-    return UP_ERR_HIP;
-  if ((phase_mask & UP_PHASE_ROW_STATS) &&
-      launch_row_stats(pb, q, k, cu_seqlens_dev, workspace, s) != hipSuccess)
-    return UP_ERR_HIP;
-  if ((phase_mask & UP_PHASE_MERGE_STATS) &&
-      launch_merge_stats(pb, cu_seqlens_dev, workspace, s) != hipSuccess)
-    return UP_ERR_HIP;
-  if (phase_mask & UP_PHASE_SWEEP_SELECT) {
-    const SelectArgs sa = make_select_args(pb, nullptr, cu_seqlens_dev, keep_ratio_dev,
-                                           new_cu_seqlens_dev, kept_idx);
-    if (launch_column_sums(pb, q, k, cu_seqlens_dev, workspace, scores_out, &sa, s) != hipSuccess)
-      return UP_ERR_HIP;
-  }
-  if (phase_mask & UP_PHASE_GATHER) {
-    // one wave per kept row: measured faster than gathering inside the scoring kernel, whose
-    // work-groups all reach their gather at the same moment
-    const long long total_kept = host_total_kept(pb, cu_seqlens_host, keep_ratio_host, nullptr);
-    if (launch_compact(pb, hidden, pos, kept_idx, total_kept, hidden_out, pos_out, s) != hipSuccess)
-      return UP_ERR_HIP;
-  }
-  return UP_OK;
+  return fused_impl(p, q, k, hidden, pos, cu_seqlens_dev, cu_seqlens_host, nullptr, nullptr, false,
+                    keep_ratio_dev, keep_ratio_host, hidden_out, pos_out, kept_idx, new_cu_seqlens_dev,
+                    scores_out, workspace, workspace_bytes, phase_mask, stream);
+}
+
+int uniprefill_fused_chunked(const up_params* p, const void* q, const void* k, const void* hidden,
+                             const int32_t* pos, const int32_t* cu_seqlens_dev,
+                             const int32_t* cu_seqlens_host, const int32_t* cu_seqlens_k_dev,
+                             const int32_t* cu_seqlens_k_host, const float* keep_ratio_dev,
+                             const float* keep_ratio_host, void* hidden_out, int32_t* pos_out,
+                             int32_t* kept_idx, int32_t* new_cu_seqlens_dev, float* scores_out,
+                             void* workspace, size_t workspace_bytes, void* stream) {
+  return fused_impl(p, q, k, hidden, pos, cu_seqlens_dev, cu_seqlens_host, cu_seqlens_k_dev,
+                    cu_seqlens_k_host, true, keep_ratio_dev, keep_ratio_host, hidden_out, pos_out, kept_idx,
+                    new_cu_seqlens_dev, scores_out, workspace, workspace_bytes, UP_PHASE_ALL, stream);
 }
 
 int uniprefill_fused(const up_params* p, const void* q, const void* k, const void* hidden,

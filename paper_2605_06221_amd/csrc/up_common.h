@@ -81,7 +81,8 @@ UP_HD int seq_kept(const SeqGeom& s) { return kept_before(s, ceil_div(s.N, s.G))
 // Packed units (key chunks, selection blocks) are numbered without a prefix
 // scan: sequence r owns slots [cu[r]/unit + r, ...), which never overlap
 // because floor((c+N)/u) - floor(c/u) + 1 >= ceil(N/u).
-UP_HD int slot_base(int cu_r, int r, int unit) { return cu_r / unit + r; }
+// (spare = 2: one more slot per sequence, for units that are not aligned with the sequence start)
+UP_HD int slot_base(int cu_r, int r, int unit, int spare = 1) { return cu_r / unit + spare * r; }
 
 // Rows of per-sequence statistics: sequence r owns row slots starting at
 // min(cu[r], r * n_obs); consecutive starts differ by at least min(N_r, n_obs).
@@ -92,11 +93,12 @@ UP_HD int rowslot_base(int cu_r, int r, int n_obs) {
 
 #if defined(__HIPCC__)
 // Largest r in [0, R) with slot_base(cu[r], r, unit) <= slot.
-__device__ __forceinline__ int locate_slot(const int* __restrict__ cu, int R, int unit, int slot) {
+__device__ __forceinline__ int locate_slot(const int* __restrict__ cu, int R, int unit, int slot,
+                                           int spare = 1) {
   int lo = 0, hi = R - 1;
   while (lo < hi) {
     const int mid = (lo + hi + 1) >> 1;
-    if (slot_base(cu[mid], mid, unit) <= slot) lo = mid; else hi = mid - 1;
+    if (slot_base(cu[mid], mid, unit, spare) <= slot) lo = mid; else hi = mid - 1;
   }
   return lo;
 }

@@ -12,6 +12,8 @@ struct SelectArgs;
 // Static description of one call, derived on the host from up_params.
 struct Problem {
   int R, T;
+  int Tk;                     // key rows: T, or more when the tokens follow earlier context
+  int has_ctx;                // a key-side cu_seqlens is given
   int G, n_obs, n_sink;
   int Hq, Hkv, Gq;            // Gq = query heads per kv head
   int d;
@@ -20,9 +22,18 @@ struct Problem {
   int qk_is_f32;
   int head_dim;               // 64, 128 or 256 (256: bf16 only)
   float scale;                // softmax scale (resolved, > 0)
-  int key_block;              // keys per work-group of the scoring sweeps: 256 or 512
-  int key_block_slots;        // T / key_block + R: key blocks of all sequences (an upper bound)
+  // pass 1 (row statistics) runs over every key of every sequence
+  int key_block;              // keys per work-group: 256 or 512
+  int key_block_slots;        // Tk / key_block + R: key blocks of all sequences (an upper bound)
   int split;                  // work-groups per key block: each sweeps Hkv / split kv heads
+  // pass 2 (column sums) runs over the tokens' own keys; without earlier context its geometry is
+  // that of pass 1
+  int key_block2, split2;
+  int spare2;                 // slots per sequence beyond N / key_block2: 1, or 2 with earlier context
+                              // (the tokens' first key is then not aligned with a key block)
+  int key_block_slots2;       // T / key_block2 + spare2 * R
+  int via_finish;             // pass 2 leaves column sums in the workspace and k_finish selects
+                              // (split2 > 1, or earlier context: tokens and key blocks not aligned)
   int max_key_blocks;         // key blocks of the longest sequence
   int row_slots;              // min(T, R * n_obs): window rows of all sequences
 };
@@ -51,10 +62,11 @@ hipError_t launch_slot_mapping(const int32_t* pos_kept, const int32_t* new_cu, i
                                long long capacity, int64_t* slots, hipStream_t s);
 
 // --- selection
-hipError_t launch_plan(const Problem& pb, const int32_t* cu, const float* ratio, int32_t* new_cu,
-                       hipStream_t s);
-SelectArgs make_select_args(const Problem& pb, const float* scores, const int32_t* cu, const float* ratio,
-                            const int32_t* new_cu, int32_t* kept_idx);
+// (cu_k: key-side offsets when the tokens follow earlier context, else nullptr)
+hipError_t launch_plan(const Problem& pb, const int32_t* cu, const int32_t* cu_k, const float* ratio,
+                       int32_t* new_cu, hipStream_t s);
+SelectArgs make_select_args(const Problem& pb, const float* scores, const int32_t* cu, const int32_t* cu_k,
+                            const float* ratio, const int32_t* new_cu, int32_t* kept_idx);
 hipError_t launch_select(const Problem& pb, const SelectArgs& a, hipStream_t s);
 
 // --- block-level top-p selection (Eq. 4-6); kept_idx needs room for T entries
@@ -80,14 +92,17 @@ hipError_t launch_compact_counted(const Problem& pb, const void* hidden, const i
 
 // --- scoring (Eq. 2-3)
 // pass 1: softmax statistics of every window row per key block (into the workspace)
+// (cu_k as above; the kernels take cu itself where it is nullptr)
 hipError_t launch_row_stats(const Problem& pb, const void* q, const void* k, const int32_t* cu,
-                            void* workspace, hipStream_t s);
+                            const int32_t* cu_k, void* workspace, hipStream_t s);
 // merge of the per-block statistics into one (reference, 1/sum) per row
-hipError_t launch_merge_stats(const Problem& pb, const int32_t* cu, void* workspace, hipStream_t s);
+hipError_t launch_merge_stats(const Problem& pb, const int32_t* cu, const int32_t* cu_k, void* workspace,
+                              hipStream_t s);
 // pass 2: normalised weights summed per token; optional scores_out; sel != nullptr runs the
 // block-local top-k (in the same kernel when every key block has one work-group, otherwise in
 // k_finish)
 hipError_t launch_column_sums(const Problem& pb, const void* q, const void* k, const int32_t* cu,
-                              void* workspace, float* scores_out, const SelectArgs* sel, hipStream_t s);
+                              const int32_t* cu_k, void* workspace, float* scores_out, const SelectArgs* sel,
+                              hipStream_t s);
 
 }  // namespace up

@@ -21,6 +21,7 @@ constexpr int kMaxKeyBlock = 512;    // most tokens a work-group of the fused ke
 struct SelectArgs {
   const float* scores;      // stand-alone kernel: given scores
   const int32_t* cu;
+  const int32_t* cu_k;      // key-side offsets when the tokens follow earlier context, else nullptr
   const float* ratio;
   const int32_t* new_cu;
   int32_t* kept_idx;
@@ -32,6 +33,13 @@ struct SelectSmem {
   float score[kMaxKeyBlock];
   int cnt0, base;
 };
+
+// Sinks among the N tokens of sequence r: the first A tokens of the sequence so far, of which
+// the earlier context (cu_k given: keys minus tokens) already holds some or all.
+__device__ __forceinline__ int sinks_of(const int32_t* cu_k, int n_sink, int r, int N) {
+  if (cu_k == nullptr) return n_sink;
+  return imax(0, n_sink - ((cu_k[r + 1] - cu_k[r]) - N));
+}
 
 // Monotone IEEE-754 -> unsigned map of Eq. 14 (sign read from the sign bit).
 __device__ __forceinline__ unsigned phi(float x) {
@@ -46,7 +54,8 @@ __device__ __forceinline__ void select_block(const SelectArgs& a, SelectSmem& sm
                                              int g, const float* block_scores) {
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
-  SeqGeom sg{N, a.G, a.n_obs, a.n_sink, (double)a.ratio[r]};
+  const int n_sink = sinks_of(a.cu_k, a.n_sink, r, N);
+  SeqGeom sg{N, a.G, a.n_obs, n_sink, (double)a.ratio[r]};
   const int lo = g * a.G;
   const int L = imin(a.G, N - lo);
   const int kg = block_kept(sg, g);
@@ -54,7 +63,7 @@ __device__ __forceinline__ void select_block(const SelectArgs& a, SelectSmem& sm
 
   if (tid < L) {
     const int i = lo + tid;
-    const bool forced = (i < a.n_sink) || (i >= N - a.n_obs);
+    const bool forced = (i < n_sink) || (i >= N - a.n_obs);
     const unsigned hi = forced ? 0xFFFFFFFFu : phi(block_scores[tid]);
     sm.keys[tid] = ((unsigned long long)hi << 32) | (unsigned)(a.G - 1 - tid);
   }

@@ -8,7 +8,7 @@ namespace up {
 
 // Per-sequence kept totals and their exclusive prefix (the compacted stream's
 // sequence offsets).  One work-group; sequences are scanned 1024 at a time.
-__global__ __launch_bounds__(1024) void k_plan(const int32_t* __restrict__ cu,
+__global__ __launch_bounds__(1024) void k_plan(const int32_t* __restrict__ cu, const int32_t* __restrict__ cu_k,
                                                const float* __restrict__ ratio, int R, int G,
                                                int n_obs, int n_sink, int32_t* __restrict__ new_cu) {
   __shared__ int wave_tot[16];
@@ -20,7 +20,8 @@ __global__ __launch_bounds__(1024) void k_plan(const int32_t* __restrict__ cu,
     const int r = base + tid;
     int v = 0;
     if (r < R) {
-      SeqGeom sg{cu[r + 1] - cu[r], G, n_obs, n_sink, (double)ratio[r]};
+      const int N = cu[r + 1] - cu[r];
+      SeqGeom sg{N, G, n_obs, sinks_of(cu_k, n_sink, r, N), (double)ratio[r]};
       v = seq_kept(sg);
     }
     // inclusive scan inside the wave, then over the 16 wave totals
@@ -53,17 +54,17 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
   select_block(a, sm, r, c0, N, g, a.scores + c0 + g * a.G);
 }
 
-SelectArgs make_select_args(const Problem& pb, const float* scores, const int32_t* cu, const float* ratio,
-                            const int32_t* new_cu, int32_t* kept_idx) {
+SelectArgs make_select_args(const Problem& pb, const float* scores, const int32_t* cu, const int32_t* cu_k,
+                            const float* ratio, const int32_t* new_cu, int32_t* kept_idx) {
   SelectArgs a;
-  a.scores = scores; a.cu = cu; a.ratio = ratio; a.new_cu = new_cu; a.kept_idx = kept_idx;
+  a.scores = scores; a.cu = cu; a.cu_k = cu_k; a.ratio = ratio; a.new_cu = new_cu; a.kept_idx = kept_idx;
   a.R = pb.R; a.T = pb.T; a.G = pb.G; a.n_obs = pb.n_obs; a.n_sink = pb.n_sink;
   return a;
 }
 
-hipError_t launch_plan(const Problem& pb, const int32_t* cu, const float* ratio, int32_t* new_cu,
-                       hipStream_t s) {
-  hipLaunchKernelGGL(k_plan, dim3(1), dim3(1024), 0, s, cu, ratio, pb.R, pb.G, pb.n_obs, pb.n_sink,
+hipError_t launch_plan(const Problem& pb, const int32_t* cu, const int32_t* cu_k, const float* ratio,
+                       int32_t* new_cu, hipStream_t s) {
+  hipLaunchKernelGGL(k_plan, dim3(1), dim3(1024), 0, s, cu, cu_k, ratio, pb.R, pb.G, pb.n_obs, pb.n_sink,
                      new_cu);
   return hipGetLastError();
 }

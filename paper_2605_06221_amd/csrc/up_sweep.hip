@@ -36,6 +36,12 @@
 // straight on to their block-local top-k.  The gather of the kept rows is a
 // launch of its own.
 //
+// Tokens that follow earlier context (chunked prefill): the keys of a sequence are then its
+// earlier tokens' keys followed by its own (`cu_k` differs from `cu`), window row j sits at
+// key position P + j (P earlier tokens), pass 1 runs over all keys, pass 2 only over key blocks
+// that hold keys of the tokens -- with a launch geometry of its own, since these are far fewer --
+// and k_finish picks each token's column sum at key P + i.
+//
 // Logits are handled in log2 units: x = s_raw * c + negref, c = scale*log2(e),
 // so the exponential is a bare v_exp_f32.
 #include <type_traits>
@@ -60,15 +66,18 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 struct SweepArgs {
   const char* q;
   const char* k;
-  const int32_t* cu;
+  const int32_t* cu;     // token offsets (queries, scores)
+  const int32_t* cu_k;   // key offsets (== cu when no sequence has earlier context)
   float2* stat_part;   // [key_block_slots][Hq * n_obs]  (reference in log2 units, sum)
   float2* stat_fin;    // [Hq][row_slots]                 (negative reference, 1/sum)
   float* scores_out;   // pass 2: optional
-  double* o_part;      // pass 2, split > 1: [key_block_slots][split][keys per block] partial column sums
+  double* o_part;      // pass 2, via_finish: [pass-2 slots][split][keys per block] partial column sums
   long long q_stride_b, k_stride_b;   // bytes between tokens
   float c;             // scale * log2(e)
   int R, T, Hq, Hkv, Gq, n_obs, row_slots;
-  int split;           // work-groups per key block; each sweeps Hkv / split kv heads
+  int split;           // work-groups per key block in this pass; each sweeps Hkv / split kv heads
+  int spare2;          // pass 2 numbers its key blocks by the tokens: slots per sequence beyond N / KB
+  int via_finish;      // pass 2 ends with the partial column sums; k_finish forms scores and selects
   int do_select;       // pass 2: run the block-local top-k
   SelectArgs sel;
 };
@@ -127,7 +136,7 @@ struct UnitCursor {
 
 template <int PASS, bool EDGE, int NW, bool F32, int D>
 __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem<NW, F32, D>& sm, int r, int c0, int N,
-                                            int kblock, int slot, int g0, int n_heads) {
+                                            int ck0, int Lk, int kblock, int slot, int g0, int n_heads) {
   constexpr int KB = 32 * NW;                               // keys per work-group
   constexpr int THREADS = 64 * NW;
   constexpr int SRCB = kHeadRowBytes<F32, D>;               // bytes of a head row in global memory
@@ -141,8 +150,11 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem<NW, F3
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
   const int l32 = lane & 31, half = lane >> 5;
+  // N tokens (queries) at packed rows c0.., Lk >= N keys at packed key rows ck0..; the tokens are
+  // the last N positions of the Lk
   const int n_eff = imin(a.n_obs, N);
-  const int first_q = N - n_eff;
+  const int first_q = N - n_eff;                   // first window row among the tokens
+  const int first_pos = Lk - n_eff;                // ... and its position among the keys
   const int rows_total = n_eff * a.Gq;
   const int n_units = (rows_total + kUnit - 1) / kUnit;
   const int n_flat = n_heads * n_units;            // this work-group sweeps kv heads g0 .. g0 + n_heads - 1
@@ -163,7 +175,7 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem<NW, F3
   constexpr int HOFF = F32 ? SRCB / 2 : 16;       // byte offset of the second lane half
   constexpr int KSTEP = F32 ? 16 : 32;            // bytes between a lane's register groups
   u32x4 kf[KREG];
-  const char* k_lane = a.k + (long long)(c0 + imin(key_base + l32, N - 1)) * a.k_stride_b + half * HOFF;
+  const char* k_lane = a.k + (long long)(ck0 + imin(key_base + l32, Lk - 1)) * a.k_stride_b + half * HOFF;
   auto load_keys = [&](int g) {
 #pragma unroll
     for (int kk = 0; kk < KREG; ++kk)
@@ -216,7 +228,7 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem<NW, F3
   auto fetch_meta = [&](const UnitCursor& uc) {
     int hh, jj;
     const bool have = unit_row(uc, tid & (kUnit - 1), hh, jj);
-    pre_pos = have ? first_q + jj : -1;
+    pre_pos = have ? first_pos + jj : -1;
     if (PASS == 2) {
       const float2 v = a.stat_fin[(size_t)(uc.g * a.Gq + hh) * a.row_slots + rs0 + jj];
       pre_cst = have ? v : make_float2(-INFINITY, 0.0f);   // no such row: weight exactly zero
@@ -392,11 +404,11 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem<NW, F3
         // range; otherwise any tile of a wave whose keys reach the window is treated as mixed.
         bool none = false, mixed;
         if (whole_heads) {
-          const int r_lo = first_q + cur.jj0 + 32 * rt;
+          const int r_lo = first_pos + cur.jj0 + 32 * rt;
           none = key_base > r_lo + 31;
           mixed = key_base + 31 > r_lo;
         } else {
-          mixed = key_base + 31 > first_q;
+          mixed = key_base + 31 > first_pos;
         }
         if (none) {
           if (PASS == 1) {
@@ -439,24 +451,30 @@ __global__ __launch_bounds__(64 * NW) void k_sweep(SweepArgs a) {
   constexpr int KB = 32 * NW;
   __shared__ SweepSmem<NW, F32, D> sm;
   const int slot = blockIdx.x / a.split, part = blockIdx.x % a.split;
-  const int r = locate_slot(a.cu, a.R, KB, slot);
+  // pass 1 numbers the key blocks of all keys; pass 2 only those that hold keys of the tokens
+  // (column sums are not wanted for the earlier context), starting with the block of the first one
+  const int r = PASS == 1 ? locate_slot(a.cu_k, a.R, KB, slot) : locate_slot(a.cu, a.R, KB, slot, a.spare2);
+  const int ck0 = a.cu_k[r];
+  const int Lk = a.cu_k[r + 1] - ck0;
   const int c0 = a.cu[r];
   const int N = a.cu[r + 1] - c0;
-  const int kblock = slot - slot_base(c0, r, KB);
-  if (kblock * KB >= N) return;
+  const int kblock = PASS == 1 ? slot - slot_base(ck0, r, KB)
+                               : (Lk - N) / KB + slot - slot_base(c0, r, KB, a.spare2);
+  if (kblock * KB >= Lk || N == 0) return;
   const int n_eff = imin(a.n_obs, N);
   // causal masking and the ragged end only matter where keys reach the query window
-  const bool edge = (kblock + 1) * KB - 1 > N - n_eff;
+  const bool edge = (kblock + 1) * KB - 1 > Lk - n_eff;
   const int n_heads = a.Hkv / a.split;
-  if (edge) sweep_block<PASS, true, NW, F32, D>(a, sm, r, c0, N, kblock, slot, part * n_heads, n_heads);
-  else sweep_block<PASS, false, NW, F32, D>(a, sm, r, c0, N, kblock, slot, part * n_heads, n_heads);
+  if (edge) sweep_block<PASS, true, NW, F32, D>(a, sm, r, c0, N, ck0, Lk, kblock, slot, part * n_heads, n_heads);
+  else sweep_block<PASS, false, NW, F32, D>(a, sm, r, c0, N, ck0, Lk, kblock, slot, part * n_heads, n_heads);
 
   if (PASS == 2) {
     __syncthreads();
     const int tid = threadIdx.x;
-    if (a.split > 1) {
-      // the key block's heads are shared by `split` work-groups: each leaves its partial sums in
-      // the workspace and k_finish adds them up (in a fixed order) after this kernel has ended
+    if (a.via_finish) {
+      // the key block's heads are shared by `split` work-groups, or its keys are not aligned with
+      // the tokens' selection blocks: each work-group leaves its partial sums in the workspace and
+      // k_finish adds them up (in a fixed order) after this kernel has ended
       if (tid < KB) a.o_part[((size_t)slot * a.split + part) * KB + tid] = sm.tail.o64[tid];
       return;
     }
@@ -480,10 +498,10 @@ __global__ __launch_bounds__(64 * NW) void k_sweep(SweepArgs a) {
   }
 }
 
-// When the kv heads of a key block were shared by several work-groups (split > 1): one
-// work-group per selection block adds the parts' column sums in a fixed order, forms the
-// scores (mean, floor) and runs the block-local top-k.
-__global__ __launch_bounds__(256) void k_finish(SweepArgs a, int key_block) {
+// When the kv heads of a key block were shared by several work-groups (split > 1), or the
+// tokens follow earlier context: one work-group per selection block adds the parts' column
+// sums in a fixed order, forms the scores (mean, floor) and runs the block-local top-k.
+__global__ __launch_bounds__(256) void k_finish(SweepArgs a, int key_block) {   // (pass 2's key block)
   __shared__ SelectSmem sm;
   const int G = a.sel.G;
   const int slot = blockIdx.x;
@@ -493,18 +511,21 @@ __global__ __launch_bounds__(256) void k_finish(SweepArgs a, int key_block) {
   const int g = slot - slot_base(c0, r, G);
   if (g * G >= N) return;   // slack slot (also every slot of an empty sequence)
   const int tid = threadIdx.x;
-  const int key = g * G + tid;
+  const int tok = g * G + tid;
   if (tid < G) {
     float sc = 0.0f;
-    if (key < N) {
+    if (tok < N) {
+      const int ck0 = a.cu_k[r];
+      const int earlier = (a.cu_k[r + 1] - ck0) - N;
+      const int key = earlier + tok;                       // the token's place among the sequence's keys
       const int kblock = key / key_block;
-      const double* part0 = a.o_part + (size_t)(slot_base(c0, r, key_block) + kblock) * a.split * key_block +
-                            (key - kblock * key_block);
+      const int slot2 = slot_base(c0, r, key_block, a.spare2) + kblock - earlier / key_block;
+      const double* part0 = a.o_part + (size_t)slot2 * a.split * key_block + (key - kblock * key_block);
       double sum = 0.0;
       for (int pp = 0; pp < a.split; ++pp) sum += part0[(size_t)pp * key_block];
       const double o = sum / (double)(imin(a.n_obs, N) * a.Hq);
       sc = o < 0x1p-64 ? 0.0f : (float)o;
-      if (a.scores_out != nullptr) a.scores_out[c0 + key] = sc;
+      if (a.scores_out != nullptr) a.scores_out[c0 + tok] = sc;
     }
     sm.score[tid] = sc;
   }
@@ -522,6 +543,7 @@ __global__ __launch_bounds__(256) void k_finish(SweepArgs a, int key_block) {
 // ends at once.
 template <int LPR>
 __global__ __launch_bounds__(32 * LPR) void k_combine(const int32_t* __restrict__ cu,
+                                                      const int32_t* __restrict__ cu_k,
                                                       const float2* __restrict__ stat_part,
                                                       float2* __restrict__ stat_fin, int R, int Hq,
                                                       int n_obs, int row_slots, int key_block) {
@@ -541,8 +563,9 @@ __global__ __launch_bounds__(32 * LPR) void k_combine(const int32_t* __restrict_
     const int jj = u - rowslot_base(c0, r, n_obs);
     live = jj < imin(n_obs, N);
     if (live) {
-      n_blocks = ceil_div(N, key_block);
-      p = stat_part + (size_t)slot_base(c0, r, key_block) * stride + (size_t)h * n_obs + jj;
+      const int ck0 = cu_k[r];
+      n_blocks = ceil_div(cu_k[r + 1] - ck0, key_block);
+      p = stat_part + (size_t)slot_base(ck0, r, key_block) * stride + (size_t)h * n_obs + jj;
     }
   }
   if (__syncthreads_or(live) == 0) return;
@@ -600,22 +623,24 @@ Workspace workspace_layout(const Problem& pb) {
   w.stat_fin_off = off;
   off = al(off + (size_t)pb.row_slots * pb.Hq * sizeof(float2));
   w.o_part_off = off;
-  if (pb.split > 1) off = al(off + (size_t)pb.key_block_slots * pb.split * pb.key_block * sizeof(double));
+  if (pb.via_finish) off = al(off + (size_t)pb.key_block_slots2 * pb.split2 * pb.key_block2 * sizeof(double));
   w.total = off;
   return w;
 }
 
 static SweepArgs make_sweep_args(const Problem& pb, const void* q, const void* k, const int32_t* cu,
-                                 void* workspace) {
+                                 const int32_t* cu_k, void* workspace) {
   const Workspace w = workspace_layout(pb);
   char* ws = (char*)workspace;
   SweepArgs a{};
-  a.q = (const char*)q; a.k = (const char*)k; a.cu = cu;
+  a.q = (const char*)q; a.k = (const char*)k; a.cu = cu; a.cu_k = cu_k != nullptr ? cu_k : cu;
   a.stat_part = (float2*)(ws + w.stat_part_off);
   a.stat_fin = (float2*)(ws + w.stat_fin_off);
   a.scores_out = nullptr;
   a.o_part = (double*)(ws + w.o_part_off);
-  a.split = pb.split;
+  a.split = pb.split;              // (pass 2 overwrites it)
+  a.spare2 = pb.spare2;
+  a.via_finish = pb.via_finish;
   const int eb = pb.qk_is_f32 ? 4 : 2;
   a.q_stride_b = pb.q_stride * eb; a.k_stride_b = pb.k_stride * eb;
   a.c = pb.scale * 1.44269504088896340736f;
@@ -630,8 +655,8 @@ static SweepArgs make_sweep_args(const Problem& pb, const void* q, const void* k
 // head rows of up to 256 bytes in bf16.
 template <int PASS>
 static hipError_t launch_sweep(const Problem& pb, const SweepArgs& a, hipStream_t s) {
-  const dim3 grid((unsigned)(pb.key_block_slots * pb.split));
-  const bool wide = pb.key_block == 512;
+  const dim3 grid(PASS == 1 ? (unsigned)(pb.key_block_slots * pb.split) : (unsigned)(pb.key_block_slots2 * pb.split2));
+  const bool wide = (PASS == 1 ? pb.key_block : pb.key_block2) == 512;
 #define UP_SWEEP(NW_, F32_, D_) hipLaunchKernelGGL((k_sweep<PASS, NW_, F32_, D_>), grid, dim3(64 * NW_), 0, s, a)
   if (pb.qk_is_f32) {
     if (wide) return hipErrorInvalidValue;
@@ -653,36 +678,39 @@ static hipError_t launch_sweep(const Problem& pb, const SweepArgs& a, hipStream_
 }
 
 hipError_t launch_row_stats(const Problem& pb, const void* q, const void* k, const int32_t* cu,
-                            void* workspace, hipStream_t s) {
+                            const int32_t* cu_k, void* workspace, hipStream_t s) {
   if (pb.T == 0) return hipSuccess;
-  const SweepArgs a = make_sweep_args(pb, q, k, cu, workspace);
+  const SweepArgs a = make_sweep_args(pb, q, k, cu, cu_k, workspace);
   return launch_sweep<1>(pb, a, s);
 }
 
-hipError_t launch_merge_stats(const Problem& pb, const int32_t* cu, void* workspace, hipStream_t s) {
+hipError_t launch_merge_stats(const Problem& pb, const int32_t* cu, const int32_t* cu_k, void* workspace,
+                              hipStream_t s) {
   if (pb.T == 0) return hipSuccess;
-  const SweepArgs a = make_sweep_args(pb, nullptr, nullptr, cu, workspace);
+  const SweepArgs a = make_sweep_args(pb, nullptr, nullptr, cu, cu_k, workspace);
   const dim3 grid((unsigned)((pb.row_slots + 31) / 32), (unsigned)pb.Hq);
   if (pb.max_key_blocks > 128)
-    hipLaunchKernelGGL(k_combine<32>, grid, dim3(1024), 0, s, cu, a.stat_part, a.stat_fin, pb.R, pb.Hq,
+    hipLaunchKernelGGL(k_combine<32>, grid, dim3(1024), 0, s, cu, a.cu_k, a.stat_part, a.stat_fin, pb.R, pb.Hq,
                        pb.n_obs, pb.row_slots, pb.key_block);
   else
-    hipLaunchKernelGGL(k_combine<8>, grid, dim3(256), 0, s, cu, a.stat_part, a.stat_fin, pb.R, pb.Hq,
+    hipLaunchKernelGGL(k_combine<8>, grid, dim3(256), 0, s, cu, a.cu_k, a.stat_part, a.stat_fin, pb.R, pb.Hq,
                        pb.n_obs, pb.row_slots, pb.key_block);
   return hipGetLastError();
 }
 
 hipError_t launch_column_sums(const Problem& pb, const void* q, const void* k, const int32_t* cu,
-                              void* workspace, float* scores_out, const SelectArgs* sel, hipStream_t s) {
+                              const int32_t* cu_k, void* workspace, float* scores_out, const SelectArgs* sel,
+                              hipStream_t s) {
   if (pb.T == 0) return hipSuccess;
-  SweepArgs a = make_sweep_args(pb, q, k, cu, workspace);
+  SweepArgs a = make_sweep_args(pb, q, k, cu, cu_k, workspace);
+  a.split = pb.split2;
   a.scores_out = scores_out;
   if (sel != nullptr) { a.sel = *sel; a.do_select = 1; }
-  else { a.sel.G = pb.G; }
+  else { a.sel.G = pb.G; a.sel.cu_k = nullptr; }
   const hipError_t e = launch_sweep<2>(pb, a, s);
   if (e != hipSuccess) return e;
-  if (pb.split > 1)
-    hipLaunchKernelGGL(k_finish, dim3((unsigned)(pb.T / pb.G + pb.R)), dim3(256), 0, s, a, pb.key_block);
+  if (pb.via_finish)
+    hipLaunchKernelGGL(k_finish, dim3((unsigned)(pb.T / pb.G + pb.R)), dim3(256), 0, s, a, pb.key_block2);
   return hipGetLastError();
 }
 

@@ -32,7 +32,14 @@ class DeviceBatch:
             n_sink=w.n_sink, num_q_heads=w.num_q_heads, num_kv_heads=w.num_kv_heads, head_dim=w.head_dim,
             hidden_dim=w.hidden_dim, softmax_scale=softmax_scale,
             qk_dtype=up.UP_BF16 if qk_f32 is None else up.UP_F32)
-        _, self.new_cu_plan, self.total_kept, self.ws_bytes = up.uniprefill_plan(self.p, self.cu_host, self.ratio_host)
+        self.ctx = w.cu_seqlens_k is not None      # the requests follow earlier context
+        if self.ctx:
+            self.cu_k_host = np.ascontiguousarray(w.cu_seqlens_k, dtype=np.int32)
+            self.cu_k = torch.from_numpy(self.cu_k_host).cuda()
+            _, self.new_cu_plan, self.total_kept, self.ws_bytes = up.uniprefill_plan_chunked(
+                self.p, self.cu_host, self.cu_k_host, self.ratio_host)
+        else:
+            _, self.new_cu_plan, self.total_kept, self.ws_bytes = up.uniprefill_plan(self.p, self.cu_host, self.ratio_host)
         T, d = w.total_tokens, w.hidden_dim
         if qk_f32 is None:
             self.q = dev_bf16(w.q)
@@ -55,16 +62,28 @@ class DeviceBatch:
 
     # ---- entry points -------------------------------------------------------
     def fused(self, want_scores=True, stream=None):
+        if self.ctx:
+            return up.uniprefill_fused_chunked(self.p, self.q, self.k, self.hidden, self.pos, self.cu, self.cu_host,
+                                               self.cu_k, self.cu_k_host, self.ratio, self.ratio_host,
+                                               self.hidden_out, self.pos_out, self.kept_idx, self.new_cu,
+                                               self.scores if want_scores else None, self.workspace,
+                                               self.ws_bytes, stream=stream)
         return up.uniprefill_fused(self.p, self.q, self.k, self.hidden, self.pos, self.cu, self.cu_host,
                                    self.ratio, self.ratio_host, self.hidden_out, self.pos_out, self.kept_idx,
                                    self.new_cu, self.scores if want_scores else None, self.workspace,
                                    self.ws_bytes, stream=stream)
 
     def score(self):
+        if self.ctx:
+            return up.uniprefill_score_chunked(self.p, self.q, self.k, self.cu, self.cu_host, self.cu_k,
+                                               self.cu_k_host, self.scores, self.workspace, self.ws_bytes)
         return up.uniprefill_score(self.p, self.q, self.k, self.cu, self.cu_host, self.scores,
                                    self.workspace, self.ws_bytes)
 
     def select(self, scores_dev):
+        if self.ctx:
+            return up.uniprefill_select_chunked(self.p, scores_dev, self.cu, self.cu_host, self.cu_k, self.cu_k_host,
+                                                self.ratio, self.ratio_host, self.kept_idx, self.new_cu)
         return up.uniprefill_select(self.p, scores_dev, self.cu, self.cu_host, self.ratio, self.ratio_host,
                                     self.kept_idx, self.new_cu)
 
@@ -96,6 +115,9 @@ def oracle_run(w, scale=None):
     import workloads
     qf = _LazyQ(w.q)      # the oracle slices only the window rows; upcast those on demand
     kf = workloads.bf16_bits_to_f32(w.k)
+    if w.cu_seqlens_k is not None:
+        return oracle.sparsify_with_context(qf, kf, w.hidden, w.pos, w.cu_seqlens, w.cu_seqlens_k, w.keep_ratio,
+                                            block_size=w.block_size, n_obs=w.n_obs, n_sink=w.n_sink, scale=scale)
     return oracle.sparsify(qf, kf, w.hidden, w.pos, w.cu_seqlens, w.keep_ratio, block_size=w.block_size,
                            n_obs=w.n_obs, n_sink=w.n_sink, scale=scale)
 
@@ -122,9 +144,10 @@ def score_margin_report(res_oracle, w):
     kept[res_oracle["kept_idx"]] = True
     best = np.inf
     cu = w.cu_seqlens
+    sinks = [w.n_sink] * w.num_seqs if w.cu_seqlens_k is None else oracle.sinks_in_chunk(cu, w.cu_seqlens_k, w.n_sink)
     for r in range(w.num_seqs):
         N = int(cu[r + 1] - cu[r])
-        f = oracle.forced_mask(N, w.n_obs, w.n_sink)
+        f = oracle.forced_mask(N, w.n_obs, int(sinks[r]))
         for lo in range(0, N, w.block_size):
             sl = slice(int(cu[r]) + lo, int(cu[r]) + min(N, lo + w.block_size))
             kk = kept[sl] & ~f[lo:lo + w.block_size]

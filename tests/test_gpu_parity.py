@@ -671,3 +671,107 @@ def test_slot_mapping_of_a_compacted_stream():
     torch.cuda.synchronize()
     np.testing.assert_array_equal(slots[:n].cpu().numpy(), want)
     assert (slots[n:] == -77).all()
+
+
+# ---- tokens that follow earlier context (chunked prefill: the keys of earlier tokens are cached)
+
+def _score_oracle_ctx(w, q=None, k=None):
+    return oracle.quantise_scores(oracle.importance_scores_with_context(
+        _q_f32(w) if q is None else q, workloads.bf16_bits_to_f32(w.k) if k is None else k,
+        w.cu_seqlens, w.cu_seqlens_k, n_obs=w.n_obs))
+
+
+@pytest.mark.parametrize("case", [
+    dict(lengths=[700], earlier=[300], Hq=8, Hkv=2, n_obs=128),
+    dict(lengths=[1, 5, 130, 0, 257, 1000, 64], earlier=[0, 1000, 77, 50, 512, 3, 2048], Hq=8, Hkv=2, n_obs=128),
+    dict(lengths=[64], earlier=[5000], Hq=4, Hkv=4, n_obs=128),
+    dict(lengths=[2100, 300], earlier=[513, 4096], Hq=12, Hkv=4, n_obs=200),
+    dict(lengths=[1500, 1500], earlier=[0, 1], Hq=40, Hkv=8, n_obs=128),
+    dict(lengths="many", earlier="many", Hq=8, Hkv=2, n_obs=128),
+    dict(lengths=[900, 77, 1], earlier=[100, 1000, 700], Hq=4, Hkv=2, n_obs=32, head_dim=64),
+    dict(lengths=[900, 77, 1], earlier=[100, 1000, 700], Hq=4, Hkv=2, n_obs=32, head_dim=256),
+])
+def test_scores_with_earlier_context_match_oracle(case):
+    if case["lengths"] == "many":
+        lengths = _many_lengths(8, 230)
+        earlier = [int(x) for x in np.random.default_rng(9).integers(0, 600, size=len(lengths))]
+    else:
+        lengths, earlier = case["lengths"], case["earlier"]
+    _say("score with context", {k: v for k, v in case.items() if v != "many"}, "T", sum(lengths), "Tk", sum(lengths) + sum(earlier))
+    w = workloads.make_custom(name="ctx", seed=17, lengths=lengths, keep_ratio=[0.5] * len(lengths), hidden_dim=8,
+                              num_q_heads=case["Hq"], num_kv_heads=case["Hkv"], block_size=64, n_obs=case["n_obs"],
+                              head_dim=case.get("head_dim", 128), earlier=earlier)
+    b = DeviceBatch(w)
+    b.score()
+    got = b.results()["scores"]
+    ok, worst = _score_close(got, _score_oracle_ctx(w))
+    _say("  worst relative score error", worst)
+    assert ok
+    assert b.canaries_intact()
+
+
+def test_scores_with_earlier_context_from_fp32_operands():
+    _say("score with context fp32")
+    w = workloads.make_custom(name="ctx32", seed=18, lengths=[700, 1, 300], keep_ratio=[0.5] * 3, hidden_dim=8,
+                              num_q_heads=8, num_kv_heads=2, block_size=64, n_obs=128, earlier=[300, 999, 0])
+    q32, k32 = _f32_operands(w, 34)
+    b = DeviceBatch(w, qk_f32=(q32, k32))
+    b.score()
+    got = b.results()["scores"].astype(np.float64)
+    want = _score_oracle_ctx(w, q32, k32).astype(np.float64)
+    err = np.abs(got - want)
+    _say("  worst relative score error", (err / np.maximum(want, 1e-300))[want > 0].max())
+    assert (err <= SCORE_RTOL_F32 * want + SCORE_ATOL).all()
+    assert b.canaries_intact()
+
+
+@pytest.mark.parametrize("case", [
+    dict(lengths=[3000, 40, 777, 9000], earlier=[1000, 0, 64, 12345], ratios=[0.3, 0.5, 0.7, 0.25], G=64),
+    dict(lengths=[8129, 8190, 1, 1, 4000], earlier=[8192, 100, 5000, 0, 17], ratios=[0.4, 0.4, 0.4, 0.4, 0.2], G=128),
+    dict(lengths=[20000], earlier=[45000], ratios=[0.3], G=32),
+])
+def test_fused_with_earlier_context_bit_exact(case):
+    _say("fused with context", case)
+    w = workloads.make_custom(name="ctxf", seed=19, lengths=case["lengths"], keep_ratio=case["ratios"],
+                              hidden_dim=64, num_q_heads=8, num_kv_heads=2, block_size=case["G"], n_obs=128,
+                              earlier=case["earlier"])
+    b = DeviceBatch(w)
+    b.fused()
+    _assert_fused_exact(w, b, oracle_run(w))
+
+
+def test_chunked_entry_with_equal_offsets_equals_the_plain_entry():
+    """cu_seqlens_k == cu_seqlens: no earlier context; every output equals the plain entry's, bit for bit
+    (the column sums take the route through the workspace, the arithmetic is the same)."""
+    _say("chunked == plain without context")
+    w = workloads.make_custom(name="ctx0", seed=20, lengths=[3000, 0, 40, 5000], keep_ratio=[0.3, 0.5, 0.5, 0.6],
+                              hidden_dim=64, num_q_heads=8, num_kv_heads=2, block_size=64, n_obs=128)
+    plain = DeviceBatch(w)
+    plain.fused()
+    want = plain.results()
+    w.cu_seqlens_k = w.cu_seqlens.copy()
+    chunked = DeviceBatch(w)
+    chunked.fused()
+    got = chunked.results()
+    for key in want:
+        np.testing.assert_array_equal(got[key], want[key], err_msg=key)
+    assert chunked.canaries_intact()
+
+
+def test_select_with_earlier_context_on_given_scores():
+    _say("select with context")
+    rng = np.random.default_rng(23)
+    lengths, earlier = [700, 64, 1, 3000, 129], [100, 0, 5000, 127, 128]
+    w = workloads.make_custom(name="ctxs", seed=21, lengths=lengths, keep_ratio=[0.25, 0.5, 0.5, 0.1, 0.9],
+                              hidden_dim=8, num_q_heads=2, num_kv_heads=1, block_size=64, n_obs=128, earlier=earlier)
+    scores = rng.random(w.total_tokens).astype(np.float32)
+    scores[rng.random(w.total_tokens) < 0.3] = 0.0        # ties
+    b = DeviceBatch(w)
+    b.select(torch.from_numpy(scores).cuda())
+    res = b.results()
+    kept, new_cu = oracle.select_tokens_with_context(scores, w.cu_seqlens, w.cu_seqlens_k, w.keep_ratio,
+                                                     block_size=64, n_obs=128, n_sink=w.n_sink)
+    np.testing.assert_array_equal(res["new_cu_seqlens"], new_cu)
+    np.testing.assert_array_equal(res["kept_idx"], kept)
+    np.testing.assert_array_equal(b.new_cu_plan, new_cu)
+    assert b.canaries_intact()

@@ -212,3 +212,41 @@ def test_slot_mapping_rejects_bad_arguments():
     assert L.uniprefill_slot_mapping(v(fake), v(fake), 2, v(fake), 8, 0, 10, v(fake), None) == up.UP_ERR_RANGE
     assert L.uniprefill_slot_mapping(v(fake), v(fake), -1, v(fake), 8, 16, 10, v(fake), None) == up.UP_ERR_RANGE
     assert L.uniprefill_slot_mapping(v(fake), v(fake), 2, v(fake), 8, 16, 0, v(fake), None) == up.UP_OK
+
+
+def test_plan_chunked_matches_oracle_and_rejects_bad_offsets():
+    import oracle
+    rng = np.random.default_rng(9)
+    for _ in range(30):
+        R = int(rng.integers(1, 9))
+        Ns = rng.integers(0, 900, size=R)
+        Ps = rng.integers(0, 400, size=R) * (rng.random(R) < 0.7)
+        G = int(rng.choice([32, 64, 128]))
+        n_obs, n_sink = int(rng.choice([16, 128, 200])), int(rng.choice([0, 4, 128]))
+        cu = np.concatenate([[0], np.cumsum(Ns)]).astype(np.int32)
+        cu_k = np.concatenate([[0], np.cumsum(Ns + Ps)]).astype(np.int32)
+        ratio = rng.uniform(0.05, 1.0, size=R).astype(np.float32)
+        p = _params(num_seqs=R, total_tokens=int(cu[-1]), block_size=G, n_obs=n_obs, n_sink=n_sink)
+        st, new_cu, total, ws = up.uniprefill_plan_chunked(p, cu, cu_k, ratio)
+        assert st == up.UP_OK and ws > 0
+        sinks = oracle.sinks_in_chunk(cu, cu_k, n_sink)
+        want = np.zeros(R + 1, np.int64)
+        for r in range(R):
+            want[r + 1] = want[r] + sum(oracle.block_kept_counts(int(Ns[r]), G, n_obs, int(sinks[r]), ratio[r]))
+        np.testing.assert_array_equal(new_cu, want)
+        assert total == want[-1]
+        # equal offsets: the plain plan
+        st2, new_cu2, total2, _ = up.uniprefill_plan_chunked(p, cu, cu, ratio)
+        _, new_cu3, total3, _ = up.uniprefill_plan(p, cu, ratio)
+        np.testing.assert_array_equal(new_cu2, new_cu3)
+        assert total2 == total3
+    cu = np.array([0, 100, 300], np.int32)
+    ratio = np.array([0.5, 0.5], np.float32)
+    p = _params(num_seqs=2, total_tokens=300)
+    plan = lambda ck: up.uniprefill_plan_chunked(p, cu, ck, ratio, check=False)[0]
+    assert plan(np.array([0, 100, 300], np.int32)) == up.UP_OK
+    assert plan(np.array([0, 1000, 1200], np.int32)) == up.UP_OK
+    assert plan(np.array([0, 99, 400], np.int32)) == up.UP_ERR_SHAPE      # fewer keys than tokens
+    assert plan(np.array([5, 105, 305], np.int32)) == up.UP_ERR_SHAPE     # does not start at zero
+    assert up.lib().uniprefill_plan_chunked(ctypes.byref(p), up.ptr(cu), None, up.ptr(ratio), None, None,
+                                            None) == up.UP_ERR_NULL

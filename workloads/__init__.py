@@ -74,6 +74,8 @@ class Workload:
                                       last n_obs tokens are NaN (never read)
     k          : uint16 [T, Hkv, D]   bf16 bits
     pos        : int32 [T]     position ids (data, gathered like a column)
+    cu_seqlens_k : None, or int32 [R+1] when the requests follow earlier context: k is then
+                   [Tk, Hkv, D], per request the keys of its earlier tokens, then of its own
     """
 
     name: str
@@ -92,6 +94,7 @@ class Workload:
     pos: np.ndarray
     seed: int = 0
     notes: dict = field(default_factory=dict)
+    cu_seqlens_k: np.ndarray | None = None
 
     @property
     def num_seqs(self) -> int:
@@ -135,11 +138,15 @@ def make_custom(
     k_row_lognormal: bool = False,
     pos_offsets=None,
     rng: np.random.Generator | None = None,
+    earlier=None,
 ) -> Workload:
     """Draw one batch.  Draw order: hidden, q (window rows only), k, extra scales.
 
     (Lengths, ratios and position offsets are drawn by the caller from the same
-    generator *before* this call when they are random.)"""
+    generator *before* this call when they are random.)
+
+    ``earlier`` = tokens of earlier context per request (chunked prefill): k then has
+    ``earlier[r] + lengths[r]`` rows per request and position ids start at ``earlier[r]``."""
     rng = np.random.default_rng(seed) if rng is None else rng
     lengths = np.asarray(lengths, dtype=np.int64)
     R = int(lengths.shape[0])
@@ -147,6 +154,14 @@ def make_custom(
     cu[1:] = np.cumsum(lengths)
     T = int(cu[-1])
     ratio = np.asarray(keep_ratio, dtype=np.float32).reshape(R)
+    cu_k = None
+    Tk = T
+    if earlier is not None:
+        cu_k = np.zeros(R + 1, dtype=np.int32)
+        cu_k[1:] = np.cumsum(lengths + np.asarray(earlier, dtype=np.int64))
+        Tk = int(cu_k[-1])
+        if pos_offsets is None:
+            pos_offsets = [int(e) for e in earlier]
 
     hidden = _normal_bf16(rng, (T, hidden_dim))
 
@@ -157,13 +172,13 @@ def make_custom(
             q[cu[r + 1] - n_eff:cu[r + 1]] = _normal_bf16(rng, (n_eff, num_q_heads, head_dim))
 
     if k_row_lognormal:
-        kf = rng.standard_normal((T, num_kv_heads, head_dim), dtype=np.float32)
-        z = rng.standard_normal(T, dtype=np.float32)
+        kf = rng.standard_normal((Tk, num_kv_heads, head_dim), dtype=np.float32)
+        z = rng.standard_normal(Tk, dtype=np.float32)
         kf *= np.exp(z)[:, None, None]
         k = f32_to_bf16_bits(kf)
         del kf
     else:
-        k = _normal_bf16(rng, (T, num_kv_heads, head_dim))
+        k = _normal_bf16(rng, (Tk, num_kv_heads, head_dim))
 
     pos = np.empty(T, dtype=np.int32)
     for r in range(R):
@@ -174,7 +189,7 @@ def make_custom(
         name=name, block_size=block_size, n_obs=n_obs, n_sink=n_sink,
         num_q_heads=num_q_heads, num_kv_heads=num_kv_heads, head_dim=head_dim,
         hidden_dim=hidden_dim, cu_seqlens=cu, keep_ratio=ratio,
-        hidden=hidden, q=q, k=k, pos=pos, seed=seed,
+        hidden=hidden, q=q, k=k, pos=pos, seed=seed, cu_seqlens_k=cu_k,
     )
 
 
