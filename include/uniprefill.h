@@ -247,6 +247,17 @@ int uniprefill_fused_phases(const up_params* p, const void* q, const void* k, co
                             int32_t* kept_idx, int32_t* new_cu_seqlens_dev, float* scores_out,
                             void* workspace, size_t workspace_bytes, int phase_mask, void* stream);
 
+/* Compaction of one per-token column (Sparsity Propagation, Eq. 7, for what travels
+ * with the hidden states besides the int32 position ids that uniprefill_compact
+ * takes: 64-bit position ids, token ids, ...): column_out[t] = column[kept_idx[t]]
+ * for t < capacity, and t < total_kept_dev[0] when that device pointer is given
+ * (the count of a top-p selection).  column is a device array of total_tokens
+ * elements of elem_bytes = 4 or 8 bytes (else UP_ERR_UNSUPPORTED), aligned to its
+ * element size (UP_ERR_ALIGN); column_out has room for capacity elements. */
+int uniprefill_compact_column(const void* column, int32_t elem_bytes, const int32_t* kept_idx,
+                              int64_t capacity, const int32_t* total_kept_dev, void* column_out,
+                              void* stream);
+
 /* ---- Tokens that follow earlier context (chunked prefill) -----------------
  *
  * The paper scores whole prompts (Token Importance Estimation, Eq. 2-3) and runs

@@ -22,7 +22,8 @@ EXPORTS = ["uniprefill_plan", "uniprefill_score", "uniprefill_select", "uniprefi
            "uniprefill_scatter", "uniprefill_fused", "uniprefill_fused_phases", "uniprefill_select_top_p",
            "uniprefill_compact_counted", "uniprefill_fused_top_p", "uniprefill_compose_index",
            "uniprefill_slot_mapping", "uniprefill_plan_chunked", "uniprefill_score_chunked",
-           "uniprefill_select_chunked", "uniprefill_fused_chunked", "uniprefill_status_string"]
+           "uniprefill_select_chunked", "uniprefill_fused_chunked", "uniprefill_compact_column",
+           "uniprefill_status_string"]
 
 UP_PHASE_PLAN, UP_PHASE_ROW_STATS, UP_PHASE_MERGE_STATS, UP_PHASE_SWEEP_SELECT, UP_PHASE_GATHER = 1, 2, 4, 8, 16
 UP_PHASE_ALL = 31
@@ -171,6 +172,13 @@ def uniprefill_fused(p, q, k, hidden, pos, cu_seqlens_dev, cu_seqlens_host, keep
                                ptr(hidden_out), ptr(pos_out), ptr(kept_idx), ptr(new_cu_seqlens_dev),
                                ptr(scores_out), ptr(workspace), workspace_bytes, _stream(stream))
     return _check(st, "uniprefill_fused", check)
+
+
+def uniprefill_compact_column(column, elem_bytes, kept_idx, capacity, total_kept_dev, column_out, stream=None,
+                              check=True):
+    st = _lib.uniprefill_compact_column(ptr(column), int(elem_bytes), ptr(kept_idx), ctypes.c_int64(capacity),
+                                        ptr(total_kept_dev), ptr(column_out), _stream(stream))
+    return _check(st, "uniprefill_compact_column", check)
 
 
 def uniprefill_plan_chunked(p: up_params, cu_seqlens_host: np.ndarray, cu_seqlens_k_host: np.ndarray,

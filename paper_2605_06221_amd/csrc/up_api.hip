@@ -466,6 +466,22 @@ int uniprefill_compose_index(const int32_t* outer_idx, int64_t n_outer, const in
   return UP_OK;
 }
 
+int uniprefill_compact_column(const void* column, int32_t elem_bytes, const int32_t* kept_idx,
+                              int64_t capacity, const int32_t* total_kept_dev, void* column_out,
+                              void* stream) {
+  if (elem_bytes != 4 && elem_bytes != 8) return UP_ERR_UNSUPPORTED;
+  if (capacity < 0) return UP_ERR_RANGE;
+  if (capacity == 0) return UP_OK;
+  if (!column || !kept_idx || !column_out) return UP_ERR_NULL;
+  const uintptr_t mask = (uintptr_t)elem_bytes - 1;
+  if ((reinterpret_cast<uintptr_t>(column) & mask) || (reinterpret_cast<uintptr_t>(column_out) & mask))
+    return UP_ERR_ALIGN;
+  if (launch_column(column, elem_bytes, kept_idx, capacity, total_kept_dev, column_out,
+                    (hipStream_t)stream) != hipSuccess)
+    return UP_ERR_HIP;
+  return UP_OK;
+}
+
 int uniprefill_slot_mapping(const int32_t* pos_kept, const int32_t* new_cu_seqlens_dev, int32_t num_seqs,
                             const int32_t* block_table, int64_t block_table_stride, int32_t kv_block_size,
                             int64_t capacity, int64_t* slots, void* stream) {

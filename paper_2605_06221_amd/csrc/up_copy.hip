@@ -67,6 +67,17 @@ __global__ __launch_bounds__(256) void k_compose(const int32_t* __restrict__ out
   out[t] = outer[inner[t]];
 }
 
+// Gather of one per-token column of 4- or 8-byte elements (Eq. 7 for position ids of either
+// width, token ids, ...): out[t] = column[idx[t]].
+template <typename E>
+__global__ __launch_bounds__(256) void k_column(const E* __restrict__ column, const int32_t* __restrict__ idx,
+                                                long long n, const int32_t* __restrict__ count_dev,
+                                                E* __restrict__ out) {
+  const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (t >= n || (count_dev != nullptr && t >= (long long)count_dev[0])) return;
+  out[t] = column[idx[t]];
+}
+
 // Physical KV-cache slot of every retained token (Eq. 16): token t of sequence r (found from
 // the compacted stream's offsets) at logical position p goes to block_table[r][p / B] * B + p % B.
 __global__ __launch_bounds__(256) void k_slot_mapping(const int32_t* __restrict__ pos_kept,
@@ -87,6 +98,19 @@ hipError_t launch_slot_mapping(const int32_t* pos_kept, const int32_t* new_cu, i
   if (capacity == 0 || R == 0) return hipSuccess;
   hipLaunchKernelGGL(k_slot_mapping, dim3((unsigned)((capacity + 255) / 256)), dim3(256), 0, s, pos_kept, new_cu,
                      R, block_table, table_stride, kv_block, capacity, slots);
+  return hipGetLastError();
+}
+
+hipError_t launch_column(const void* column, int elem_bytes, const int32_t* idx, long long n,
+                         const int32_t* count_dev, void* out, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  const dim3 grid((unsigned)((n + 255) / 256));
+  if (elem_bytes == 8)
+    hipLaunchKernelGGL(k_column<uint64_t>, grid, dim3(256), 0, s, (const uint64_t*)column, idx, n, count_dev,
+                       (uint64_t*)out);
+  else
+    hipLaunchKernelGGL(k_column<uint32_t>, grid, dim3(256), 0, s, (const uint32_t*)column, idx, n, count_dev,
+                       (uint32_t*)out);
   return hipGetLastError();
 }
 

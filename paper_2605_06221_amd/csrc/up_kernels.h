@@ -56,6 +56,10 @@ hipError_t launch_scatter(const Problem& pb, const void* hidden_compact, const i
 hipError_t launch_compose(const int32_t* outer, const int32_t* inner, long long n,
                           const int32_t* count_dev, int32_t* out, hipStream_t s);
 
+// one per-token column of 4- or 8-byte elements: out[t] = column[idx[t]], t < n (and < count_dev[0])
+hipError_t launch_column(const void* column, int elem_bytes, const int32_t* idx, long long n,
+                         const int32_t* count_dev, void* out, hipStream_t s);
+
 // physical KV-cache slots of the retained tokens (Eq. 16); the token count is new_cu[R] on the device
 hipError_t launch_slot_mapping(const int32_t* pos_kept, const int32_t* new_cu, int R,
                                const int32_t* block_table, long long table_stride, int kv_block,

@@ -775,3 +775,28 @@ def test_select_with_earlier_context_on_given_scores():
     np.testing.assert_array_equal(res["kept_idx"], kept)
     np.testing.assert_array_equal(b.new_cu_plan, new_cu)
     assert b.canaries_intact()
+
+
+@pytest.mark.parametrize("dtype", [np.int64, np.int32])
+def test_compact_column_of_position_ids(dtype):
+    """64-bit (and 32-bit) per-token columns follow the kept indices like the hidden rows (Eq. 7);
+    with a count on the device only that many entries are written."""
+    _say("compact column", dtype.__name__)
+    rng = np.random.default_rng(31)
+    T = 100003
+    column = rng.integers(-2**40 if dtype == np.int64 else -2**30, 2**40 if dtype == np.int64 else 2**30, size=T).astype(dtype)
+    kept = np.sort(rng.choice(T, size=33333, replace=False)).astype(np.int32)
+    want, _ = oracle.compact(column, column, kept)
+    col_d, kept_d = torch.from_numpy(column).cuda(), torch.from_numpy(kept).cuda()
+    out = torch.full((len(kept) + 64,), -77, dtype=col_d.dtype, device="cuda")
+    up.uniprefill_compact_column(col_d, column.itemsize, kept_d, len(kept), None, out)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(out[:len(kept)].cpu().numpy(), want)
+    assert bool((out[len(kept):] == -77).all())
+    # count on the device, smaller than the capacity
+    out.fill_(-77)
+    count = torch.tensor([1000], dtype=torch.int32, device="cuda")
+    up.uniprefill_compact_column(col_d, column.itemsize, kept_d, len(kept), count, out)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(out[:1000].cpu().numpy(), want[:1000])
+    assert bool((out[1000:] == -77).all())

@@ -250,3 +250,17 @@ def test_plan_chunked_matches_oracle_and_rejects_bad_offsets():
     assert plan(np.array([5, 105, 305], np.int32)) == up.UP_ERR_SHAPE     # does not start at zero
     assert up.lib().uniprefill_plan_chunked(ctypes.byref(p), up.ptr(cu), None, up.ptr(ratio), None, None,
                                             None) == up.UP_ERR_NULL
+
+
+def test_compact_column_rejects_bad_arguments():
+    L = up.lib()
+    fake = ctypes.c_void_p(0x1000)
+    call = lambda col, eb, idx, cap, out: L.uniprefill_compact_column(col, eb, idx, ctypes.c_int64(cap), None, out, None)
+    assert call(fake, 2, fake, 10, fake) == up.UP_ERR_UNSUPPORTED
+    assert call(fake, 8, fake, -1, fake) == up.UP_ERR_RANGE
+    assert call(fake, 8, fake, 0, fake) == up.UP_OK            # nothing to do, nothing launched
+    assert call(None, 8, fake, 10, fake) == up.UP_ERR_NULL
+    assert call(fake, 8, None, 10, fake) == up.UP_ERR_NULL
+    assert call(fake, 8, fake, 10, None) == up.UP_ERR_NULL
+    assert call(ctypes.c_void_p(0x1004), 8, fake, 10, fake) == up.UP_ERR_ALIGN
+    assert call(fake, 4, fake, 10, ctypes.c_void_p(0x1002)) == up.UP_ERR_ALIGN
