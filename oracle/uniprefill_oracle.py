@@ -357,6 +357,23 @@ def seqused(retained_len_at_last_drop, kv_len, orig_len):
     return (s + (np.asarray(kv_len, dtype=np.int64) - np.asarray(orig_len, dtype=np.int64))).astype(np.int32)
 
 
+def seqused_per_layer(drop_layers, retained, kv_len, orig_len, num_layers):
+    """Eq. 17 for every layer: int32 [num_layers, R].  ``drop_layers`` are the layers l_k of the drop
+    events (ascending), ``retained[k][r]`` the length s_k^r request r kept at event k.  Layer l sees
+    the length kept by the last event at a layer strictly before l -- the whole prompt if there is
+    none -- plus the tokens appended since prefill."""
+    drop_layers = [int(x) for x in drop_layers]
+    retained = np.asarray(retained, dtype=np.int64).reshape(len(drop_layers), -1)
+    kv = np.asarray(kv_len, dtype=np.int64)
+    orig = np.asarray(orig_len, dtype=np.int64)
+    out = np.zeros((int(num_layers), orig.shape[0]), dtype=np.int32)
+    for layer in range(int(num_layers)):
+        before = [k for k, lk in enumerate(drop_layers) if lk < layer]
+        s = retained[max(before)] if before else orig
+        out[layer] = s + (kv - orig)
+    return out
+
+
 # --------------------------------------------------------------------------- #
 # chunks that follow earlier context  (chunked prefill: keys of earlier tokens are cached)
 # --------------------------------------------------------------------------- #

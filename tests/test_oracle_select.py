@@ -409,3 +409,27 @@ def test_kv_slot_mapping_and_seqused_small_cases():
     s = oracle.kv_slot_mapping(pos, [0, 200, 323], bt, 16)
     assert len(set(s.tolist())) == 323
     np.testing.assert_array_equal(oracle.seqused([100, 7], [1030, 9], [1024, 8]), [106, 8])
+
+
+def test_seqused_per_layer_hand_worked_history():
+    """Eq. 17 on a history worked by hand: 6 layers, drops at layers 1 and 3.  Request 0: prompt of
+    1000 tokens, 400 kept at layer 1, 150 at layer 3, 5 tokens decoded since; request 1: prompt of
+    8, nothing dropped (8, 8), 1 token decoded.  Layers up to and including the first drop layer
+    see the whole prompt; a drop takes effect in the layers after it."""
+    got = oracle.seqused_per_layer([1, 3], [[400, 8], [150, 8]], [1005, 9], [1000, 8], 6)
+    np.testing.assert_array_equal(got, [[1005, 9], [1005, 9], [405, 9], [405, 9], [155, 9], [155, 9]])
+    # no drop events: every layer sees the whole KV length
+    got = oracle.seqused_per_layer([], np.zeros((0, 2)), [1005, 9], [1000, 8], 3)
+    np.testing.assert_array_equal(got, [[1005, 9]] * 3)
+    # each layer agrees with the single-layer form, and lengths never grow with depth
+    rng = np.random.default_rng(13)
+    orig = rng.integers(100, 5000, size=7)
+    hist = np.sort(rng.integers(1, 100, size=(3, 7)), axis=0)[::-1] * orig // 100 + 1
+    hist = np.minimum.accumulate(np.minimum(hist, orig), axis=0)
+    kv = orig + rng.integers(0, 50, size=7)
+    table = oracle.seqused_per_layer([0, 4, 9], hist, kv, orig, 12)
+    for layer in range(12):
+        k = max([i for i, lk in enumerate([0, 4, 9]) if lk < layer], default=None)
+        s = orig if k is None else hist[k]
+        np.testing.assert_array_equal(table[layer], oracle.seqused(s, kv, orig))
+    assert (np.diff(table.astype(np.int64), axis=0) <= 0).all()
