@@ -363,9 +363,9 @@ def seqused_per_layer(drop_layers, retained, kv_len, orig_len, num_layers):
     the length kept by the last event at a layer strictly before l -- the whole prompt if there is
     none -- plus the tokens appended since prefill."""
     drop_layers = [int(x) for x in drop_layers]
-    retained = np.asarray(retained, dtype=np.int64).reshape(len(drop_layers), -1)
     kv = np.asarray(kv_len, dtype=np.int64)
     orig = np.asarray(orig_len, dtype=np.int64)
+    retained = np.asarray(retained, dtype=np.int64).reshape(len(drop_layers), orig.shape[0])
     out = np.zeros((int(num_layers), orig.shape[0]), dtype=np.int32)
     for layer in range(int(num_layers)):
         before = [k for k, lk in enumerate(drop_layers) if lk < layer]
