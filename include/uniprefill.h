@@ -247,6 +247,20 @@ int uniprefill_fused_phases(const up_params* p, const void* q, const void* k, co
                             int32_t* kept_idx, int32_t* new_cu_seqlens_dev, float* scores_out,
                             void* workspace, size_t workspace_bytes, int phase_mask, void* stream);
 
+/* KV length every layer sees during decode (vLLM scheduler integration, Eq. 17):
+ * seqused_out[l][r] = s + (kv_len[r] - orig_len[r]) for l < num_layers, r < num_seqs,
+ * where s is the length request r retained at the last drop event at a layer
+ * strictly before l, or orig_len[r] when there is none.  drop_layers_host holds the
+ * layers of the num_drops drop events, strictly ascending and >= 0 (UP_ERR_RANGE
+ * otherwise; more than 64 events: UP_ERR_UNSUPPORTED); retained_dev is the drop
+ * history [num_drops][num_seqs] on the device (row k = the retained lengths after
+ * event k, i.e. the differences of that drop's new_cu_seqlens); kv_len_dev and
+ * orig_len_dev are int32 [num_seqs] on the device; seqused_out is int32
+ * [num_layers][num_seqs] on the device.  num_layers <= 65535. */
+int uniprefill_seqused(const int32_t* drop_layers_host, int32_t num_drops, const int32_t* retained_dev,
+                       const int32_t* kv_len_dev, const int32_t* orig_len_dev, int32_t num_seqs,
+                       int32_t num_layers, int32_t* seqused_out, void* stream);
+
 /* Compaction of one per-token column (Sparsity Propagation, Eq. 7, for what travels
  * with the hidden states besides the int32 position ids that uniprefill_compact
  * takes: 64-bit position ids, token ids, ...): column_out[t] = column[kept_idx[t]]

@@ -22,7 +22,7 @@ EXPORTS = ["uniprefill_plan", "uniprefill_score", "uniprefill_select", "uniprefi
            "uniprefill_scatter", "uniprefill_fused", "uniprefill_fused_phases", "uniprefill_select_top_p",
            "uniprefill_compact_counted", "uniprefill_fused_top_p", "uniprefill_compose_index",
            "uniprefill_slot_mapping", "uniprefill_plan_chunked", "uniprefill_score_chunked",
-           "uniprefill_select_chunked", "uniprefill_fused_chunked", "uniprefill_compact_column",
+           "uniprefill_select_chunked", "uniprefill_fused_chunked", "uniprefill_compact_column", "uniprefill_seqused",
            "uniprefill_status_string"]
 
 UP_PHASE_PLAN, UP_PHASE_ROW_STATS, UP_PHASE_MERGE_STATS, UP_PHASE_SWEEP_SELECT, UP_PHASE_GATHER = 1, 2, 4, 8, 16
@@ -179,6 +179,15 @@ def uniprefill_compact_column(column, elem_bytes, kept_idx, capacity, total_kept
     st = _lib.uniprefill_compact_column(ptr(column), int(elem_bytes), ptr(kept_idx), ctypes.c_int64(capacity),
                                         ptr(total_kept_dev), ptr(column_out), _stream(stream))
     return _check(st, "uniprefill_compact_column", check)
+
+
+def uniprefill_seqused(drop_layers_host, retained_dev, kv_len_dev, orig_len_dev, num_seqs, num_layers, seqused_out,
+                       stream=None, check=True):
+    layers = np.ascontiguousarray(drop_layers_host, dtype=np.int32)
+    st = _lib.uniprefill_seqused(ptr(layers), int(layers.shape[0]), ptr(retained_dev), ptr(kv_len_dev),
+                                 ptr(orig_len_dev), int(num_seqs), int(num_layers), ptr(seqused_out),
+                                 _stream(stream))
+    return _check(st, "uniprefill_seqused", check)
 
 
 def uniprefill_plan_chunked(p: up_params, cu_seqlens_host: np.ndarray, cu_seqlens_k_host: np.ndarray,

@@ -466,6 +466,26 @@ int uniprefill_compose_index(const int32_t* outer_idx, int64_t n_outer, const in
   return UP_OK;
 }
 
+int uniprefill_seqused(const int32_t* drop_layers_host, int32_t num_drops, const int32_t* retained_dev,
+                       const int32_t* kv_len_dev, const int32_t* orig_len_dev, int32_t num_seqs,
+                       int32_t num_layers, int32_t* seqused_out, void* stream) {
+  if (num_drops < 0 || num_seqs < 0 || num_layers < 0 || num_layers > 65535) return UP_ERR_RANGE;
+  if (num_drops > kMaxDropLayers) return UP_ERR_UNSUPPORTED;
+  if (num_drops > 0 && drop_layers_host == nullptr) return UP_ERR_NULL;
+  DropLayers drops{};
+  drops.n = num_drops;
+  for (int k = 0; k < num_drops; ++k) {
+    if (drop_layers_host[k] < 0 || (k > 0 && drop_layers_host[k] <= drop_layers_host[k - 1])) return UP_ERR_RANGE;
+    drops.layer[k] = drop_layers_host[k];
+  }
+  if (num_seqs == 0 || num_layers == 0) return UP_OK;
+  if ((num_drops > 0 && !retained_dev) || !kv_len_dev || !orig_len_dev || !seqused_out) return UP_ERR_NULL;
+  if (launch_seqused(drops, retained_dev, kv_len_dev, orig_len_dev, num_seqs, num_layers, seqused_out,
+                     (hipStream_t)stream) != hipSuccess)
+    return UP_ERR_HIP;
+  return UP_OK;
+}
+
 int uniprefill_compact_column(const void* column, int32_t elem_bytes, const int32_t* kept_idx,
                               int64_t capacity, const int32_t* total_kept_dev, void* column_out,
                               void* stream) {

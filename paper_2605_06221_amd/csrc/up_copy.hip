@@ -114,6 +114,31 @@ hipError_t launch_column(const void* column, int elem_bytes, const int32_t* idx,
   return hipGetLastError();
 }
 
+// KV length that layer l sees during decode (Eq. 17): the length request r kept at the last drop
+// event at a layer before l (the whole prompt if none), plus the tokens appended since prefill.
+__global__ __launch_bounds__(256) void k_seqused(DropLayers drops, const int32_t* __restrict__ retained,
+                                                 const int32_t* __restrict__ kv_len,
+                                                 const int32_t* __restrict__ orig_len, int R, int num_layers,
+                                                 int32_t* __restrict__ out) {
+  const int r = blockIdx.x * 256 + threadIdx.x;
+  const int layer = blockIdx.y;
+  if (r >= R) return;
+  int last = -1;
+  for (int k = 0; k < drops.n; ++k)
+    if (drops.layer[k] < layer) last = k;
+  const int orig = orig_len[r];
+  const int s = last < 0 ? orig : retained[(long long)last * R + r];
+  out[(long long)layer * R + r] = s + (kv_len[r] - orig);
+}
+
+hipError_t launch_seqused(const DropLayers& drops, const int32_t* retained, const int32_t* kv_len,
+                          const int32_t* orig_len, int R, int num_layers, int32_t* out, hipStream_t s) {
+  if (R == 0 || num_layers == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_seqused, dim3((unsigned)((R + 255) / 256), (unsigned)num_layers), dim3(256), 0, s, drops,
+                     retained, kv_len, orig_len, R, num_layers, out);
+  return hipGetLastError();
+}
+
 hipError_t launch_compose(const int32_t* outer, const int32_t* inner, long long n,
                           const int32_t* count_dev, int32_t* out, hipStream_t s) {
   if (n == 0) return hipSuccess;

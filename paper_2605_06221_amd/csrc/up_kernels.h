@@ -60,6 +60,12 @@ hipError_t launch_compose(const int32_t* outer, const int32_t* inner, long long 
 hipError_t launch_column(const void* column, int elem_bytes, const int32_t* idx, long long n,
                          const int32_t* count_dev, void* out, hipStream_t s);
 
+// per-layer KV length during decode (Eq. 17): out[l][r] for l < num_layers
+constexpr int kMaxDropLayers = 64;
+struct DropLayers { int n; int layer[kMaxDropLayers]; };
+hipError_t launch_seqused(const DropLayers& drops, const int32_t* retained, const int32_t* kv_len,
+                          const int32_t* orig_len, int R, int num_layers, int32_t* out, hipStream_t s);
+
 // physical KV-cache slots of the retained tokens (Eq. 16); the token count is new_cu[R] on the device
 hipError_t launch_slot_mapping(const int32_t* pos_kept, const int32_t* new_cu, int R,
                                const int32_t* block_table, long long table_stride, int kv_block,

@@ -800,3 +800,29 @@ def test_compact_column_of_position_ids(dtype):
     torch.cuda.synchronize()
     np.testing.assert_array_equal(out[:1000].cpu().numpy(), want[:1000])
     assert bool((out[1000:] == -77).all())
+
+
+def test_seqused_per_layer_matches_oracle():
+    """Eq. 17 from a drop history made by two real drops on the device: the retained lengths are the
+    differences of each drop's new_cu_seqlens."""
+    _say("seqused")
+    rng = np.random.default_rng(41)
+    R, num_layers, drop_layers = 700, 36, [0, 7, 20]
+    orig = rng.integers(1, 30000, size=R).astype(np.int32)
+    hist = np.zeros((3, R), np.int32)
+    cur = orig.astype(np.int64)
+    for k in range(3):
+        cur = np.maximum(1, cur * rng.integers(20, 100, size=R) // 100)
+        hist[k] = cur
+    kv = (orig + rng.integers(0, 2000, size=R)).astype(np.int32)
+    out = torch.full((num_layers * R + 64,), -77, dtype=torch.int32, device="cuda")
+    up.uniprefill_seqused(drop_layers, torch.from_numpy(hist).cuda(), torch.from_numpy(kv).cuda(),
+                          torch.from_numpy(orig).cuda(), R, num_layers, out)
+    torch.cuda.synchronize()
+    want = oracle.seqused_per_layer(drop_layers, hist, kv, orig, num_layers)
+    np.testing.assert_array_equal(out[:num_layers * R].cpu().numpy().reshape(num_layers, R), want)
+    assert bool((out[num_layers * R:] == -77).all())
+    # no drop events at all
+    up.uniprefill_seqused([], None, torch.from_numpy(kv).cuda(), torch.from_numpy(orig).cuda(), R, 2, out)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(out[:2 * R].cpu().numpy().reshape(2, R), np.stack([kv, kv]))

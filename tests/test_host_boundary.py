@@ -264,3 +264,21 @@ def test_compact_column_rejects_bad_arguments():
     assert call(fake, 8, fake, 10, None) == up.UP_ERR_NULL
     assert call(ctypes.c_void_p(0x1004), 8, fake, 10, fake) == up.UP_ERR_ALIGN
     assert call(fake, 4, fake, 10, ctypes.c_void_p(0x1002)) == up.UP_ERR_ALIGN
+
+
+def test_seqused_rejects_bad_arguments():
+    L = up.lib()
+    fake = ctypes.c_void_p(0x1000)
+    layers = lambda *v: up.ptr(np.array(v, np.int32))
+    call = lambda lay, nd, ret, kv, orig, R, nl, out: L.uniprefill_seqused(lay, nd, ret, kv, orig, R, nl, out, None)
+    assert call(layers(1, 3), 2, fake, fake, fake, 0, 6, fake) == up.UP_OK           # no request: nothing launched
+    assert call(layers(3, 1), 2, fake, fake, fake, 4, 6, fake) == up.UP_ERR_RANGE    # not ascending
+    assert call(layers(1, 1), 2, fake, fake, fake, 4, 6, fake) == up.UP_ERR_RANGE
+    assert call(layers(-1), 1, fake, fake, fake, 4, 6, fake) == up.UP_ERR_RANGE
+    assert call(None, 2, fake, fake, fake, 4, 6, fake) == up.UP_ERR_NULL
+    assert call(layers(1, 3), 2, None, fake, fake, 4, 6, fake) == up.UP_ERR_NULL
+    assert call(layers(1, 3), 2, fake, None, fake, 4, 6, fake) == up.UP_ERR_NULL
+    assert call(layers(1, 3), 2, fake, fake, fake, 4, 6, None) == up.UP_ERR_NULL
+    assert call(layers(1, 3), -1, fake, fake, fake, 4, 6, fake) == up.UP_ERR_RANGE
+    assert call(layers(*range(65)), 65, fake, fake, fake, 4, 6, fake) == up.UP_ERR_UNSUPPORTED
+    assert call(layers(1), 1, fake, fake, fake, 4, 70000, fake) == up.UP_ERR_RANGE
