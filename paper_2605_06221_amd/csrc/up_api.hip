@@ -362,12 +362,13 @@ int uniprefill_select_top_p(const up_params* p, const float* scores, const int32
   if (!scores || !cu_seqlens_dev || !top_p_dev || !kept_idx || !new_cu_seqlens_dev) return UP_ERR_NULL;
   if ((st = check_cu(p, cu_seqlens_host)) != UP_OK) return st;
   if ((st = check_ratio(p, top_p_host)) != UP_OK) return st;
+  int max_blocks = 0;
   for (int r = 0; r < p->num_seqs; ++r)
-    if ((cu_seqlens_host[r + 1] - cu_seqlens_host[r] + pb.G - 1) / pb.G > kMaxTopPBlocks)
-      return UP_ERR_UNSUPPORTED;
+    max_blocks = imax(max_blocks, (cu_seqlens_host[r + 1] - cu_seqlens_host[r] + pb.G - 1) / pb.G);
+  if (max_blocks > kMaxTopPBlocks) return UP_ERR_UNSUPPORTED;
   if (workspace == nullptr || workspace_bytes < workspace_layout(pb).tp_total) return UP_ERR_WORKSPACE;
   if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return UP_ERR_ALIGN;
-  if (launch_top_p(pb, scores, cu_seqlens_dev, top_p_dev, kept_idx, new_cu_seqlens_dev, workspace,
+  if (launch_top_p(pb, scores, cu_seqlens_dev, top_p_dev, kept_idx, new_cu_seqlens_dev, workspace, max_blocks,
                    (hipStream_t)stream) != hipSuccess)
     return UP_ERR_HIP;
   return UP_OK;

@@ -41,7 +41,7 @@ struct Problem {
 // Workspace carve-up (byte offsets, each 256-aligned).
 struct Workspace {
   size_t stat_part_off, stat_fin_off, o_part_off, total;
-  size_t tp_keep_off, tp_off_off, tp_seq_off, tp_mass_off, tp_total;   // top-p selection part (first tp_total bytes)
+  size_t tp_keep_off, tp_off_off, tp_seq_off, tp_mass_off, tp_rank_off, tp_total;   // top-p selection part (first tp_total bytes)
 };
 Workspace workspace_layout(const Problem& pb);
 
@@ -91,10 +91,12 @@ struct TopPArgs {
   int32_t* blk_off;      // [T/G + R] kept tokens of the sequence before this block
   int32_t* seq_kept;     // [R] kept tokens per sequence
   float* blk_mass;       // [T/G + R] block masses
+  int32_t* blk_rank;     // [T/G + R] place of the block in the descending order of its sequence
   int R, T, G, n_obs, n_sink;
 };
+// (max_blocks: selection blocks of the longest sequence, at most kMaxTopPBlocks)
 hipError_t launch_top_p(const Problem& pb, const float* scores, const int32_t* cu, const float* top_p,
-                        int32_t* kept_idx, int32_t* new_cu, void* workspace, hipStream_t s);
+                        int32_t* kept_idx, int32_t* new_cu, void* workspace, int max_blocks, hipStream_t s);
 // gather with the row count on the device (count_dev[0] rows, at most capacity)
 hipError_t launch_compact_counted(const Problem& pb, const void* hidden, const int32_t* pos,
                                   const int32_t* kept_idx, const int32_t* count_dev, long long capacity,

@@ -5,10 +5,12 @@
 // attention sinks and the query window always kept.
 //
 // Kept counts depend on the data, so the outputs are sized for the worst case
-// and the totals stay on the device (new_cu_seqlens).  Four launches:
+// and the totals stay on the device (new_cu_seqlens).  Five launches:
 //   k_block_mass     one wave per block: its mass
-//   k_top_p_blocks   one work-group per sequence: ranks, threshold, keep flags
-//                    and in-sequence output offsets of the blocks
+//   k_top_p_rank     place of every block in the descending order of the keys, by counting the
+//                    larger keys: 256 x 256 pairs per work-group, spread over the chip
+//   k_top_p_blocks   one work-group per sequence: running sum in that order, threshold, keep
+//                    flags and in-sequence output offsets of the blocks
 //   k_top_p_offsets  prefix sum of the per-sequence totals
 //   k_top_p_emit     one work-group per block: kept token ids, ascending
 //
@@ -16,6 +18,8 @@
 // bit: a block's mass is the double sum of its float scores in index order,
 // rounded to float; the running sum over the ordered blocks is a double sum in
 // that order; the threshold is (double)p times the total.
+#include <type_traits>
+
 #include "up_common.h"
 #include "up_kernels.h"
 #include "up_select.h"
@@ -25,7 +29,6 @@ namespace up {
 constexpr int kTopPThreads = 1024;
 
 struct TopPSmem {
-  unsigned long long key[kMaxTopPBlocks];
   float sorted_mass[kMaxTopPBlocks];
   int rank[kMaxTopPBlocks];
   double run[kMaxTopPBlocks];     // running sum over the ordered blocks
@@ -58,7 +61,45 @@ __global__ __launch_bounds__(256) void k_block_mass(TopPArgs a) {
 #pragma unroll
     for (int i = 0; i < 64; ++i) acc += (double)__shfl(v1, i);
   }
-  if (lane == 0) a.blk_mass[slot] = (float)acc;
+  if (lane == 0) {
+    a.blk_mass[slot] = (float)acc;
+    a.blk_rank[slot] = 0;      // k_top_p_rank adds to it
+  }
+}
+
+// Place of every block in the descending order of the packed keys of Eq. 14 (mass, then the
+// lower block index first) = the number of larger keys; the keys are distinct.  A sequence
+// of nb blocks is covered by ceil(nb/256)^2 work-groups: each counts, for 256 blocks, the larger
+// keys among 256 others (LDS broadcasts, eight reads in flight) and adds its count to the
+// block's total -- integer additions, so their order does not matter.  For the few thousand
+// blocks of a sequence this beats a sorting network, whose every stage ends in a barrier.
+__global__ __launch_bounds__(256) void k_top_p_rank(TopPArgs a, int chunks) {
+  __shared__ unsigned long long others[256];
+  const int r = blockIdx.x / (chunks * chunks);
+  const int pair = blockIdx.x % (chunks * chunks);
+  const int c0 = a.cu[r];
+  const int N = a.cu[r + 1] - c0;
+  const int nb = ceil_div(N, a.G);
+  const int ci = pair / chunks, cj = pair % chunks;
+  if (ci * 256 >= nb || cj * 256 >= nb) return;
+  const int slot0 = slot_base(c0, r, a.G);
+  const int tid = threadIdx.x;
+  auto key_of = [&](int g) {
+    return ((unsigned long long)phi(a.blk_mass[slot0 + g]) << 32) | (unsigned)(nb - 1 - g);
+  };
+  const int j = cj * 256 + tid, i = ci * 256 + tid;
+  others[tid] = j < nb ? key_of(j) : 0ull;                       // zero is larger than no key
+  const unsigned long long mine = i < nb ? key_of(i) : ~0ull;
+  __syncthreads();
+  int cnt = 0;
+  for (int j0 = 0; j0 < 256; j0 += 8) {
+    unsigned long long o[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) o[u] = others[j0 + u];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) cnt += o[u] > mine ? 1 : 0;
+  }
+  if (i < nb && cnt > 0) atomicAdd(&a.blk_rank[slot0 + i], cnt);
 }
 
 __global__ __launch_bounds__(kTopPThreads) void k_top_p_blocks(TopPArgs a) {
@@ -75,53 +116,29 @@ __global__ __launch_bounds__(kTopPThreads) void k_top_p_blocks(TopPArgs a) {
   const int nb = ceil_div(N, G);
   const int slot0 = slot_base(c0, r, G);
 
-  // 1. ordering keys from the block masses
+  // 1.-2. every block's place in the descending order of the keys (counted by k_top_p_rank) and
+  // the masses in that order
   for (int g = tid; g < nb; g += kTopPThreads) {
-    const float m = a.blk_mass[slot0 + g];
-    sm.key[g] = ((unsigned long long)phi(m) << 32) | (unsigned)(nb - 1 - g);
+    const int rk = a.blk_rank[slot0 + g];
+    sm.rank[g] = rk;
+    sm.sorted_mass[rk] = a.blk_mass[slot0 + g];
   }
+  // 3. running sum in that order, one addition after the other (sixteen reads in flight, then
+  // the sixteen additions; the list is padded with zeros to a multiple of sixteen so that the
+  // loop has no conditions in it)
+  const int nb16 = (nb + 15) & ~15;
+  if (tid < nb16 - nb) sm.sorted_mass[nb + tid] = 0.0f;
   __syncthreads();
-  // 2. keys into descending order (bitonic network over the next power of two, padded with
-  // zero keys, which sort behind every real key); a key names its block and carries its mass
-  int n2 = 64;
-  while (n2 < nb) n2 <<= 1;
-  for (int i = nb + tid; i < n2; i += kTopPThreads) sm.key[i] = 0ull;
-  __syncthreads();
-  for (int k = 2; k <= n2; k <<= 1) {
-    for (int j = k >> 1; j > 0; j >>= 1) {
-      for (int i = tid; i < n2; i += kTopPThreads) {
-        const int other = i ^ j;
-        if (other > i) {
-          const unsigned long long x = sm.key[i], y = sm.key[other];
-          const bool first_larger = (i & k) == 0;        // this stretch is being put in descending order
-          if (first_larger ? x < y : x > y) {
-            sm.key[i] = y;
-            sm.key[other] = x;
-          }
-        }
-      }
-      __syncthreads();
-    }
-  }
-  for (int k = tid; k < nb; k += kTopPThreads) {
-    const unsigned long long key = sm.key[k];
-    const int g = nb - 1 - (int)(unsigned)(key & 0xFFFFFFFFull);
-    const unsigned hi = (unsigned)(key >> 32);
-    sm.rank[g] = k;
-    sm.sorted_mass[k] = __uint_as_float((hi & 0x80000000u) ? (hi ^ 0x80000000u) : ~hi);   // inverse of phi
-  }
-  __syncthreads();
-  // 3. running sum in that order, one addition after the other
   if (tid == 0) {
     double acc = 0.0;
-    for (int k0 = 0; k0 < nb; k0 += 16) {
-      float v[16];     // sixteen reads in flight, then the additions in order
+    for (int k0 = 0; k0 < nb16; k0 += 16) {
+      float v[16];
 #pragma unroll
-      for (int j = 0; j < 16; ++j) v[j] = k0 + j < nb ? sm.sorted_mass[k0 + j] : 0.0f;
+      for (int j = 0; j < 16; ++j) v[j] = sm.sorted_mass[k0 + j];
 #pragma unroll
       for (int j = 0; j < 16; ++j) {
         acc += (double)v[j];
-        if (k0 + j < nb) sm.run[k0 + j] = acc;
+        sm.run[k0 + j] = acc;
       }
     }
     sm.thr = (double)a.top_p[r] * acc;
@@ -222,7 +239,7 @@ __global__ __launch_bounds__(128) void k_top_p_emit(TopPArgs a) {
 }
 
 hipError_t launch_top_p(const Problem& pb, const float* scores, const int32_t* cu, const float* top_p,
-                        int32_t* kept_idx, int32_t* new_cu, void* workspace, hipStream_t s) {
+                        int32_t* kept_idx, int32_t* new_cu, void* workspace, int max_blocks, hipStream_t s) {
   const Workspace w = workspace_layout(pb);
   char* ws = (char*)workspace;
   TopPArgs a;
@@ -231,9 +248,14 @@ hipError_t launch_top_p(const Problem& pb, const float* scores, const int32_t* c
   a.blk_off = (int32_t*)(ws + w.tp_off_off);
   a.seq_kept = (int32_t*)(ws + w.tp_seq_off);
   a.blk_mass = (float*)(ws + w.tp_mass_off);
+  a.blk_rank = (int32_t*)(ws + w.tp_rank_off);
   a.R = pb.R; a.T = pb.T; a.G = pb.G; a.n_obs = pb.n_obs; a.n_sink = pb.n_sink;
   if (pb.T > 0)
     hipLaunchKernelGGL(k_block_mass, dim3((unsigned)((pb.T / pb.G + pb.R + 3) / 4)), dim3(256), 0, s, a);
+  if (pb.T > 0 && max_blocks > 0) {
+    const int chunks = (max_blocks + 255) / 256;
+    hipLaunchKernelGGL(k_top_p_rank, dim3((unsigned)(chunks * chunks * pb.R)), dim3(256), 0, s, a, chunks);
+  }
   if (pb.R > 0)
     hipLaunchKernelGGL(k_top_p_blocks, dim3((unsigned)pb.R), dim3(kTopPThreads), 0, s, a);
   hipLaunchKernelGGL(k_top_p_offsets, dim3(1), dim3(1024), 0, s, a.seq_kept, pb.R, new_cu);
