@@ -826,3 +826,38 @@ def test_seqused_per_layer_matches_oracle():
     up.uniprefill_seqused([], None, torch.from_numpy(kv).cuda(), torch.from_numpy(orig).cuda(), R, 2, out)
     torch.cuda.synchronize()
     np.testing.assert_array_equal(out[:2 * R].cpu().numpy().reshape(2, R), np.stack([kv, kv]))
+
+
+def test_fused_call_replayed_from_a_hip_graph():
+    """The fused call allocates nothing, never synchronises and records no memset, so a caller can
+    capture it in a HIP graph.  Replays with new inputs written into the captured buffers between
+    them (and eager work and synchronisations in between) must each equal the eager result."""
+    _say("fused under graph capture")
+    ws = [workloads.make_custom(name=f"g{i}", seed=50 + i, lengths=[3000, 40, 777], keep_ratio=[0.3, 0.5, 0.7],
+                                hidden_dim=64, num_q_heads=8, num_kv_heads=2, block_size=64, n_obs=128)
+          for i in range(3)]
+    b = DeviceBatch(ws[0])
+    b.fused()                                     # warm-up outside the capture (module load)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            b.fused()
+    torch.cuda.synchronize()
+    for rep, w in enumerate(ws + ws[:1]):
+        # new inputs into the captured buffers; outputs poisoned
+        b.q.copy_(dev_bf16(w.q)); b.k.copy_(dev_bf16(w.k)); b.hidden.copy_(dev_bf16(w.hidden))
+        b.pos.copy_(torch.from_numpy(w.pos).cuda())
+        b.hidden_out.fill_(-7.0); b.kept_idx.fill_(-77); b.pos_out.fill_(-77); b.scores.fill_(-7.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = b.results()
+        eager = DeviceBatch(w)
+        eager.fused()
+        want = eager.results()
+        for key in want:
+            np.testing.assert_array_equal(got[key], want[key], err_msg=f"replay {rep}: {key}")
+        assert b.canaries_intact()
