@@ -861,3 +861,30 @@ def test_fused_call_replayed_from_a_hip_graph():
         for key in want:
             np.testing.assert_array_equal(got[key], want[key], err_msg=f"replay {rep}: {key}")
         assert b.canaries_intact()
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_fused_random_geometries_with_context_and_head_dims_bit_exact(seed):
+    """Like the random geometries above, with a random amount of earlier context per request
+    (none for some) and head dimensions 64 / 128 / 256."""
+    rng = np.random.default_rng(3000 + seed)
+    R = int(rng.integers(1, 7))
+    lengths = [int(x) for x in rng.choice([0, 1, 17, 64, 129, 300, 512, 777, 1500, 2600], size=R)]
+    if sum(lengths) == 0:
+        lengths[0] = 333
+    earlier = [int(x) for x in rng.choice([0, 0, 1, 63, 128, 511, 512, 513, 1000, 3000, 7000], size=R)]
+    Hkv = int(rng.choice([1, 2, 4, 8]))
+    Hq = Hkv * int(rng.choice([1, 2, 4]))
+    G = int(rng.choice([32, 64, 128]))
+    n_obs = int(rng.choice([16, 100, 128, 256]))
+    n_sink = int(rng.choice([0, 4, 128, 200]))
+    head_dim = int(rng.choice([64, 128, 256]))
+    ratios = [float(x) for x in rng.uniform(0.05, 1.0, size=R)]
+    _say("random geometry with context", seed, dict(lengths=lengths, earlier=earlier, Hq=Hq, Hkv=Hkv, G=G, n_obs=n_obs,
+                                                    n_sink=n_sink, head_dim=head_dim))
+    w = workloads.make_custom(name=f"rndc{seed}", seed=4000 + seed, lengths=lengths, keep_ratio=ratios, hidden_dim=32,
+                              num_q_heads=Hq, num_kv_heads=Hkv, block_size=G, n_obs=n_obs, n_sink=n_sink,
+                              head_dim=head_dim, earlier=earlier)
+    b = DeviceBatch(w)
+    b.fused()
+    _assert_fused_exact(w, b, oracle_run(w))
