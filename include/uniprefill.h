@@ -225,7 +225,8 @@ int uniprefill_slot_mapping(const int32_t* pos_kept, const int32_t* new_cu_seqle
 /* The kernels behind uniprefill_fused, in stream order.  Measurement aid: a
  * caller that wants to time one kernel enqueues the phases one by one. */
 enum {
-  UP_PHASE_PLAN = 1,                 /* new_cu_seqlens_dev */
+  UP_PHASE_PLAN = 1,                 /* new_cu_seqlens_dev (a kernel of its own when asked for alone;
+                                        together with UP_PHASE_MERGE_STATS it rides in that kernel) */
   UP_PHASE_ROW_STATS = 2,            /* pass 1 of the two-pass softmax: row statistics per key block */
   UP_PHASE_MERGE_STATS = 4,          /* merge of the per-block statistics */
   UP_PHASE_SWEEP_SELECT = 8,         /* pass 2 (normalised weights summed per token) with the

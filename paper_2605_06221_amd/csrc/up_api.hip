@@ -233,7 +233,7 @@ int score_impl(const up_params* p, const void* q, const void* k, const int32_t* 
   if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return UP_ERR_ALIGN;
   hipStream_t s = (hipStream_t)stream;
   if (launch_row_stats(pb, q, k, cu_dev, cu_k_dev, workspace, s) != hipSuccess) return UP_ERR_HIP;
-  if (launch_merge_stats(pb, cu_dev, cu_k_dev, workspace, s) != hipSuccess) return UP_ERR_HIP;
+  if (launch_merge_stats(pb, cu_dev, cu_k_dev, workspace, nullptr, nullptr, s) != hipSuccess) return UP_ERR_HIP;
   if (launch_column_sums(pb, q, k, cu_dev, cu_k_dev, workspace, scores_out, nullptr, s) != hipSuccess)
     return UP_ERR_HIP;
   return UP_OK;
@@ -279,14 +279,17 @@ int fused_impl(const up_params* p, const void* q, const void* k, const void* hid
   if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return UP_ERR_ALIGN;
   if (phase_mask & ~UP_PHASE_ALL) return UP_ERR_RANGE;
   hipStream_t s = (hipStream_t)stream;
-  if ((phase_mask & UP_PHASE_PLAN) &&
+  // the plan rides in the merge kernel when both are asked for (one launch less)
+  const bool plan_in_merge = (phase_mask & UP_PHASE_PLAN) && (phase_mask & UP_PHASE_MERGE_STATS);
+  if ((phase_mask & UP_PHASE_PLAN) && !plan_in_merge &&
       launch_plan(pb, cu_dev, cu_k_dev, ratio_dev, new_cu_dev, s) != hipSuccess)
     return UP_ERR_HIP;
   if ((phase_mask & UP_PHASE_ROW_STATS) &&
       launch_row_stats(pb, q, k, cu_dev, cu_k_dev, workspace, s) != hipSuccess)
     return UP_ERR_HIP;
   if ((phase_mask & UP_PHASE_MERGE_STATS) &&
-      launch_merge_stats(pb, cu_dev, cu_k_dev, workspace, s) != hipSuccess)
+      launch_merge_stats(pb, cu_dev, cu_k_dev, workspace, plan_in_merge ? ratio_dev : nullptr,
+                         plan_in_merge ? new_cu_dev : nullptr, s) != hipSuccess)
     return UP_ERR_HIP;
   if (phase_mask & UP_PHASE_SWEEP_SELECT) {
     const SelectArgs sa = make_select_args(pb, nullptr, cu_dev, cu_k_dev, ratio_dev, new_cu_dev, kept_idx);

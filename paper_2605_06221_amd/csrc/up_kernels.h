@@ -107,9 +107,10 @@ hipError_t launch_compact_counted(const Problem& pb, const void* hidden, const i
 // (cu_k as above; the kernels take cu itself where it is nullptr)
 hipError_t launch_row_stats(const Problem& pb, const void* q, const void* k, const int32_t* cu,
                             const int32_t* cu_k, void* workspace, hipStream_t s);
-// merge of the per-block statistics into one (reference, 1/sum) per row
+// merge of the per-block statistics into one (reference, 1/sum) per row; with plan_ratio given
+// the same launch also does what launch_plan does (into plan_new_cu)
 hipError_t launch_merge_stats(const Problem& pb, const int32_t* cu, const int32_t* cu_k, void* workspace,
-                              hipStream_t s);
+                              const float* plan_ratio, int32_t* plan_new_cu, hipStream_t s);
 // pass 2: normalised weights summed per token; optional scores_out; sel != nullptr runs the
 // block-local top-k (in the same kernel when every key block has one work-group, otherwise in
 // k_finish)

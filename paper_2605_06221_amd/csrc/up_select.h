@@ -41,6 +41,42 @@ __device__ __forceinline__ int sinks_of(const int32_t* cu_k, int n_sink, int r, 
   return imax(0, n_sink - ((cu_k[r + 1] - cu_k[r]) - N));
 }
 
+// Per-sequence kept totals and their exclusive prefix (the compacted stream's sequence
+// offsets), by one work-group of NT threads (whole waves, at most 1024); sequences are scanned
+// NT at a time.  wave_tot (16 ints) and carry are LDS of the caller.
+template <int NT>
+__device__ __forceinline__ void plan_scan(const int32_t* __restrict__ cu, const int32_t* __restrict__ cu_k,
+                                          const float* __restrict__ ratio, int R, int G, int n_obs, int n_sink,
+                                          int32_t* __restrict__ new_cu, int* wave_tot, int* carry) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (tid == 0) { *carry = 0; new_cu[0] = 0; }
+  __syncthreads();
+  for (int base = 0; base < R; base += NT) {
+    const int r = base + tid;
+    int v = 0;
+    if (r < R) {
+      const int N = cu[r + 1] - cu[r];
+      SeqGeom sg{N, G, n_obs, sinks_of(cu_k, n_sink, r, N), (double)ratio[r]};
+      v = seq_kept(sg);
+    }
+    // inclusive scan inside the wave, then over the wave totals
+    int incl = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int up_v = __shfl_up(incl, o);
+      if (lane >= o) incl += up_v;
+    }
+    if (lane == 63) wave_tot[wave] = incl;
+    __syncthreads();
+    int before = *carry;
+    for (int w2 = 0; w2 < wave; ++w2) before += wave_tot[w2];
+    if (r < R) new_cu[r + 1] = before + incl;
+    __syncthreads();
+    if (tid == NT - 1) *carry = before + incl;
+    __syncthreads();
+  }
+}
+
 // Monotone IEEE-754 -> unsigned map of Eq. 14 (sign read from the sign bit).
 __device__ __forceinline__ unsigned phi(float x) {
   const unsigned b = __float_as_uint(x);

@@ -6,40 +6,13 @@
 
 namespace up {
 
-// Per-sequence kept totals and their exclusive prefix (the compacted stream's
-// sequence offsets).  One work-group; sequences are scanned 1024 at a time.
+// The plan as a kernel of its own (one work-group).
 __global__ __launch_bounds__(1024) void k_plan(const int32_t* __restrict__ cu, const int32_t* __restrict__ cu_k,
                                                const float* __restrict__ ratio, int R, int G,
                                                int n_obs, int n_sink, int32_t* __restrict__ new_cu) {
   __shared__ int wave_tot[16];
   __shared__ int carry;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  if (tid == 0) { carry = 0; new_cu[0] = 0; }
-  __syncthreads();
-  for (int base = 0; base < R; base += 1024) {
-    const int r = base + tid;
-    int v = 0;
-    if (r < R) {
-      const int N = cu[r + 1] - cu[r];
-      SeqGeom sg{N, G, n_obs, sinks_of(cu_k, n_sink, r, N), (double)ratio[r]};
-      v = seq_kept(sg);
-    }
-    // inclusive scan inside the wave, then over the 16 wave totals
-    int incl = v;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-      const int up_v = __shfl_up(incl, o);
-      if (lane >= o) incl += up_v;
-    }
-    if (lane == 63) wave_tot[wave] = incl;
-    __syncthreads();
-    int before = carry;
-    for (int w2 = 0; w2 < wave; ++w2) before += wave_tot[w2];
-    if (r < R) new_cu[r + 1] = before + incl;
-    __syncthreads();
-    if (tid == 1023) carry = before + incl;
-    __syncthreads();
-  }
+  plan_scan<1024>(cu, cu_k, ratio, R, G, n_obs, n_sink, new_cu, wave_tot, &carry);
 }
 
 // One work-group per selection block.

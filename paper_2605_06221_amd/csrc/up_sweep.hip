@@ -540,15 +540,29 @@ __global__ __launch_bounds__(256) void k_finish(SweepArgs a, int key_block) {   
 // threads that share a row each take 16 key blocks per round, all loads in flight
 // (LPR = 32 for long sequences, 8 when no sequence has more than 128 key blocks).
 // Row slots are laid out with slack between sequences; a work-group without a live row
-// ends at once.
+// ends at once.  In the fused call the first work-group also does the plan (kept totals per
+// sequence and their prefix), which nothing needs before the kernel after this one: one launch
+// and its gap less than with k_plan.
+struct PlanInCombine {
+  const float* ratio;      // nullptr: no plan here
+  int32_t* new_cu;
+  const int32_t* cu_k_sel; // key-side offsets for the sinks (nullptr without earlier context)
+  int G, n_sink;
+};
 template <int LPR>
 __global__ __launch_bounds__(32 * LPR) void k_combine(const int32_t* __restrict__ cu,
                                                       const int32_t* __restrict__ cu_k,
                                                       const float2* __restrict__ stat_part,
                                                       float2* __restrict__ stat_fin, int R, int Hq,
-                                                      int n_obs, int row_slots, int key_block) {
+                                                      int n_obs, int row_slots, int key_block,
+                                                      PlanInCombine plan) {
   __shared__ float sh_m[LPR][33];
   __shared__ double sh_l[LPR][33];
+  if (plan.ratio != nullptr && blockIdx.x == 0 && blockIdx.y == 0) {
+    __shared__ int wave_tot[16];
+    __shared__ int carry;
+    plan_scan<32 * LPR>(cu, plan.cu_k_sel, plan.ratio, R, plan.G, n_obs, plan.n_sink, plan.new_cu, wave_tot, &carry);
+  }
   const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
   const int u = blockIdx.x * 32 + tx;
   const int h = blockIdx.y;
@@ -687,16 +701,20 @@ hipError_t launch_row_stats(const Problem& pb, const void* q, const void* k, con
 }
 
 hipError_t launch_merge_stats(const Problem& pb, const int32_t* cu, const int32_t* cu_k, void* workspace,
-                              hipStream_t s) {
-  if (pb.T == 0) return hipSuccess;
+                              const float* plan_ratio, int32_t* plan_new_cu, hipStream_t s) {
+  if (pb.T == 0) {
+    // nothing to merge; the plan still has to say so (new_cu = 0 everywhere)
+    return plan_ratio != nullptr ? launch_plan(pb, cu, cu_k, plan_ratio, plan_new_cu, s) : hipSuccess;
+  }
+  const PlanInCombine plan{plan_ratio, plan_new_cu, cu_k, pb.G, pb.n_sink};
   const SweepArgs a = make_sweep_args(pb, nullptr, nullptr, cu, cu_k, workspace);
   const dim3 grid((unsigned)((pb.row_slots + 31) / 32), (unsigned)pb.Hq);
   if (pb.max_key_blocks > 128)
     hipLaunchKernelGGL(k_combine<32>, grid, dim3(1024), 0, s, cu, a.cu_k, a.stat_part, a.stat_fin, pb.R, pb.Hq,
-                       pb.n_obs, pb.row_slots, pb.key_block);
+                       pb.n_obs, pb.row_slots, pb.key_block, plan);
   else
     hipLaunchKernelGGL(k_combine<8>, grid, dim3(256), 0, s, cu, a.cu_k, a.stat_part, a.stat_fin, pb.R, pb.Hq,
-                       pb.n_obs, pb.row_slots, pb.key_block);
+                       pb.n_obs, pb.row_slots, pb.key_block, plan);
   return hipGetLastError();
 }
 
