@@ -282,3 +282,12 @@ def test_seqused_rejects_bad_arguments():
     assert call(layers(1, 3), -1, fake, fake, fake, 4, 6, fake) == up.UP_ERR_RANGE
     assert call(layers(*range(65)), 65, fake, fake, fake, 4, 6, fake) == up.UP_ERR_UNSUPPORTED
     assert call(layers(1), 1, fake, fake, fake, 4, 70000, fake) == up.UP_ERR_RANGE
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True,
+                         text=True, timeout=120)
+    assert res.returncode != 0
+    assert "ONE GPU" in res.stderr and res.stdout.strip() == ""
