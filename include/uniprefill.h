@@ -314,6 +314,31 @@ int uniprefill_fused_chunked(const up_params* p, const void* q, const void* k, c
                              int32_t* kept_idx, int32_t* new_cu_seqlens_dev, float* scores_out,
                              void* workspace, size_t workspace_bytes, void* stream);
 
+/* The same with the keys in a paged KV cache (vLLM scheduler integration; the
+ * indexing of Eq. 16): key i of sequence r is row
+ *     block_table[r * block_table_stride + i / kv_block_size] * kv_block_size + i % kv_block_size
+ * of k_cache, a device array of rows [num_kv_heads, head_dim] with k_row_stride
+ * elements between rows.  cu_seqlens_k still gives the number of keys per
+ * sequence (earlier tokens + own tokens) and sizes the workspace through
+ * uniprefill_plan_chunked; block_table is int32 on the device, one row of
+ * block_table_stride entries per sequence, which must hold at least
+ * ceil(keys / kv_block_size) entries (UP_ERR_SHAPE otherwise; kv_block_size < 1:
+ * UP_ERR_RANGE).  Its entries must name existing blocks of the cache: they are
+ * read on the device and cannot be checked. */
+int uniprefill_score_paged(const up_params* p, const void* q, const void* k_cache,
+                           const int32_t* cu_seqlens_dev, const int32_t* cu_seqlens_host,
+                           const int32_t* cu_seqlens_k_dev, const int32_t* cu_seqlens_k_host,
+                           const int32_t* block_table, int64_t block_table_stride, int32_t kv_block_size,
+                           float* scores_out, void* workspace, size_t workspace_bytes, void* stream);
+int uniprefill_fused_paged(const up_params* p, const void* q, const void* k_cache, const void* hidden,
+                           const int32_t* pos, const int32_t* cu_seqlens_dev,
+                           const int32_t* cu_seqlens_host, const int32_t* cu_seqlens_k_dev,
+                           const int32_t* cu_seqlens_k_host, const int32_t* block_table,
+                           int64_t block_table_stride, int32_t kv_block_size, const float* keep_ratio_dev,
+                           const float* keep_ratio_host, void* hidden_out, int32_t* pos_out,
+                           int32_t* kept_idx, int32_t* new_cu_seqlens_dev, float* scores_out,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
 /* Static, never NULL. */
 const char* uniprefill_status_string(int status);
 

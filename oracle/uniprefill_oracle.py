@@ -426,6 +426,21 @@ def importance_scores_with_context(q, k, cu_seqlens_q, cu_seqlens_k, *, n_obs, s
     return o
 
 
+def gather_paged_keys(k_cache, cu_seqlens_k, block_table, kv_block_size):
+    """Keys of every request read out of a paged KV cache into the packed layout that
+    ``importance_scores_with_context`` takes: key i of request r is row
+    block_table[r, i // B] * B + i % B of the cache (the indexing of Eq. 16)."""
+    cache = np.asarray(k_cache)
+    ck = np.asarray(cu_seqlens_k, dtype=np.int64)
+    bt = np.asarray(block_table, dtype=np.int64)
+    B = int(kv_block_size)
+    out = np.empty((int(ck[-1]),) + cache.shape[1:], dtype=cache.dtype)
+    for r in range(len(ck) - 1):
+        for i in range(int(ck[r + 1] - ck[r])):
+            out[ck[r] + i] = cache[bt[r, i // B] * B + i % B]
+    return out
+
+
 def sinks_in_chunk(cu_seqlens_q, cu_seqlens_k, n_sink):
     """Number of sink tokens inside each request's chunk: max(0, A - P_r)."""
     cq = np.asarray(cu_seqlens_q, dtype=np.int64)

@@ -218,23 +218,52 @@ int plan_impl(const up_params* p, const int32_t* cu_host, const int32_t* cu_k_ho
   return UP_OK;
 }
 
+// Where the keys of the tokens' sequences are: packed with the tokens (ctx false), packed by
+// their own offsets after earlier context (ctx), or in a paged cache addressed through a block
+// table (ctx with paged).
+struct KeySide {
+  const int32_t* cu_k_dev;
+  const int32_t* cu_k_host;
+  bool ctx;
+  const PagedKeys* paged;
+};
+const KeySide kOwnKeys{nullptr, nullptr, false, nullptr};
+
+int check_key_side(const up_params* p, const int32_t* cu_host, const KeySide& ks) {
+  if (!ks.ctx) return UP_OK;
+  if (!ks.cu_k_dev) return UP_ERR_NULL;
+  int st = check_cu_k(p, cu_host, ks.cu_k_host);
+  if (st != UP_OK) return st;
+  if (ks.paged != nullptr) {
+    if (ks.paged->block_table == nullptr) return UP_ERR_NULL;
+    if (ks.paged->kv_block < 1 || ks.paged->table_stride < 0) return UP_ERR_RANGE;
+    for (int r = 0; r < p->num_seqs; ++r) {
+      const long long blocks = ((long long)(ks.cu_k_host[r + 1] - ks.cu_k_host[r]) + ks.paged->kv_block - 1) / ks.paged->kv_block;
+      if (blocks > ks.paged->table_stride) return UP_ERR_SHAPE;     // a row of the table is too short
+    }
+  }
+  return UP_OK;
+}
+
 int score_impl(const up_params* p, const void* q, const void* k, const int32_t* cu_dev,
-               const int32_t* cu_host, const int32_t* cu_k_dev, const int32_t* cu_k_host, bool ctx,
-               float* scores_out, void* workspace, size_t workspace_bytes, void* stream) {
+               const int32_t* cu_host, const KeySide& ks, float* scores_out, void* workspace,
+               size_t workspace_bytes, void* stream) {
+  const int32_t* cu_k_dev = ks.cu_k_dev;
+  const int32_t* cu_k_host = ks.cu_k_host;
   Problem pb;
   int st = check_params(p, true, false, &pb);
   if (st != UP_OK) return st;
-  if (!q || !k || !cu_dev || !scores_out || (ctx && !cu_k_dev)) return UP_ERR_NULL;
+  if (!q || !k || !cu_dev || !scores_out) return UP_ERR_NULL;
   if ((st = check_cu(p, cu_host)) != UP_OK) return st;
-  if (ctx && (st = check_cu_k(p, cu_host, cu_k_host)) != UP_OK) return st;
+  if ((st = check_key_side(p, cu_host, ks)) != UP_OK) return st;
   if (!aligned16(q) || !aligned16(k)) return UP_ERR_ALIGN;
   choose_geometry(&pb, cu_host, cu_k_host);
   if (workspace == nullptr || workspace_bytes < workspace_layout(pb).total) return UP_ERR_WORKSPACE;
   if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return UP_ERR_ALIGN;
   hipStream_t s = (hipStream_t)stream;
-  if (launch_row_stats(pb, q, k, cu_dev, cu_k_dev, workspace, s) != hipSuccess) return UP_ERR_HIP;
+  if (launch_row_stats(pb, q, k, cu_dev, cu_k_dev, ks.paged, workspace, s) != hipSuccess) return UP_ERR_HIP;
   if (launch_merge_stats(pb, cu_dev, cu_k_dev, workspace, nullptr, nullptr, s) != hipSuccess) return UP_ERR_HIP;
-  if (launch_column_sums(pb, q, k, cu_dev, cu_k_dev, workspace, scores_out, nullptr, s) != hipSuccess)
+  if (launch_column_sums(pb, q, k, cu_dev, cu_k_dev, ks.paged, workspace, scores_out, nullptr, s) != hipSuccess)
     return UP_ERR_HIP;
   return UP_OK;
 }
@@ -257,19 +286,20 @@ int select_impl(const up_params* p, const float* scores, const int32_t* cu_dev, 
 }
 
 int fused_impl(const up_params* p, const void* q, const void* k, const void* hidden, const int32_t* pos,
-               const int32_t* cu_dev, const int32_t* cu_host, const int32_t* cu_k_dev,
-               const int32_t* cu_k_host, bool ctx, const float* ratio_dev, const float* ratio_host,
-               void* hidden_out, int32_t* pos_out, int32_t* kept_idx, int32_t* new_cu_dev,
-               float* scores_out, void* workspace, size_t workspace_bytes, int phase_mask, void* stream) {
+               const int32_t* cu_dev, const int32_t* cu_host, const KeySide& ks, const float* ratio_dev,
+               const float* ratio_host, void* hidden_out, int32_t* pos_out, int32_t* kept_idx,
+               int32_t* new_cu_dev, float* scores_out, void* workspace, size_t workspace_bytes,
+               int phase_mask, void* stream) {
+  const int32_t* cu_k_dev = ks.cu_k_dev;
+  const int32_t* cu_k_host = ks.cu_k_host;
   Problem pb;
   int st = check_params(p, true, true, &pb);
   if (st != UP_OK) return st;
-  if (!q || !k || !hidden || !cu_dev || !ratio_dev || !hidden_out || !kept_idx || !new_cu_dev ||
-      (ctx && !cu_k_dev))
+  if (!q || !k || !hidden || !cu_dev || !ratio_dev || !hidden_out || !kept_idx || !new_cu_dev)
     return UP_ERR_NULL;
   if ((pos == nullptr) != (pos_out == nullptr)) return UP_ERR_NULL;
   if ((st = check_cu(p, cu_host)) != UP_OK) return st;
-  if (ctx && (st = check_cu_k(p, cu_host, cu_k_host)) != UP_OK) return st;
+  if ((st = check_key_side(p, cu_host, ks)) != UP_OK) return st;
   if ((st = check_ratio(p, ratio_host)) != UP_OK) return st;
   if (!aligned16(q) || !aligned16(k) || !aligned16(hidden) || !aligned16(hidden_out))
     return UP_ERR_ALIGN;
@@ -285,7 +315,7 @@ int fused_impl(const up_params* p, const void* q, const void* k, const void* hid
       launch_plan(pb, cu_dev, cu_k_dev, ratio_dev, new_cu_dev, s) != hipSuccess)
     return UP_ERR_HIP;
   if ((phase_mask & UP_PHASE_ROW_STATS) &&
-      launch_row_stats(pb, q, k, cu_dev, cu_k_dev, workspace, s) != hipSuccess)
+      launch_row_stats(pb, q, k, cu_dev, cu_k_dev, ks.paged, workspace, s) != hipSuccess)
     return UP_ERR_HIP;
   if ((phase_mask & UP_PHASE_MERGE_STATS) &&
       launch_merge_stats(pb, cu_dev, cu_k_dev, workspace, plan_in_merge ? ratio_dev : nullptr,
@@ -293,7 +323,7 @@ int fused_impl(const up_params* p, const void* q, const void* k, const void* hid
     return UP_ERR_HIP;
   if (phase_mask & UP_PHASE_SWEEP_SELECT) {
     const SelectArgs sa = make_select_args(pb, nullptr, cu_dev, cu_k_dev, ratio_dev, new_cu_dev, kept_idx);
-    if (launch_column_sums(pb, q, k, cu_dev, cu_k_dev, workspace, scores_out, &sa, s) != hipSuccess)
+    if (launch_column_sums(pb, q, k, cu_dev, cu_k_dev, ks.paged, workspace, scores_out, &sa, s) != hipSuccess)
       return UP_ERR_HIP;
   }
   if (phase_mask & UP_PHASE_GATHER) {
@@ -326,16 +356,27 @@ int uniprefill_plan_chunked(const up_params* p, const int32_t* cu_seqlens_host,
 int uniprefill_score(const up_params* p, const void* q, const void* k, const int32_t* cu_seqlens_dev,
                      const int32_t* cu_seqlens_host, float* scores_out, void* workspace,
                      size_t workspace_bytes, void* stream) {
-  return score_impl(p, q, k, cu_seqlens_dev, cu_seqlens_host, nullptr, nullptr, false, scores_out,
-                    workspace, workspace_bytes, stream);
+  return score_impl(p, q, k, cu_seqlens_dev, cu_seqlens_host, kOwnKeys, scores_out, workspace,
+                    workspace_bytes, stream);
 }
 
 int uniprefill_score_chunked(const up_params* p, const void* q, const void* k,
                              const int32_t* cu_seqlens_dev, const int32_t* cu_seqlens_host,
                              const int32_t* cu_seqlens_k_dev, const int32_t* cu_seqlens_k_host,
                              float* scores_out, void* workspace, size_t workspace_bytes, void* stream) {
-  return score_impl(p, q, k, cu_seqlens_dev, cu_seqlens_host, cu_seqlens_k_dev, cu_seqlens_k_host, true,
-                    scores_out, workspace, workspace_bytes, stream);
+  const KeySide ks{cu_seqlens_k_dev, cu_seqlens_k_host, true, nullptr};
+  return score_impl(p, q, k, cu_seqlens_dev, cu_seqlens_host, ks, scores_out, workspace, workspace_bytes, stream);
+}
+
+int uniprefill_score_paged(const up_params* p, const void* q, const void* k_cache,
+                           const int32_t* cu_seqlens_dev, const int32_t* cu_seqlens_host,
+                           const int32_t* cu_seqlens_k_dev, const int32_t* cu_seqlens_k_host,
+                           const int32_t* block_table, int64_t block_table_stride, int32_t kv_block_size,
+                           float* scores_out, void* workspace, size_t workspace_bytes, void* stream) {
+  const PagedKeys paged{block_table, block_table_stride, kv_block_size};
+  const KeySide ks{cu_seqlens_k_dev, cu_seqlens_k_host, true, &paged};
+  return score_impl(p, q, k_cache, cu_seqlens_dev, cu_seqlens_host, ks, scores_out, workspace, workspace_bytes,
+                    stream);
 }
 
 int uniprefill_select(const up_params* p, const float* scores, const int32_t* cu_seqlens_dev,
@@ -524,7 +565,7 @@ int uniprefill_fused_phases(const up_params* p, const void* q, const void* k, co
                             const float* keep_ratio_host, void* hidden_out, int32_t* pos_out,
                             int32_t* kept_idx, int32_t* new_cu_seqlens_dev, float* scores_out,
                             void* workspace, size_t workspace_bytes, int phase_mask, void* stream) {
-  return fused_impl(p, q, k, hidden, pos, cu_seqlens_dev, cu_seqlens_host, nullptr, nullptr, false,
+  return fused_impl(p, q, k, hidden, pos, cu_seqlens_dev, cu_seqlens_host, kOwnKeys,
                     keep_ratio_dev, keep_ratio_host, hidden_out, pos_out, kept_idx, new_cu_seqlens_dev,
                     scores_out, workspace, workspace_bytes, phase_mask, stream);
 }
@@ -536,9 +577,25 @@ int uniprefill_fused_chunked(const up_params* p, const void* q, const void* k, c
                              const float* keep_ratio_host, void* hidden_out, int32_t* pos_out,
                              int32_t* kept_idx, int32_t* new_cu_seqlens_dev, float* scores_out,
                              void* workspace, size_t workspace_bytes, void* stream) {
-  return fused_impl(p, q, k, hidden, pos, cu_seqlens_dev, cu_seqlens_host, cu_seqlens_k_dev,
-                    cu_seqlens_k_host, true, keep_ratio_dev, keep_ratio_host, hidden_out, pos_out, kept_idx,
-                    new_cu_seqlens_dev, scores_out, workspace, workspace_bytes, UP_PHASE_ALL, stream);
+  const KeySide ks{cu_seqlens_k_dev, cu_seqlens_k_host, true, nullptr};
+  return fused_impl(p, q, k, hidden, pos, cu_seqlens_dev, cu_seqlens_host, ks, keep_ratio_dev, keep_ratio_host,
+                    hidden_out, pos_out, kept_idx, new_cu_seqlens_dev, scores_out, workspace, workspace_bytes,
+                    UP_PHASE_ALL, stream);
+}
+
+int uniprefill_fused_paged(const up_params* p, const void* q, const void* k_cache, const void* hidden,
+                           const int32_t* pos, const int32_t* cu_seqlens_dev,
+                           const int32_t* cu_seqlens_host, const int32_t* cu_seqlens_k_dev,
+                           const int32_t* cu_seqlens_k_host, const int32_t* block_table,
+                           int64_t block_table_stride, int32_t kv_block_size, const float* keep_ratio_dev,
+                           const float* keep_ratio_host, void* hidden_out, int32_t* pos_out,
+                           int32_t* kept_idx, int32_t* new_cu_seqlens_dev, float* scores_out,
+                           void* workspace, size_t workspace_bytes, void* stream) {
+  const PagedKeys paged{block_table, block_table_stride, kv_block_size};
+  const KeySide ks{cu_seqlens_k_dev, cu_seqlens_k_host, true, &paged};
+  return fused_impl(p, q, k_cache, hidden, pos, cu_seqlens_dev, cu_seqlens_host, ks, keep_ratio_dev,
+                    keep_ratio_host, hidden_out, pos_out, kept_idx, new_cu_seqlens_dev, scores_out, workspace,
+                    workspace_bytes, UP_PHASE_ALL, stream);
 }
 
 int uniprefill_fused(const up_params* p, const void* q, const void* k, const void* hidden,

@@ -102,11 +102,20 @@ hipError_t launch_compact_counted(const Problem& pb, const void* hidden, const i
                                   const int32_t* kept_idx, const int32_t* count_dev, long long capacity,
                                   void* hidden_out, int32_t* pos_out, hipStream_t s);
 
+// Keys in a paged KV cache: key i of sequence r is row
+// block_table[r * table_stride + i / kv_block] * kv_block + i % kv_block of k (the indexing of Eq. 16).
+struct PagedKeys {
+  const int32_t* block_table;
+  long long table_stride;
+  int kv_block;
+};
+
 // --- scoring (Eq. 2-3)
 // pass 1: softmax statistics of every window row per key block (into the workspace)
 // (cu_k as above; the kernels take cu itself where it is nullptr)
+// (paged: nullptr when the keys are packed by cu / cu_k)
 hipError_t launch_row_stats(const Problem& pb, const void* q, const void* k, const int32_t* cu,
-                            const int32_t* cu_k, void* workspace, hipStream_t s);
+                            const int32_t* cu_k, const PagedKeys* paged, void* workspace, hipStream_t s);
 // merge of the per-block statistics into one (reference, 1/sum) per row; with plan_ratio given
 // the same launch also does what launch_plan does (into plan_new_cu)
 hipError_t launch_merge_stats(const Problem& pb, const int32_t* cu, const int32_t* cu_k, void* workspace,
@@ -115,7 +124,7 @@ hipError_t launch_merge_stats(const Problem& pb, const int32_t* cu, const int32_
 // block-local top-k (in the same kernel when every key block has one work-group, otherwise in
 // k_finish)
 hipError_t launch_column_sums(const Problem& pb, const void* q, const void* k, const int32_t* cu,
-                              const int32_t* cu_k, void* workspace, float* scores_out, const SelectArgs* sel,
-                              hipStream_t s);
+                              const int32_t* cu_k, const PagedKeys* paged, void* workspace, float* scores_out,
+                              const SelectArgs* sel, hipStream_t s);
 
 }  // namespace up

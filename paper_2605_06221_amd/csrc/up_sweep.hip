@@ -68,6 +68,9 @@ struct SweepArgs {
   const char* k;
   const int32_t* cu;     // token offsets (queries, scores)
   const int32_t* cu_k;   // key offsets (== cu when no sequence has earlier context)
+  const int32_t* block_table;   // paged keys: physical block of every logical KV block, or nullptr
+  long long table_stride;       // entries per sequence in block_table
+  int kv_block;                 // tokens per KV block
   float2* stat_part;   // [key_block_slots][Hq * n_obs]  (reference in log2 units, sum)
   float2* stat_fin;    // [Hq][row_slots]                 (negative reference, 1/sum)
   float* scores_out;   // pass 2: optional
@@ -175,7 +178,13 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem<NW, F3
   constexpr int HOFF = F32 ? SRCB / 2 : 16;       // byte offset of the second lane half
   constexpr int KSTEP = F32 ? 16 : 32;            // bytes between a lane's register groups
   u32x4 kf[KREG];
-  const char* k_lane = a.k + (long long)(ck0 + imin(key_base + l32, Lk - 1)) * a.k_stride_b + half * HOFF;
+  // (paged keys: key i of the sequence lives in row block_table[r][i / B] * B + i % B of the cache)
+  const int k_idx = imin(key_base + l32, Lk - 1);
+  const long long k_row = a.block_table == nullptr
+                              ? (long long)ck0 + k_idx
+                              : (long long)a.block_table[(long long)r * a.table_stride + k_idx / a.kv_block] * a.kv_block +
+                                    k_idx % a.kv_block;
+  const char* k_lane = a.k + k_row * a.k_stride_b + half * HOFF;
   auto load_keys = [&](int g) {
 #pragma unroll
     for (int kk = 0; kk < KREG; ++kk)
@@ -645,11 +654,12 @@ Workspace workspace_layout(const Problem& pb) {
 }
 
 static SweepArgs make_sweep_args(const Problem& pb, const void* q, const void* k, const int32_t* cu,
-                                 const int32_t* cu_k, void* workspace) {
+                                 const int32_t* cu_k, void* workspace, const PagedKeys* paged = nullptr) {
   const Workspace w = workspace_layout(pb);
   char* ws = (char*)workspace;
   SweepArgs a{};
   a.q = (const char*)q; a.k = (const char*)k; a.cu = cu; a.cu_k = cu_k != nullptr ? cu_k : cu;
+  if (paged != nullptr) { a.block_table = paged->block_table; a.table_stride = paged->table_stride; a.kv_block = paged->kv_block; }
   a.stat_part = (float2*)(ws + w.stat_part_off);
   a.stat_fin = (float2*)(ws + w.stat_fin_off);
   a.scores_out = nullptr;
@@ -694,9 +704,9 @@ static hipError_t launch_sweep(const Problem& pb, const SweepArgs& a, hipStream_
 }
 
 hipError_t launch_row_stats(const Problem& pb, const void* q, const void* k, const int32_t* cu,
-                            const int32_t* cu_k, void* workspace, hipStream_t s) {
+                            const int32_t* cu_k, const PagedKeys* paged, void* workspace, hipStream_t s) {
   if (pb.T == 0) return hipSuccess;
-  const SweepArgs a = make_sweep_args(pb, q, k, cu, cu_k, workspace);
+  const SweepArgs a = make_sweep_args(pb, q, k, cu, cu_k, workspace, paged);
   return launch_sweep<1>(pb, a, s);
 }
 
@@ -719,10 +729,10 @@ hipError_t launch_merge_stats(const Problem& pb, const int32_t* cu, const int32_
 }
 
 hipError_t launch_column_sums(const Problem& pb, const void* q, const void* k, const int32_t* cu,
-                              const int32_t* cu_k, void* workspace, float* scores_out, const SelectArgs* sel,
-                              hipStream_t s) {
+                              const int32_t* cu_k, const PagedKeys* paged, void* workspace, float* scores_out,
+                              const SelectArgs* sel, hipStream_t s) {
   if (pb.T == 0) return hipSuccess;
-  SweepArgs a = make_sweep_args(pb, q, k, cu, cu_k, workspace);
+  SweepArgs a = make_sweep_args(pb, q, k, cu, cu_k, workspace, paged);
   a.split = pb.split2;
   a.scores_out = scores_out;
   if (sel != nullptr) { a.sel = *sel; a.do_select = 1; }

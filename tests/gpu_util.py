@@ -21,9 +21,10 @@ def host_bits(t: torch.Tensor) -> np.ndarray:
 class DeviceBatch:
     """A workload resident in HBM plus output buffers sized by uniprefill_plan."""
 
-    def __init__(self, w, softmax_scale: float = 0.0, canary: bool = True, qk_f32=None):
+    def __init__(self, w, softmax_scale: float = 0.0, canary: bool = True, qk_f32=None, paged=None):
         """qk_f32 = (q, k) float32 arrays of the workload's shapes: score from those instead of
-        the workload's bf16 tensors (the fp32 operand path)."""
+        the workload's bf16 tensors (the fp32 operand path).
+        paged = (k_cache bits, block_table, kv_block_size): the keys sit in a paged cache."""
         self.w = w
         self.cu_host = np.ascontiguousarray(w.cu_seqlens, dtype=np.int32)
         self.ratio_host = np.ascontiguousarray(w.keep_ratio, dtype=np.float32)
@@ -47,6 +48,11 @@ class DeviceBatch:
         else:
             self.q = torch.from_numpy(np.ascontiguousarray(qk_f32[0], dtype=np.float32)).cuda()
             self.k = torch.from_numpy(np.ascontiguousarray(qk_f32[1], dtype=np.float32)).cuda()
+        self.paged = None
+        if paged is not None:
+            self.k = dev_bf16(paged[0])
+            self.paged = (torch.from_numpy(np.ascontiguousarray(paged[1], dtype=np.int32)).cuda(), int(paged[1].shape[1]),
+                          int(paged[2]))
         self.hidden = dev_bf16(w.hidden)
         self.pos = torch.from_numpy(w.pos).cuda()
         self.cu = torch.from_numpy(self.cu_host).cuda()
@@ -62,6 +68,12 @@ class DeviceBatch:
 
     # ---- entry points -------------------------------------------------------
     def fused(self, want_scores=True, stream=None):
+        if self.paged is not None:
+            return up.uniprefill_fused_paged(self.p, self.q, self.k, self.hidden, self.pos, self.cu, self.cu_host,
+                                             self.cu_k, self.cu_k_host, self.paged[0], self.paged[1], self.paged[2],
+                                             self.ratio, self.ratio_host, self.hidden_out, self.pos_out,
+                                             self.kept_idx, self.new_cu, self.scores if want_scores else None,
+                                             self.workspace, self.ws_bytes, stream=stream)
         if self.ctx:
             return up.uniprefill_fused_chunked(self.p, self.q, self.k, self.hidden, self.pos, self.cu, self.cu_host,
                                                self.cu_k, self.cu_k_host, self.ratio, self.ratio_host,
@@ -74,6 +86,10 @@ class DeviceBatch:
                                    self.ws_bytes, stream=stream)
 
     def score(self):
+        if self.paged is not None:
+            return up.uniprefill_score_paged(self.p, self.q, self.k, self.cu, self.cu_host, self.cu_k, self.cu_k_host,
+                                             self.paged[0], self.paged[1], self.paged[2], self.scores,
+                                             self.workspace, self.ws_bytes)
         if self.ctx:
             return up.uniprefill_score_chunked(self.p, self.q, self.k, self.cu, self.cu_host, self.cu_k,
                                                self.cu_k_host, self.scores, self.workspace, self.ws_bytes)

@@ -888,3 +888,33 @@ def test_fused_random_geometries_with_context_and_head_dims_bit_exact(seed):
     b = DeviceBatch(w)
     b.fused()
     _assert_fused_exact(w, b, oracle_run(w))
+
+
+@pytest.mark.parametrize("kv_block", [16, 256])
+def test_paged_keys_equal_packed_keys(kv_block):
+    """Keys read through a block table out of a paged cache (random physical blocks, unused rows NaN):
+    the scores match the oracle on the keys gathered by Eq. 16, and the fused results are those of
+    the chunked entry on the packed keys, bit for bit."""
+    _say("paged keys, KV block", kv_block)
+    lengths, earlier = [3000, 40, 777, 1, 5000], [1000, 0, 64, 4097, 12345]
+    w = workloads.make_custom(name="paged", seed=23, lengths=lengths, keep_ratio=[0.3, 0.5, 0.7, 0.5, 0.25],
+                              hidden_dim=64, num_q_heads=8, num_kv_heads=2, block_size=64, n_obs=128, earlier=earlier)
+    cache, table = workloads.make_paged_cache(w.k, w.cu_seqlens_k, kv_block, seed=5)
+    packed = DeviceBatch(w)
+    packed.fused()
+    want = packed.results()
+    paged = DeviceBatch(w, paged=(cache, table, kv_block))
+    paged.fused()
+    got = paged.results()
+    for key in want:
+        np.testing.assert_array_equal(got[key], want[key], err_msg=key)
+    assert paged.canaries_intact()
+    # and against the oracle, reading the cache itself
+    k_read = oracle.gather_paged_keys(cache, w.cu_seqlens_k, table, kv_block)
+    ref = oracle.quantise_scores(oracle.importance_scores_with_context(
+        _q_f32(w), workloads.bf16_bits_to_f32(k_read), w.cu_seqlens, w.cu_seqlens_k, n_obs=w.n_obs))
+    paged.scores.fill_(-7.0)
+    paged.score()
+    ok, worst = _score_close(paged.results()["scores"], ref)
+    _say("  worst relative score error", worst)
+    assert ok

@@ -291,3 +291,21 @@ def test_bench_refuses_more_than_one_gpu():
                          text=True, timeout=120)
     assert res.returncode != 0
     assert "ONE GPU" in res.stderr and res.stdout.strip() == ""
+
+
+def test_paged_entries_reject_bad_block_tables():
+    L = up.lib()
+    fake = ctypes.c_void_p(0x1000)
+    cu = np.array([0, 100, 300], np.int32)
+    cu_k = np.array([0, 1000, 1200], np.int32)
+    p = _params(num_seqs=2, total_tokens=300)
+    odd = ctypes.c_void_p(0x1010)      # a workspace that is not 256-aligned: the last check before any launch
+    def score(table, stride, B):
+        return L.uniprefill_score_paged(ctypes.byref(p), fake, fake, fake, up.ptr(cu), fake, up.ptr(cu_k), table,
+                                        ctypes.c_int64(stride), B, fake, odd, ctypes.c_size_t(1 << 30), None)
+    assert score(None, 64, 16) == up.UP_ERR_NULL
+    assert score(fake, 64, 0) == up.UP_ERR_RANGE
+    assert score(fake, 62, 16) == up.UP_ERR_SHAPE          # 1000 keys need 63 blocks of 16
+    assert score(fake, -1, 16) == up.UP_ERR_RANGE
+    # the table is long enough with 63 entries: the next complaint is the workspace's alignment
+    assert score(fake, 63, 16) == up.UP_ERR_ALIGN

@@ -133,3 +133,20 @@ def test_selection_with_context_forces_only_the_sinks_that_fall_in_the_chunk():
         idx, ncu = oracle.select_tokens(s[cq[r]:cq[r + 1]], [0, Ns[r]], [0.25], block_size=64, n_obs=128, n_sink=A)
         assert ncu[1] == new_cu[r + 1] - new_cu[r]
         assert set(int(x) + int(cq[r]) for x in idx) <= kept
+
+
+def test_gather_paged_keys_hand_case_and_round_trip():
+    """Eq. 16 indexing.  Blocks of 2 rows; request 0 has 3 keys in physical blocks 2 and 0,
+    request 1 has 2 keys in block 3: written out by hand."""
+    cache = np.arange(10 * 1).reshape(10, 1).astype(np.float64)      # row i holds the value i
+    table = np.array([[2, 0], [3, -1]])
+    got = oracle.gather_paged_keys(cache, [0, 3, 5], table, 2)
+    np.testing.assert_array_equal(got[:, 0], [4, 5, 0, 6, 7])
+    # the generator's layout read back is the packed tensor (its own, independent, writer)
+    import workloads
+    rng = np.random.default_rng(8)
+    ck = np.array([0, 37, 37, 100, 164])
+    k = rng.standard_normal((164, 2, 4))
+    cache, table = workloads.make_paged_cache(k, ck, 16, seed=3)
+    np.testing.assert_array_equal(oracle.gather_paged_keys(cache, ck, table, 16), k)
+    assert len(set(table[table >= 0].tolist())) == (table >= 0).sum()        # no block used twice

@@ -23,6 +23,7 @@ import numpy as np
 
 __all__ = [
     "Workload",
+    "make_paged_cache",
     "f32_to_bf16_bits",
     "bf16_bits_to_f32",
     "make_config",
@@ -191,6 +192,30 @@ def make_custom(
         hidden_dim=hidden_dim, cu_seqlens=cu, keep_ratio=ratio,
         hidden=hidden, q=q, k=k, pos=pos, seed=seed, cu_seqlens_k=cu_k,
     )
+
+
+def make_paged_cache(k: np.ndarray, cu_seqlens_k, kv_block_size: int, seed: int, spare_blocks: int = 3):
+    """Lay packed keys out as a paged KV cache (input preparation only: a permuted copy).
+
+    Returns (k_cache [num_blocks * B, ...] with unused rows NaN, block_table int32 [R, max_blocks]
+    with unused entries -1).  Physical blocks are a seeded random permutation, a few stay unused."""
+    ck = np.asarray(cu_seqlens_k, dtype=np.int64)
+    B = int(kv_block_size)
+    R = len(ck) - 1
+    need = [int(-(-(ck[r + 1] - ck[r]) // B)) for r in range(R)]
+    total = sum(need) + spare_blocks
+    order = np.random.default_rng(seed).permutation(total)
+    table = np.full((R, max(need + [1])), -1, dtype=np.int32)
+    cache = np.full((total * B,) + k.shape[1:], 0x7FC0 if k.dtype == np.uint16 else np.nan, dtype=k.dtype)
+    nxt = 0
+    for r in range(R):
+        for b in range(need[r]):
+            phys = int(order[nxt]); nxt += 1
+            table[r, b] = phys
+            lo = int(ck[r]) + b * B
+            hi = min(int(ck[r + 1]), lo + B)
+            cache[phys * B:phys * B + (hi - lo)] = k[lo:hi]
+    return cache, table
 
 
 def make_config(idx: int, shrink: int = 1, hidden_dim: int | None = None) -> Workload:
