@@ -918,3 +918,29 @@ def test_paged_keys_equal_packed_keys(kv_block):
     ok, worst = _score_close(paged.results()["scores"], ref)
     _say("  worst relative score error", worst)
     assert ok
+
+
+def test_fused_one_million_tokens_bit_exact():
+    """One sequence of 2^20 tokens (2048 key blocks, 8192 selection blocks): row slots, key-block
+    slots and byte offsets far beyond the benchmark sizes."""
+    _say("fused 1M tokens")
+    w = workloads.make_custom(name="1m", seed=61, lengths=[1 << 20], keep_ratio=[0.2], hidden_dim=64,
+                              num_q_heads=8, num_kv_heads=2, block_size=128, n_obs=128)
+    b = DeviceBatch(w)
+    b.fused()
+    _assert_fused_exact(w, b, oracle_run(w))
+
+
+def test_fused_three_thousand_sequences_bit_exact():
+    """A continuous batch of 3000 short requests (empty ones and single tokens among them): the plan
+    scans the sequences 1024 (or 256) at a time, and every slot search runs over 3000 offsets."""
+    rng = np.random.default_rng(62)
+    lengths = [int(x) for x in rng.integers(0, 260, size=3000)]
+    lengths[:6] = [0, 1, 1, 0, 259, 128]
+    ratios = [float(x) for x in rng.uniform(0.1, 1.0, size=3000)]
+    _say("fused 3000 sequences, T", sum(lengths))
+    w = workloads.make_custom(name="3k", seed=63, lengths=lengths, keep_ratio=ratios, hidden_dim=32,
+                              num_q_heads=4, num_kv_heads=2, block_size=32, n_obs=16, n_sink=4)
+    b = DeviceBatch(w)
+    b.fused()
+    _assert_fused_exact(w, b, oracle_run(w))
