@@ -22,10 +22,13 @@
  *     no kernel ran.  Nothing throws or aborts.
  *       UP_ERR_NULL        a required pointer is NULL
  *       UP_ERR_SHAPE       cu_seqlens[0] != 0, cu_seqlens decreasing, or
- *                          cu_seqlens[R] != total_tokens; negative sizes
+ *                          cu_seqlens[R] != total_tokens; negative sizes; a
+ *                          sequence with fewer keys than tokens (cu_seqlens_k);
+ *                          a block-table row shorter than the sequence's keys
  *       UP_ERR_RANGE       keep ratio not in (0,1] or NaN; block_size not in
  *                          {32,64,128}; n_obs < 1 or > 1024; n_sink < 0;
- *                          total_kept inconsistent with the plan
+ *                          total_kept inconsistent with the plan; KV block
+ *                          size < 1; drop layers not strictly ascending
  *       UP_ERR_UNSUPPORTED head_dim not in {64,128,256}, or 256 with UP_F32
  *                          operands; num_q_heads % num_kv_heads != 0; more than
  *                          64 query heads per kv head; unknown dtype
