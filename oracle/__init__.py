@@ -5,5 +5,5 @@ from .uniprefill_oracle import (  # noqa: F401
     block_kept_counts, plan, select_tokens, compact, scatter, sparsify, block_mass, select_blocks_top_p,
     block_mass_f32, top_p_block_keys, top_p_kept_blocks, select_tokens_top_p, compose_index,
     retained_lengths, kv_slot_mapping, seqused, seqused_per_layer, importance_scores_with_context, sinks_in_chunk, gather_paged_keys,
-    select_tokens_with_context, sparsify_with_context,
+    select_tokens_with_context, sparsify_with_context, select_tokens_top_p_with_context,
 )

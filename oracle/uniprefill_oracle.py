@@ -467,6 +467,25 @@ def select_tokens_with_context(scores_f32, cu_seqlens_q, cu_seqlens_k, keep_rati
     return kept_idx.astype(np.int32), new_cu
 
 
+def select_tokens_top_p_with_context(scores_f32, cu_seqlens_q, cu_seqlens_k, top_p, *, block_size, n_obs, n_sink):
+    """The paper's block-level top-p rule over the chunk tokens: ``select_tokens_top_p`` request by
+    request with the sinks that fall inside the chunk.  The threshold is p times the mass of the
+    chunk's own blocks (the earlier tokens were decided when they were a chunk)."""
+    s = np.asarray(scores_f32, dtype=np.float32)
+    cq = np.asarray(cu_seqlens_q, dtype=np.int64)
+    A = sinks_in_chunk(cu_seqlens_q, cu_seqlens_k, n_sink)
+    kept = []
+    new_cu = np.zeros(len(cq), dtype=np.int32)
+    for r in range(len(cq) - 1):
+        c0, c1 = int(cq[r]), int(cq[r + 1])
+        idx, ncu = select_tokens_top_p(s[c0:c1], [0, c1 - c0], [top_p[r]], block_size=block_size,
+                                       n_obs=n_obs, n_sink=int(A[r]))
+        kept.append(idx.astype(np.int64) + c0)
+        new_cu[r + 1] = new_cu[r] + ncu[1]
+    kept_idx = np.concatenate(kept) if kept else np.zeros(0, dtype=np.int64)
+    return kept_idx.astype(np.int32), new_cu
+
+
 def sparsify_with_context(q, k, hidden, pos, cu_seqlens_q, cu_seqlens_k, keep_ratio, *, block_size, n_obs,
                           n_sink, scale=None):
     """score -> quantise -> select -> compact for chunks that follow earlier context."""

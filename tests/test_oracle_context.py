@@ -150,3 +150,26 @@ def test_gather_paged_keys_hand_case_and_round_trip():
     cache, table = workloads.make_paged_cache(k, ck, 16, seed=3)
     np.testing.assert_array_equal(oracle.gather_paged_keys(cache, ck, table, 16), k)
     assert len(set(table[table >= 0].tolist())) == (table >= 0).sum()        # no block used twice
+
+
+def test_top_p_with_context_differs_from_the_plain_rule_only_in_the_sinks():
+    rng = np.random.default_rng(11)
+    Ns, Ps = [700, 300, 64, 1000], [0, 50, 500, 127]
+    cq = np.concatenate([[0], np.cumsum(Ns)])
+    ck = np.concatenate([[0], np.cumsum(np.add(Ns, Ps))])
+    s = (rng.random(cq[-1]) ** 6).astype(np.float32)
+    tp = np.array([0.9, 0.5, 0.99, 0.7], np.float32)
+    kept, new_cu = oracle.select_tokens_top_p_with_context(s, cq, ck, tp, block_size=64, n_obs=32, n_sink=128)
+    kept = set(int(x) for x in kept)
+    # no earlier tokens anywhere: the plain rule
+    k0, n0 = oracle.select_tokens_top_p_with_context(s, cq, cq, tp, block_size=64, n_obs=32, n_sink=128)
+    k1, n1 = oracle.select_tokens_top_p(s, cq, tp, block_size=64, n_obs=32, n_sink=128)
+    np.testing.assert_array_equal(k0, k1)
+    np.testing.assert_array_equal(n0, n1)
+    for r, (N, P) in enumerate(zip(Ns, Ps)):
+        A = max(0, 128 - P)
+        # what the block rule keeps does not depend on the sinks; the forced tokens do
+        plain, _ = oracle.select_tokens_top_p(s[cq[r]:cq[r + 1]], [0, N], [tp[r]], block_size=64, n_obs=32, n_sink=0)
+        want = set(int(x) + int(cq[r]) for x in plain) | set(int(cq[r]) + i for i in range(min(A, N)))
+        assert {t for t in kept if cq[r] <= t < cq[r + 1]} == want
+        assert new_cu[r + 1] - new_cu[r] == len(want)
