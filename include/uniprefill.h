@@ -342,6 +342,27 @@ int uniprefill_fused_paged(const up_params* p, const void* q, const void* k_cach
                            int32_t* kept_idx, int32_t* new_cu_seqlens_dev, float* scores_out,
                            void* workspace, size_t workspace_bytes, void* stream);
 
+/* The paper's block-level top-p rule (uniprefill_select_top_p, uniprefill_fused_top_p) for
+ * tokens that follow earlier context: the sinks are those that fall inside the
+ * tokens (position P_r + i below n_sink), and the threshold is p times the mass
+ * of the tokens' own blocks.  The fused variant takes the keys packed by
+ * cu_seqlens_k (block_table NULL) or in a paged cache (block_table given, as
+ * for uniprefill_fused_paged).  Workspace from uniprefill_plan_chunked. */
+int uniprefill_select_top_p_chunked(const up_params* p, const float* scores,
+                                    const int32_t* cu_seqlens_dev, const int32_t* cu_seqlens_host,
+                                    const int32_t* cu_seqlens_k_dev, const int32_t* cu_seqlens_k_host,
+                                    const float* top_p_dev, const float* top_p_host, int32_t* kept_idx,
+                                    int32_t* new_cu_seqlens_dev, void* workspace,
+                                    size_t workspace_bytes, void* stream);
+int uniprefill_fused_top_p_chunked(const up_params* p, const void* q, const void* k, const void* hidden,
+                                   const int32_t* pos, const int32_t* cu_seqlens_dev,
+                                   const int32_t* cu_seqlens_host, const int32_t* cu_seqlens_k_dev,
+                                   const int32_t* cu_seqlens_k_host, const int32_t* block_table,
+                                   int64_t block_table_stride, int32_t kv_block_size,
+                                   const float* top_p_dev, const float* top_p_host, void* hidden_out,
+                                   int32_t* pos_out, int32_t* kept_idx, int32_t* new_cu_seqlens_dev,
+                                   float* scores, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Static, never NULL. */
 const char* uniprefill_status_string(int status);
 

@@ -23,7 +23,8 @@ EXPORTS = ["uniprefill_plan", "uniprefill_score", "uniprefill_select", "uniprefi
            "uniprefill_compact_counted", "uniprefill_fused_top_p", "uniprefill_compose_index",
            "uniprefill_slot_mapping", "uniprefill_plan_chunked", "uniprefill_score_chunked",
            "uniprefill_select_chunked", "uniprefill_fused_chunked", "uniprefill_compact_column", "uniprefill_seqused",
-           "uniprefill_score_paged", "uniprefill_fused_paged",
+           "uniprefill_score_paged", "uniprefill_fused_paged", "uniprefill_select_top_p_chunked",
+           "uniprefill_fused_top_p_chunked",
            "uniprefill_status_string"]
 
 UP_PHASE_PLAN, UP_PHASE_ROW_STATS, UP_PHASE_MERGE_STATS, UP_PHASE_SWEEP_SELECT, UP_PHASE_GATHER = 1, 2, 4, 8, 16
@@ -254,6 +255,30 @@ def uniprefill_fused_paged(p, q, k_cache, hidden, pos, cu_seqlens_dev, cu_seqlen
                                      ptr(pos_out), ptr(kept_idx), ptr(new_cu_seqlens_dev), ptr(scores_out),
                                      ptr(workspace), workspace_bytes, _stream(stream))
     return _check(st, "uniprefill_fused_paged", check)
+
+
+def uniprefill_select_top_p_chunked(p, scores, cu_seqlens_dev, cu_seqlens_host, cu_seqlens_k_dev, cu_seqlens_k_host,
+                                    top_p_dev, top_p_host, kept_idx, new_cu_seqlens_dev, workspace, workspace_bytes,
+                                    stream=None, check=True):
+    st = _lib.uniprefill_select_top_p_chunked(ctypes.byref(p), ptr(scores), ptr(cu_seqlens_dev), ptr(cu_seqlens_host),
+                                              ptr(cu_seqlens_k_dev), ptr(cu_seqlens_k_host), ptr(top_p_dev),
+                                              ptr(top_p_host), ptr(kept_idx), ptr(new_cu_seqlens_dev), ptr(workspace),
+                                              workspace_bytes, _stream(stream))
+    return _check(st, "uniprefill_select_top_p_chunked", check)
+
+
+def uniprefill_fused_top_p_chunked(p, q, k, hidden, pos, cu_seqlens_dev, cu_seqlens_host, cu_seqlens_k_dev,
+                                   cu_seqlens_k_host, block_table, block_table_stride, kv_block_size, top_p_dev,
+                                   top_p_host, hidden_out, pos_out, kept_idx, new_cu_seqlens_dev, scores, workspace,
+                                   workspace_bytes, stream=None, check=True):
+    st = _lib.uniprefill_fused_top_p_chunked(ctypes.byref(p), ptr(q), ptr(k), ptr(hidden), ptr(pos),
+                                             ptr(cu_seqlens_dev), ptr(cu_seqlens_host), ptr(cu_seqlens_k_dev),
+                                             ptr(cu_seqlens_k_host), ptr(block_table),
+                                             ctypes.c_int64(block_table_stride), int(kv_block_size), ptr(top_p_dev),
+                                             ptr(top_p_host), ptr(hidden_out), ptr(pos_out), ptr(kept_idx),
+                                             ptr(new_cu_seqlens_dev), ptr(scores), ptr(workspace), workspace_bytes,
+                                             _stream(stream))
+    return _check(st, "uniprefill_fused_top_p_chunked", check)
 
 
 def uniprefill_fused_phases(p, q, k, hidden, pos, cu_seqlens_dev, cu_seqlens_host, keep_ratio_dev,

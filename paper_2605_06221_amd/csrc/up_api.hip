@@ -336,6 +336,57 @@ int fused_impl(const up_params* p, const void* q, const void* k, const void* hid
   return UP_OK;
 }
 
+int select_top_p_impl(const up_params* p, const float* scores, const int32_t* cu_dev, const int32_t* cu_host,
+                      const KeySide& ks, const float* top_p_dev, const float* top_p_host, int32_t* kept_idx,
+                      int32_t* new_cu_dev, void* workspace, size_t workspace_bytes, void* stream) {
+  Problem pb;
+  int st = check_params(p, false, false, &pb);
+  if (st != UP_OK) return st;
+  if (!scores || !cu_dev || !top_p_dev || !kept_idx || !new_cu_dev) return UP_ERR_NULL;
+  if ((st = check_cu(p, cu_host)) != UP_OK) return st;
+  if ((st = check_key_side(p, cu_host, ks)) != UP_OK) return st;
+  if ((st = check_ratio(p, top_p_host)) != UP_OK) return st;
+  int max_blocks = 0;
+  for (int r = 0; r < p->num_seqs; ++r)
+    max_blocks = imax(max_blocks, (cu_host[r + 1] - cu_host[r] + pb.G - 1) / pb.G);
+  if (max_blocks > kMaxTopPBlocks) return UP_ERR_UNSUPPORTED;
+  if (workspace == nullptr || workspace_bytes < workspace_layout(pb).tp_total) return UP_ERR_WORKSPACE;
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return UP_ERR_ALIGN;
+  if (launch_top_p(pb, scores, cu_dev, ks.cu_k_dev, top_p_dev, kept_idx, new_cu_dev, workspace, max_blocks,
+                   (hipStream_t)stream) != hipSuccess)
+    return UP_ERR_HIP;
+  return UP_OK;
+}
+
+// score -> top-p selection -> gather with the count on the device; every check of the three
+// steps happens before the first launch
+int fused_top_p_impl(const up_params* p, const void* q, const void* k, const void* hidden, const int32_t* pos,
+                     const int32_t* cu_dev, const int32_t* cu_host, const KeySide& ks, const float* top_p_dev,
+                     const float* top_p_host, void* hidden_out, int32_t* pos_out, int32_t* kept_idx,
+                     int32_t* new_cu_dev, float* scores, void* workspace, size_t workspace_bytes, void* stream) {
+  Problem pb;
+  int st = check_params(p, true, true, &pb);
+  if (st != UP_OK) return st;
+  if (!q || !k || !hidden || !cu_dev || !top_p_dev || !hidden_out || !kept_idx || !new_cu_dev || !scores)
+    return UP_ERR_NULL;
+  if ((pos == nullptr) != (pos_out == nullptr)) return UP_ERR_NULL;
+  if ((st = check_cu(p, cu_host)) != UP_OK) return st;
+  if ((st = check_key_side(p, cu_host, ks)) != UP_OK) return st;
+  if ((st = check_ratio(p, top_p_host)) != UP_OK) return st;
+  for (int r = 0; r < p->num_seqs; ++r)
+    if ((cu_host[r + 1] - cu_host[r] + pb.G - 1) / pb.G > kMaxTopPBlocks) return UP_ERR_UNSUPPORTED;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(hidden) || !aligned16(hidden_out)) return UP_ERR_ALIGN;
+  choose_geometry(&pb, cu_host, ks.cu_k_host);
+  if (workspace == nullptr || workspace_bytes < workspace_layout(pb).total) return UP_ERR_WORKSPACE;
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return UP_ERR_ALIGN;
+  if ((st = score_impl(p, q, k, cu_dev, cu_host, ks, scores, workspace, workspace_bytes, stream)) != UP_OK) return st;
+  if ((st = select_top_p_impl(p, scores, cu_dev, cu_host, ks, top_p_dev, top_p_host, kept_idx, new_cu_dev,
+                              workspace, workspace_bytes, stream)) != UP_OK)
+    return st;
+  return uniprefill_compact_counted(p, hidden, pos, kept_idx, new_cu_dev + p->num_seqs, p->total_tokens, hidden_out,
+                                    pos_out, stream);
+}
+
 }  // namespace
 
 extern "C" {
@@ -400,22 +451,18 @@ int uniprefill_select_top_p(const up_params* p, const float* scores, const int32
                             const int32_t* cu_seqlens_host, const float* top_p_dev,
                             const float* top_p_host, int32_t* kept_idx, int32_t* new_cu_seqlens_dev,
                             void* workspace, size_t workspace_bytes, void* stream) {
-  Problem pb;
-  int st = check_params(p, false, false, &pb);
-  if (st != UP_OK) return st;
-  if (!scores || !cu_seqlens_dev || !top_p_dev || !kept_idx || !new_cu_seqlens_dev) return UP_ERR_NULL;
-  if ((st = check_cu(p, cu_seqlens_host)) != UP_OK) return st;
-  if ((st = check_ratio(p, top_p_host)) != UP_OK) return st;
-  int max_blocks = 0;
-  for (int r = 0; r < p->num_seqs; ++r)
-    max_blocks = imax(max_blocks, (cu_seqlens_host[r + 1] - cu_seqlens_host[r] + pb.G - 1) / pb.G);
-  if (max_blocks > kMaxTopPBlocks) return UP_ERR_UNSUPPORTED;
-  if (workspace == nullptr || workspace_bytes < workspace_layout(pb).tp_total) return UP_ERR_WORKSPACE;
-  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return UP_ERR_ALIGN;
-  if (launch_top_p(pb, scores, cu_seqlens_dev, top_p_dev, kept_idx, new_cu_seqlens_dev, workspace, max_blocks,
-                   (hipStream_t)stream) != hipSuccess)
-    return UP_ERR_HIP;
-  return UP_OK;
+  return select_top_p_impl(p, scores, cu_seqlens_dev, cu_seqlens_host, kOwnKeys, top_p_dev, top_p_host, kept_idx,
+                           new_cu_seqlens_dev, workspace, workspace_bytes, stream);
+}
+
+int uniprefill_select_top_p_chunked(const up_params* p, const float* scores, const int32_t* cu_seqlens_dev,
+                                    const int32_t* cu_seqlens_host, const int32_t* cu_seqlens_k_dev,
+                                    const int32_t* cu_seqlens_k_host, const float* top_p_dev,
+                                    const float* top_p_host, int32_t* kept_idx, int32_t* new_cu_seqlens_dev,
+                                    void* workspace, size_t workspace_bytes, void* stream) {
+  const KeySide ks{cu_seqlens_k_dev, cu_seqlens_k_host, true, nullptr};
+  return select_top_p_impl(p, scores, cu_seqlens_dev, cu_seqlens_host, ks, top_p_dev, top_p_host, kept_idx,
+                           new_cu_seqlens_dev, workspace, workspace_bytes, stream);
 }
 
 int uniprefill_compact_counted(const up_params* p, const void* hidden, const int32_t* pos,
@@ -440,33 +487,24 @@ int uniprefill_fused_top_p(const up_params* p, const void* q, const void* k, con
                            const float* top_p_host, void* hidden_out, int32_t* pos_out,
                            int32_t* kept_idx, int32_t* new_cu_seqlens_dev, float* scores,
                            void* workspace, size_t workspace_bytes, void* stream) {
-  // every check of the three steps before the first launch
-  Problem pb;
-  int st = check_params(p, true, true, &pb);
-  if (st != UP_OK) return st;
-  if (!q || !k || !hidden || !cu_seqlens_dev || !top_p_dev || !hidden_out || !kept_idx ||
-      !new_cu_seqlens_dev || !scores)
-    return UP_ERR_NULL;
-  if ((pos == nullptr) != (pos_out == nullptr)) return UP_ERR_NULL;
-  if ((st = check_cu(p, cu_seqlens_host)) != UP_OK) return st;
-  if ((st = check_ratio(p, top_p_host)) != UP_OK) return st;
-  for (int r = 0; r < p->num_seqs; ++r)
-    if ((cu_seqlens_host[r + 1] - cu_seqlens_host[r] + pb.G - 1) / pb.G > kMaxTopPBlocks)
-      return UP_ERR_UNSUPPORTED;
-  if (!aligned16(q) || !aligned16(k) || !aligned16(hidden) || !aligned16(hidden_out))
-    return UP_ERR_ALIGN;
-  choose_geometry(&pb, cu_seqlens_host);
-  if (workspace == nullptr || workspace_bytes < workspace_layout(pb).total) return UP_ERR_WORKSPACE;
-  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return UP_ERR_ALIGN;
-  if ((st = uniprefill_score(p, q, k, cu_seqlens_dev, cu_seqlens_host, scores, workspace,
-                             workspace_bytes, stream)) != UP_OK)
-    return st;
-  if ((st = uniprefill_select_top_p(p, scores, cu_seqlens_dev, cu_seqlens_host, top_p_dev, top_p_host,
-                                    kept_idx, new_cu_seqlens_dev, workspace, workspace_bytes,
-                                    stream)) != UP_OK)
-    return st;
-  return uniprefill_compact_counted(p, hidden, pos, kept_idx, new_cu_seqlens_dev + p->num_seqs,
-                                    p->total_tokens, hidden_out, pos_out, stream);
+  return fused_top_p_impl(p, q, k, hidden, pos, cu_seqlens_dev, cu_seqlens_host, kOwnKeys, top_p_dev, top_p_host,
+                          hidden_out, pos_out, kept_idx, new_cu_seqlens_dev, scores, workspace, workspace_bytes,
+                          stream);
+}
+
+int uniprefill_fused_top_p_chunked(const up_params* p, const void* q, const void* k, const void* hidden,
+                                   const int32_t* pos, const int32_t* cu_seqlens_dev,
+                                   const int32_t* cu_seqlens_host, const int32_t* cu_seqlens_k_dev,
+                                   const int32_t* cu_seqlens_k_host, const int32_t* block_table,
+                                   int64_t block_table_stride, int32_t kv_block_size, const float* top_p_dev,
+                                   const float* top_p_host, void* hidden_out, int32_t* pos_out,
+                                   int32_t* kept_idx, int32_t* new_cu_seqlens_dev, float* scores,
+                                   void* workspace, size_t workspace_bytes, void* stream) {
+  const PagedKeys paged{block_table, block_table_stride, kv_block_size};
+  const KeySide ks{cu_seqlens_k_dev, cu_seqlens_k_host, true, block_table != nullptr ? &paged : nullptr};
+  return fused_top_p_impl(p, q, k, hidden, pos, cu_seqlens_dev, cu_seqlens_host, ks, top_p_dev, top_p_host,
+                          hidden_out, pos_out, kept_idx, new_cu_seqlens_dev, scores, workspace, workspace_bytes,
+                          stream);
 }
 
 int uniprefill_compact(const up_params* p, const void* hidden, const int32_t* pos,

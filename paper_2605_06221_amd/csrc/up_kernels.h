@@ -84,6 +84,7 @@ constexpr int kMaxTopPBlocks = 4096;   // blocks of one sequence that the top-p 
 struct TopPArgs {
   const float* scores;
   const int32_t* cu;
+  const int32_t* cu_k;   // key-side offsets when the tokens follow earlier context, else nullptr
   const float* top_p;
   int32_t* kept_idx;
   int32_t* new_cu;
@@ -95,8 +96,9 @@ struct TopPArgs {
   int R, T, G, n_obs, n_sink;
 };
 // (max_blocks: selection blocks of the longest sequence, at most kMaxTopPBlocks)
-hipError_t launch_top_p(const Problem& pb, const float* scores, const int32_t* cu, const float* top_p,
-                        int32_t* kept_idx, int32_t* new_cu, void* workspace, int max_blocks, hipStream_t s);
+hipError_t launch_top_p(const Problem& pb, const float* scores, const int32_t* cu, const int32_t* cu_k,
+                        const float* top_p, int32_t* kept_idx, int32_t* new_cu, void* workspace, int max_blocks,
+                        hipStream_t s);
 // gather with the row count on the device (count_dev[0] rows, at most capacity)
 hipError_t launch_compact_counted(const Problem& pb, const void* hidden, const int32_t* pos,
                                   const int32_t* kept_idx, const int32_t* count_dev, long long capacity,

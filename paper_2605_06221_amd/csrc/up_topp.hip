@@ -156,7 +156,7 @@ __global__ __launch_bounds__(kTopPThreads) void k_top_p_blocks(TopPArgs a) {
   for (int w2 = 0; w2 < kTopPThreads / 64; ++w2) kstar += sm.kstar_part[w2];
   kstar = imin(kstar, nb);
   // 5. tokens kept per block and their exclusive prefix inside the sequence
-  SeqGeom sg{N, G, a.n_obs, a.n_sink, 1.0};
+  SeqGeom sg{N, G, a.n_obs, sinks_of(a.cu_k, a.n_sink, r, N), 1.0};
   int carry = 0;
   for (int base = 0; base < nb; base += kTopPThreads) {
     const int g = base + tid;
@@ -230,7 +230,7 @@ __global__ __launch_bounds__(128) void k_top_p_emit(TopPArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int i = g * G + tid;
   const bool in_block = tid < G && i < N;
-  const bool keep = in_block && (a.blk_keep[slot] != 0 || i < a.n_sink || i >= N - a.n_obs);
+  const bool keep = in_block && (a.blk_keep[slot] != 0 || i < sinks_of(a.cu_k, a.n_sink, r, N) || i >= N - a.n_obs);
   const unsigned long long bal = __ballot(keep);
   const int before = __popcll(bal & ((1ull << lane) - 1ull));
   if (wave == 0 && lane == 0) cnt0 = __popcll(bal);
@@ -238,12 +238,13 @@ __global__ __launch_bounds__(128) void k_top_p_emit(TopPArgs a) {
   if (keep) a.kept_idx[a.new_cu[r] + a.blk_off[slot] + before + (wave == 1 ? cnt0 : 0)] = c0 + i;
 }
 
-hipError_t launch_top_p(const Problem& pb, const float* scores, const int32_t* cu, const float* top_p,
-                        int32_t* kept_idx, int32_t* new_cu, void* workspace, int max_blocks, hipStream_t s) {
+hipError_t launch_top_p(const Problem& pb, const float* scores, const int32_t* cu, const int32_t* cu_k,
+                        const float* top_p, int32_t* kept_idx, int32_t* new_cu, void* workspace, int max_blocks,
+                        hipStream_t s) {
   const Workspace w = workspace_layout(pb);
   char* ws = (char*)workspace;
   TopPArgs a;
-  a.scores = scores; a.cu = cu; a.top_p = top_p; a.kept_idx = kept_idx; a.new_cu = new_cu;
+  a.scores = scores; a.cu = cu; a.cu_k = cu_k; a.top_p = top_p; a.kept_idx = kept_idx; a.new_cu = new_cu;
   a.blk_keep = (int32_t*)(ws + w.tp_keep_off);
   a.blk_off = (int32_t*)(ws + w.tp_off_off);
   a.seq_kept = (int32_t*)(ws + w.tp_seq_off);

@@ -944,3 +944,59 @@ def test_fused_three_thousand_sequences_bit_exact():
     b = DeviceBatch(w)
     b.fused()
     _assert_fused_exact(w, b, oracle_run(w))
+
+
+@pytest.mark.parametrize("paged", [False, True])
+def test_fused_top_p_with_earlier_context(paged):
+    """The paper's top-p rule on chunks that follow earlier context, keys packed or in a paged cache."""
+    _say("fused top-p with context, paged" if paged else "fused top-p with context")
+    lengths, earlier = [3000, 150, 0, 1111, 64], [500, 0, 77, 4000, 100]
+    w = workloads.make_custom(name="ftpc", seed=24, lengths=lengths, keep_ratio=[0.5] * 5, hidden_dim=64,
+                              num_q_heads=8, num_kv_heads=2, block_size=64, n_obs=128, earlier=earlier)
+    top_p = np.array([0.9, 0.99, 0.5, 0.8, 0.7], np.float32)
+    b = _top_p_buffers(w)
+    cu_k_host = np.ascontiguousarray(w.cu_seqlens_k, dtype=np.int32)
+    cu_k = torch.from_numpy(cu_k_host).cuda()
+    _, _, _, ws_bytes = up.uniprefill_plan_chunked(b["p"], b["cu_host"], cu_k_host, np.full(w.num_seqs, 0.5, np.float32))
+    workspace = torch.empty(ws_bytes + 256, dtype=torch.uint8, device="cuda")
+    T, d = w.total_tokens, w.hidden_dim
+    table_dev, stride, B = None, 0, 16
+    k_bits = w.k
+    if paged:
+        k_bits, table = workloads.make_paged_cache(w.k, w.cu_seqlens_k, B, seed=6)
+        table_dev, stride = torch.from_numpy(table).cuda(), table.shape[1]
+    q, k, hidden = dev_bf16(w.q), dev_bf16(k_bits), dev_bf16(w.hidden)
+    pos = torch.from_numpy(w.pos).cuda()
+    hidden_out = torch.full((T + 8, d), -7.0, dtype=torch.bfloat16, device="cuda")
+    pos_out = torch.full((T + 8,), -77, dtype=torch.int32, device="cuda")
+    scores = torch.empty(T, dtype=torch.float32, device="cuda")
+    up.uniprefill_fused_top_p_chunked(b["p"], q, k, hidden, pos, b["cu"], b["cu_host"], cu_k, cu_k_host, table_dev,
+                                      stride, B, torch.from_numpy(top_p).cuda(), top_p, hidden_out, pos_out,
+                                      b["kept_idx"], b["new_cu"], scores, workspace, ws_bytes)
+    torch.cuda.synchronize()
+    got_scores = scores.cpu().numpy()
+    got_cu = b["new_cu"][:w.num_seqs + 1].cpu().numpy()
+    total = int(got_cu[-1])
+    got_idx = b["kept_idx"][:total].cpu().numpy()
+    ref_scores = oracle.quantise_scores(oracle.importance_scores_with_context(
+        _q_f32(w), workloads.bf16_bits_to_f32(w.k), w.cu_seqlens, w.cu_seqlens_k, n_obs=w.n_obs))
+    ok, worst = _score_close(got_scores, ref_scores)
+    assert ok
+    # the selection is the oracle's rule on the scores the GPU produced, and on this input also on the oracle's
+    for sc in (got_scores, ref_scores):
+        want_idx, want_cu = oracle.select_tokens_top_p_with_context(sc, w.cu_seqlens, w.cu_seqlens_k, top_p,
+                                                                    block_size=w.block_size, n_obs=w.n_obs, n_sink=w.n_sink)
+        np.testing.assert_array_equal(got_cu, want_cu)
+        np.testing.assert_array_equal(got_idx, want_idx)
+    _say("  kept", total, "of", T, "worst score error", worst)
+    want_h, want_p = oracle.compact(w.hidden, w.pos, got_idx)
+    np.testing.assert_array_equal(host_bits(hidden_out[:total]), want_h)
+    np.testing.assert_array_equal(pos_out[:total].cpu().numpy(), want_p)
+    assert (hidden_out[total:] == -7.0).all() and (pos_out[total:] == -77).all()
+    assert (b["kept_idx"][total:] == -77).all()
+    # the stand-alone selection on the same scores
+    b["kept_idx"].fill_(-77)
+    up.uniprefill_select_top_p_chunked(b["p"], scores, b["cu"], b["cu_host"], cu_k, cu_k_host, torch.from_numpy(top_p).cuda(),
+                                       top_p, b["kept_idx"], b["new_cu"], workspace, ws_bytes)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(b["kept_idx"][:total].cpu().numpy(), got_idx)
