@@ -287,6 +287,16 @@ def main():
         cpu_baseline = {"value": round(w.total_tokens / cpu_s, 1), "unit": "tokens/s", "cores": int(threads),
                         "kind": "oracle", "seconds": round(cpu_s, 2),
                         "sample": f"the full {w.name} batch, one pass (BLAS threads = cores; numpy exp is single-threaded)"}
+        # the same pass on one thread (how much of the figure above is the BLAS library's threading)
+        try:
+            from threadpoolctl import threadpool_limits
+            with threadpool_limits(limits=1):
+                t1 = time.perf_counter()
+                oracle_run(w)
+                cpu_1 = time.perf_counter() - t1
+            cpu_baseline["single_thread"] = {"value": round(w.total_tokens / cpu_1, 1), "seconds": round(cpu_1, 2)}
+        except Exception:
+            pass
         torch.cuda.synchronize()
         parity = bool(np.array_equal(kept_idx.cpu().numpy(), ref["kept_idx"])
                       and np.array_equal(hidden_out.view(torch.int16).cpu().numpy().view(np.uint16), ref["hidden_out"])
