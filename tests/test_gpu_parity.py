@@ -164,6 +164,8 @@ def _score_close(got, want32):
     dict(lengths=[900, 77], Hq=4, Hkv=4, n_obs=32),
     dict(lengths=[600], Hq=2, Hkv=1, n_obs=512),
     dict(lengths=[2100], Hq=16, Hkv=2, n_obs=200),
+    dict(lengths=[3000, 500], Hq=2, Hkv=2, n_obs=1024),       # the largest window
+    dict(lengths=[1300, 1, 70], Hq=6, Hkv=2, n_obs=1),        # a single query row
 ])
 def test_scores_match_oracle(case):
     _say("score", case)
