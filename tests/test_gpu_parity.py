@@ -607,7 +607,7 @@ def test_second_drop_on_the_compacted_stream_and_composed_scatter():
 
 
 # ----------------------------------------------------------------------------- seeded random geometries
-@pytest.mark.parametrize("seed", range(10))
+@pytest.mark.parametrize("seed", range(24))
 def test_fused_random_geometries_bit_exact(seed):
     """Random batch shapes, head layouts, block sizes, window and sink sizes: the launch geometry
     (key-block size, head split, edge classes) must never show in the result."""
@@ -865,7 +865,7 @@ def test_fused_call_replayed_from_a_hip_graph():
         assert b.canaries_intact()
 
 
-@pytest.mark.parametrize("seed", range(8))
+@pytest.mark.parametrize("seed", range(24))
 def test_fused_random_geometries_with_context_and_head_dims_bit_exact(seed):
     """Like the random geometries above, with a random amount of earlier context per request
     (none for some) and head dimensions 64 / 128 / 256."""
