@@ -316,6 +316,15 @@ def select_tokens_top_p(scores_f32, cu_seqlens, top_p, *, block_size, n_obs, n_s
 # --------------------------------------------------------------------------- #
 # index maps across drop layers ("Sparsity Propagation Across All Layers")
 # --------------------------------------------------------------------------- #
+def keep_mask(kept_idx, total_tokens):
+    """The token keep mask M in {0,1}^T that the index list stands for ("Top-p Token Selection";
+    expansion kernel of the kernel-design paragraph): 1 at the kept packed rows."""
+    m = np.zeros(int(total_tokens), dtype=np.uint8)
+    for i in np.asarray(kept_idx, dtype=np.int64):
+        m[i] = 1
+    return m
+
+
 def compose_index(outer_idx, inner_idx):
     """Index map of two successive drops: inner_idx selects rows of the stream that
     outer_idx had compacted, so row t of the twice-compacted stream is packed row

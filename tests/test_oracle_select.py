@@ -433,3 +433,17 @@ def test_seqused_per_layer_hand_worked_history():
         s = orig if k is None else hist[k]
         np.testing.assert_array_equal(table[layer], oracle.seqused(s, kv, orig))
     assert (np.diff(table.astype(np.int64), axis=0) <= 0).all()
+
+
+def test_keep_mask_hand_case_and_agreement_with_the_selection():
+    np.testing.assert_array_equal(oracle.keep_mask([0, 3, 4, 9], 11), [1, 0, 0, 1, 1, 0, 0, 0, 0, 1, 0])
+    np.testing.assert_array_equal(oracle.keep_mask([], 3), [0, 0, 0])
+    rng = np.random.default_rng(14)
+    cu = np.array([0, 300, 300, 1000])
+    s32 = rng.random(1000).astype(np.float32)
+    kept, new_cu = oracle.select_tokens(s32, cu, [0.3, 0.5, 0.7], block_size=64, n_obs=32, n_sink=8)
+    m = oracle.keep_mask(kept, 1000)
+    assert int(m.sum()) == len(kept) == new_cu[-1]
+    np.testing.assert_array_equal(np.nonzero(m)[0], kept)                       # the list is the mask's support, ascending
+    for r in range(3):
+        assert int(m[cu[r]:cu[r + 1]].sum()) == new_cu[r + 1] - new_cu[r]
