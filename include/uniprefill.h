@@ -251,6 +251,16 @@ int uniprefill_fused_phases(const up_params* p, const void* q, const void* k, co
                             int32_t* kept_idx, int32_t* new_cu_seqlens_dev, float* scores_out,
                             void* workspace, size_t workspace_bytes, int phase_mask, void* stream);
 
+/* The token keep mask M in {0,1}^T that the index list stands for (Top-p Token
+ * Selection; what the expansion kernel of the kernel-design paragraph leaves):
+ * mask_out[t] = 1 if packed row t is among kept_idx[0 .. n), else 0, for every
+ * t < total_tokens; n = capacity, or total_kept_dev[0] when that device pointer
+ * is given and smaller.  kept_idx must be ascending (as every selection entry
+ * point writes it); mask_out is a device array of total_tokens bytes, all of
+ * which are written.  capacity > total_tokens: UP_ERR_RANGE. */
+int uniprefill_keep_mask(const int32_t* kept_idx, int64_t capacity, const int32_t* total_kept_dev,
+                         int64_t total_tokens, uint8_t* mask_out, void* stream);
+
 /* KV length every layer sees during decode (vLLM scheduler integration, Eq. 17):
  * seqused_out[l][r] = s + (kv_len[r] - orig_len[r]) for l < num_layers, r < num_seqs,
  * where s is the length request r retained at the last drop event at a layer

@@ -24,7 +24,7 @@ EXPORTS = ["uniprefill_plan", "uniprefill_score", "uniprefill_select", "uniprefi
            "uniprefill_slot_mapping", "uniprefill_plan_chunked", "uniprefill_score_chunked",
            "uniprefill_select_chunked", "uniprefill_fused_chunked", "uniprefill_compact_column", "uniprefill_seqused",
            "uniprefill_score_paged", "uniprefill_fused_paged", "uniprefill_select_top_p_chunked",
-           "uniprefill_fused_top_p_chunked",
+           "uniprefill_fused_top_p_chunked", "uniprefill_keep_mask",
            "uniprefill_status_string"]
 
 UP_PHASE_PLAN, UP_PHASE_ROW_STATS, UP_PHASE_MERGE_STATS, UP_PHASE_SWEEP_SELECT, UP_PHASE_GATHER = 1, 2, 4, 8, 16
@@ -181,6 +181,12 @@ def uniprefill_compact_column(column, elem_bytes, kept_idx, capacity, total_kept
     st = _lib.uniprefill_compact_column(ptr(column), int(elem_bytes), ptr(kept_idx), ctypes.c_int64(capacity),
                                         ptr(total_kept_dev), ptr(column_out), _stream(stream))
     return _check(st, "uniprefill_compact_column", check)
+
+
+def uniprefill_keep_mask(kept_idx, capacity, total_kept_dev, total_tokens, mask_out, stream=None, check=True):
+    st = _lib.uniprefill_keep_mask(ptr(kept_idx), ctypes.c_int64(capacity), ptr(total_kept_dev),
+                                   ctypes.c_int64(total_tokens), ptr(mask_out), _stream(stream))
+    return _check(st, "uniprefill_keep_mask", check)
 
 
 def uniprefill_seqused(drop_layers_host, retained_dev, kv_len_dev, orig_len_dev, num_seqs, num_layers, seqused_out,

@@ -549,6 +549,16 @@ int uniprefill_compose_index(const int32_t* outer_idx, int64_t n_outer, const in
   return UP_OK;
 }
 
+int uniprefill_keep_mask(const int32_t* kept_idx, int64_t capacity, const int32_t* total_kept_dev,
+                         int64_t total_tokens, uint8_t* mask_out, void* stream) {
+  if (capacity < 0 || total_tokens < 0 || capacity > total_tokens) return UP_ERR_RANGE;
+  if (total_tokens == 0) return UP_OK;
+  if (!mask_out || (capacity > 0 && !kept_idx)) return UP_ERR_NULL;
+  if (launch_keep_mask(kept_idx, capacity, total_kept_dev, total_tokens, mask_out, (hipStream_t)stream) != hipSuccess)
+    return UP_ERR_HIP;
+  return UP_OK;
+}
+
 int uniprefill_seqused(const int32_t* drop_layers_host, int32_t num_drops, const int32_t* retained_dev,
                        const int32_t* kv_len_dev, const int32_t* orig_len_dev, int32_t num_seqs,
                        int32_t num_layers, int32_t* seqused_out, void* stream) {

@@ -114,6 +114,30 @@ hipError_t launch_column(const void* column, int elem_bytes, const int32_t* idx,
   return hipGetLastError();
 }
 
+// Token keep mask from the ascending list of kept rows: token t is kept iff the list holds t
+// (binary search; every token writes its own byte, so nothing has to be cleared first).
+__global__ __launch_bounds__(256) void k_keep_mask(const int32_t* __restrict__ kept_idx, long long capacity,
+                                                   const int32_t* __restrict__ count_dev, long long T,
+                                                   uint8_t* __restrict__ mask) {
+  const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (t >= T) return;
+  long long n = capacity;
+  if (count_dev != nullptr && (long long)count_dev[0] < n) n = count_dev[0];
+  long long lo = 0, hi = n;            // first position with kept_idx[pos] >= t
+  while (lo < hi) {
+    const long long mid = (lo + hi) >> 1;
+    if ((long long)kept_idx[mid] < t) lo = mid + 1; else hi = mid;
+  }
+  mask[t] = (lo < n && (long long)kept_idx[lo] == t) ? 1 : 0;
+}
+
+hipError_t launch_keep_mask(const int32_t* kept_idx, long long capacity, const int32_t* count_dev, long long T,
+                            uint8_t* mask, hipStream_t s) {
+  if (T == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_keep_mask, dim3((unsigned)((T + 255) / 256)), dim3(256), 0, s, kept_idx, capacity, count_dev, T, mask);
+  return hipGetLastError();
+}
+
 // KV length that layer l sees during decode (Eq. 17): the length request r kept at the last drop
 // event at a layer before l (the whole prompt if none), plus the tokens appended since prefill.
 __global__ __launch_bounds__(256) void k_seqused(DropLayers drops, const int32_t* __restrict__ retained,

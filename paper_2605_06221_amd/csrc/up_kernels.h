@@ -60,6 +60,10 @@ hipError_t launch_compose(const int32_t* outer, const int32_t* inner, long long 
 hipError_t launch_column(const void* column, int elem_bytes, const int32_t* idx, long long n,
                          const int32_t* count_dev, void* out, hipStream_t s);
 
+// token keep mask (one byte per token) from the ascending list of kept rows
+hipError_t launch_keep_mask(const int32_t* kept_idx, long long capacity, const int32_t* count_dev, long long T,
+                            uint8_t* mask, hipStream_t s);
+
 // per-layer KV length during decode (Eq. 17): out[l][r] for l < num_layers
 constexpr int kMaxDropLayers = 64;
 struct DropLayers { int n; int layer[kMaxDropLayers]; };

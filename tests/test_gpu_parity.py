@@ -1002,3 +1002,27 @@ def test_fused_top_p_with_earlier_context(paged):
                                        top_p, b["kept_idx"], b["new_cu"], workspace, ws_bytes)
     torch.cuda.synchronize()
     np.testing.assert_array_equal(b["kept_idx"][:total].cpu().numpy(), got_idx)
+
+
+def test_keep_mask_from_the_index_list():
+    _say("keep mask")
+    w = workloads.make_custom(name="mask", seed=25, lengths=[3000, 0, 40, 5000, 1], keep_ratio=[0.3, 0.5, 0.5, 0.6, 1.0],
+                              hidden_dim=64, num_q_heads=8, num_kv_heads=2, block_size=64, n_obs=128)
+    b = DeviceBatch(w)
+    b.fused()
+    res = b.results()
+    T, K = w.total_tokens, b.total_kept
+    mask = torch.full((T + 64,), 7, dtype=torch.uint8, device="cuda")
+    up.uniprefill_keep_mask(b.kept_idx, K, None, T, mask)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(mask[:T].cpu().numpy(), oracle.keep_mask(res["kept_idx"], T))
+    assert bool((mask[T:] == 7).all())
+    # the count on the device (as after a top-p selection), smaller than the capacity
+    mask.fill_(7)
+    up.uniprefill_keep_mask(b.kept_idx, K, torch.tensor([100], dtype=torch.int32, device="cuda"), T, mask)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(mask[:T].cpu().numpy(), oracle.keep_mask(res["kept_idx"][:100], T))
+    # an empty list: every byte is written with zero
+    up.uniprefill_keep_mask(b.kept_idx, 0, None, T, mask)
+    torch.cuda.synchronize()
+    assert int(mask[:T].sum()) == 0

@@ -309,3 +309,14 @@ def test_paged_entries_reject_bad_block_tables():
     assert score(fake, -1, 16) == up.UP_ERR_RANGE
     # the table is long enough with 63 entries: the next complaint is the workspace's alignment
     assert score(fake, 63, 16) == up.UP_ERR_ALIGN
+
+
+def test_keep_mask_rejects_bad_arguments():
+    L = up.lib()
+    fake = ctypes.c_void_p(0x1000)
+    call = lambda idx, cap, T, out: L.uniprefill_keep_mask(idx, ctypes.c_int64(cap), None, ctypes.c_int64(T), out, None)
+    assert call(fake, 5, 0, fake) == up.UP_ERR_RANGE        # more kept rows than tokens
+    assert call(fake, -1, 10, fake) == up.UP_ERR_RANGE
+    assert call(fake, 0, 0, fake) == up.UP_OK               # nothing to do, nothing launched
+    assert call(fake, 5, 10, None) == up.UP_ERR_NULL
+    assert call(None, 5, 10, fake) == up.UP_ERR_NULL
