@@ -196,11 +196,8 @@ long long host_total_kept(const Problem& pb, const int32_t* cu, const int32_t* c
   return total;
 }
 
-}  // namespace
-
 // ---- the entry points that exist with and without earlier context share these bodies
 // (cu_k_dev / cu_k_host are nullptr for sequences whose keys are their own tokens' keys)
-namespace {
 
 int plan_impl(const up_params* p, const int32_t* cu_host, const int32_t* cu_k_host, bool ctx,
               const float* ratio_host, int32_t* new_cu_host, int64_t* total_kept, size_t* workspace_bytes) {
