@@ -435,6 +435,45 @@ def importance_scores_with_context(q, k, cu_seqlens_q, cu_seqlens_k, *, n_obs, s
     return o
 
 
+def importance_scores_from_lse(q, k, lse, cu_seqlens_q, cu_seqlens_k, *, n_obs, scale=None):
+    """The same scores when the softmax normaliser of every row is handed in instead of computed:
+    ``lse[h, t]`` is the natural logarithm of the sum of exp(scale * <q_t, k_i>) over the keys that
+    token t of head h sees (what an attention kernel returns next to its output).  The weight of
+    key i for window row j is then exp(scale * <q_j, k_i> - lse[h, j]) (Eq. 2), and the score is
+    the mean over rows and heads (Eq. 3).  ``cu_seqlens_k`` as in importance_scores_with_context
+    (pass cu_seqlens_q when there is no earlier context); only the window rows of lse are read."""
+    k = np.asarray(k)
+    lse = np.asarray(lse, dtype=np.float64)
+    cq = np.asarray(cu_seqlens_q, dtype=np.int64)
+    ck = np.asarray(cu_seqlens_k, dtype=np.int64)
+    T, Hq, D = q.shape
+    Hkv = k.shape[1]
+    group = Hq // Hkv
+    if scale is None:
+        scale = 1.0 / math.sqrt(D)
+    o = np.zeros(T, dtype=np.float64)
+    for r in range(len(cq) - 1):
+        c0, c1 = int(cq[r]), int(cq[r + 1])
+        k0, k1 = int(ck[r]), int(ck[r + 1])
+        N, L = c1 - c0, k1 - k0
+        P = L - N
+        if N == 0:
+            continue
+        n_eff = min(int(n_obs), N)
+        Kr = k[k0:k1].astype(np.float64)
+        Qw = np.asarray(q[c1 - n_eff:c1], dtype=np.float64)
+        qpos = np.arange(L - n_eff, L)
+        visible = np.arange(L)[None, :] <= qpos[:, None]
+        colsum = np.zeros(L, dtype=np.float64)
+        for h in range(Hq):
+            S = scale * (Qw[:, h, :] @ Kr[:, h // group, :].T)
+            W = np.exp(S - lse[h, c1 - n_eff:c1][:, None])
+            W[~visible] = 0.0
+            colsum += W.sum(axis=0)
+        o[c0:c1] = colsum[P:] / (n_eff * Hq)
+    return o
+
+
 def gather_paged_keys(k_cache, cu_seqlens_k, block_table, kv_block_size):
     """Keys of every request read out of a paged KV cache into the packed layout that
     ``importance_scores_with_context`` takes: key i of request r is row

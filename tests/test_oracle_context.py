@@ -173,3 +173,49 @@ def test_top_p_with_context_differs_from_the_plain_rule_only_in_the_sinks():
         want = set(int(x) + int(cq[r]) for x in plain) | set(int(cq[r]) + i for i in range(min(A, N)))
         assert {t for t in kept if cq[r] <= t < cq[r + 1]} == want
         assert new_cu[r + 1] - new_cu[r] == len(want)
+
+
+def _lse_of_window_rows(q, k, cq, ck, n_obs, scale=None):
+    """Normalisers of the window rows from a library routine (scipy's logsumexp); other rows NaN."""
+    from scipy.special import logsumexp
+    T, Hq, D = q.shape
+    group = Hq // k.shape[1]
+    scale = 1.0 / math.sqrt(D) if scale is None else scale
+    lse = np.full((Hq, T), np.nan)
+    for r in range(len(cq) - 1):
+        N, L = cq[r + 1] - cq[r], ck[r + 1] - ck[r]
+        for j in range(N - min(n_obs, N), N):
+            vis = L - N + j + 1                                    # keys 0 .. P + j
+            for h in range(Hq):
+                logits = scale * (k[ck[r]:ck[r] + vis, h // group, :] @ q[cq[r] + j, h, :])
+                lse[h, cq[r] + j] = logsumexp(logits)
+    return lse
+
+
+def test_scores_from_exact_normalisers_are_the_two_pass_scores():
+    rng = np.random.default_rng(12)
+    Ps, Ns = [0, 40, 300, 5], [64, 1, 200, 77]
+    q, k, cq, ck = _batch(rng, Ps, Ns)
+    lse = _lse_of_window_rows(q, k, cq, ck, 32)
+    got = oracle.importance_scores_from_lse(q, k, lse, cq, ck, n_obs=32)
+    want = oracle.importance_scores_with_context(q, k, cq, ck, n_obs=32)
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=0)
+    # without earlier tokens: the plain scores
+    q2, k2, cq2, _ = _batch(rng, [0, 0], [100, 9])
+    lse2 = _lse_of_window_rows(q2, k2, cq2, cq2, 16)
+    np.testing.assert_allclose(oracle.importance_scores_from_lse(q2, k2, lse2, cq2, cq2, n_obs=16),
+                               oracle.importance_scores(q2, k2, cq2, n_obs=16), rtol=1e-12, atol=0)
+
+
+def test_scores_from_normalisers_hand_case_and_scaling():
+    """One head, D = 1, scale 1, q = 1, keys ln1, ln2, ln3, window of two rows: the normalisers are
+    ln 3 and ln 6, the weights [1/3, 2/3, 0] and [1/6, 2/6, 3/6], the scores [1/4, 1/2, 1/4].
+    A normaliser that is too large by ln 2 halves that row's weights."""
+    q = np.ones((3, 1, 1))
+    k = np.log(np.array([1.0, 2.0, 3.0])).reshape(3, 1, 1)
+    lse = np.array([[np.nan, math.log(3.0), math.log(6.0)]])
+    got = oracle.importance_scores_from_lse(q, k, lse, [0, 3], [0, 3], n_obs=2, scale=1.0)
+    np.testing.assert_allclose(got, [1 / 4, 1 / 2, 1 / 4], rtol=1e-14)
+    lse[0, 2] += math.log(2.0)
+    got = oracle.importance_scores_from_lse(q, k, lse, [0, 3], [0, 3], n_obs=2, scale=1.0)
+    np.testing.assert_allclose(got, [(1 / 3 + 1 / 12) / 2, (2 / 3 + 2 / 12) / 2, (3 / 12) / 2], rtol=1e-14)
