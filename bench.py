@@ -250,6 +250,32 @@ def main():
         except up.UniPrefillError as e:      # e.g. more blocks per sequence than the top-p kernel orders
             top_p_kept = None
             print(f"[bench] top-p selection skipped: {e}", file=sys.stderr, flush=True)
+        # the fused call when the attention layer hands over its rows' log-sum-exp: no first pass.
+        # The normalisers come from a plain torch product here (an input of the call, not part of it).
+        same_kept = None
+        try:
+            lse = torch.full((w.num_q_heads, w.total_tokens), float("nan"), dtype=torch.float32, device="cuda")
+            group = w.num_q_heads // w.num_kv_heads
+            sc_l = 1.0 / float(np.sqrt(w.head_dim))
+            for r in range(w.num_seqs):
+                c0, c1 = int(cu_host[r]), int(cu_host[r + 1])
+                n_eff = min(w.n_obs, c1 - c0)
+                if n_eff == 0:
+                    continue
+                rows = torch.arange(c1 - c0 - n_eff, c1 - c0, device="cuda")[:, None]
+                cols = torch.arange(c1 - c0, device="cuda")[None, :]
+                for h in range(w.num_q_heads):
+                    logits = (q[c1 - n_eff:c1, h, :].double() @ k[c0:c1, h // group, :].double().T) * sc_l
+                    logits.masked_fill_(cols > rows, float("-inf"))
+                    lse[h, c1 - n_eff:c1] = torch.logsumexp(logits, dim=1).float()
+            idx_lse = torch.empty_like(kept_idx)
+            t_us["fused_from_lse"] = timed(lambda: up.uniprefill_fused_lse(
+                p, q, k, lse, w.total_tokens, hidden, pos, cu, cu_host, None, None, None, 0, 16, ratio, ratio_host,
+                hidden_out, pos_out, idx_lse, new_cu, None, workspace, ws_bytes, stream=stream))
+            same_kept = bool(torch.equal(idx_lse, kept_idx))
+            del lse, idx_lse
+        except Exception as e:                # (e.g. out of memory for the logits of a very long batch)
+            print(f"[bench] fused_from_lse skipped: {e}", file=sys.stderr, flush=True)
         for name, us in t_us.items():
             ent = {"avg_us": round(us, 2)}
             if name in ("compact", "scatter", "device_copy_same_bytes"):
@@ -258,6 +284,8 @@ def main():
             entry_points[name] = ent
         if top_p_kept is not None:
             entry_points["select_top_p"]["kept_at_p0.99"] = top_p_kept
+        if same_kept is not None:
+            entry_points["fused_from_lse"]["same_kept_set_as_fused"] = same_kept
         del full, src, dst
 
     if args.calibrate_copy:

@@ -352,6 +352,31 @@ int uniprefill_fused_paged(const up_params* p, const void* q, const void* k_cach
                            int32_t* kept_idx, int32_t* new_cu_seqlens_dev, float* scores_out,
                            void* workspace, size_t workspace_bytes, void* stream);
 
+/* The fused call when the attention layer's own kernel has already normalised
+ * the rows: lse[h * lse_row_stride + t] (device, float) is the natural logarithm
+ * of the sum of exp(scale * <q_t, k_i>) over the keys token t sees in query head h
+ * -- the log-sum-exp that attention kernels return next to their output, laid out
+ * [num_q_heads, total_tokens] with lse_row_stride >= total_tokens elements between
+ * heads (UP_ERR_SHAPE otherwise).  Only the entries of the window rows are read.
+ * The first of the two passes over Q.K^T (Eq. 2's normaliser) and the merge are
+ * then not needed: a small conversion kernel (which also does the plan), the
+ * second pass with the selection, and the gather.  The weights are
+ * exp(scale * <q_j, k_i> - lse) evaluated to float rounding, so with the exact
+ * normalisers the results are those of uniprefill_fused.
+ * Keys: cu_seqlens_k_dev/_host both NULL (the tokens' own keys), or both given
+ * (earlier context, as for uniprefill_fused_chunked) and then optionally a block
+ * table (paged cache, as for uniprefill_fused_paged; block_table NULL = packed).
+ * Workspace from uniprefill_plan, or uniprefill_plan_chunked when cu_seqlens_k is
+ * given. */
+int uniprefill_fused_lse(const up_params* p, const void* q, const void* k, const float* lse,
+                         int64_t lse_row_stride, const void* hidden, const int32_t* pos,
+                         const int32_t* cu_seqlens_dev, const int32_t* cu_seqlens_host,
+                         const int32_t* cu_seqlens_k_dev, const int32_t* cu_seqlens_k_host,
+                         const int32_t* block_table, int64_t block_table_stride, int32_t kv_block_size,
+                         const float* keep_ratio_dev, const float* keep_ratio_host, void* hidden_out,
+                         int32_t* pos_out, int32_t* kept_idx, int32_t* new_cu_seqlens_dev,
+                         float* scores_out, void* workspace, size_t workspace_bytes, void* stream);
+
 /* The paper's block-level top-p rule (uniprefill_select_top_p, uniprefill_fused_top_p) for
  * tokens that follow earlier context: the sinks are those that fall inside the
  * tokens (position P_r + i below n_sink), and the threshold is p times the mass

@@ -24,7 +24,7 @@ EXPORTS = ["uniprefill_plan", "uniprefill_score", "uniprefill_select", "uniprefi
            "uniprefill_slot_mapping", "uniprefill_plan_chunked", "uniprefill_score_chunked",
            "uniprefill_select_chunked", "uniprefill_fused_chunked", "uniprefill_compact_column", "uniprefill_seqused",
            "uniprefill_score_paged", "uniprefill_fused_paged", "uniprefill_select_top_p_chunked",
-           "uniprefill_fused_top_p_chunked", "uniprefill_keep_mask",
+           "uniprefill_fused_top_p_chunked", "uniprefill_keep_mask", "uniprefill_fused_lse",
            "uniprefill_status_string"]
 
 UP_PHASE_PLAN, UP_PHASE_ROW_STATS, UP_PHASE_MERGE_STATS, UP_PHASE_SWEEP_SELECT, UP_PHASE_GATHER = 1, 2, 4, 8, 16
@@ -181,6 +181,19 @@ def uniprefill_compact_column(column, elem_bytes, kept_idx, capacity, total_kept
     st = _lib.uniprefill_compact_column(ptr(column), int(elem_bytes), ptr(kept_idx), ctypes.c_int64(capacity),
                                         ptr(total_kept_dev), ptr(column_out), _stream(stream))
     return _check(st, "uniprefill_compact_column", check)
+
+
+def uniprefill_fused_lse(p, q, k, lse, lse_row_stride, hidden, pos, cu_seqlens_dev, cu_seqlens_host, cu_seqlens_k_dev,
+                         cu_seqlens_k_host, block_table, block_table_stride, kv_block_size, keep_ratio_dev,
+                         keep_ratio_host, hidden_out, pos_out, kept_idx, new_cu_seqlens_dev, scores_out, workspace,
+                         workspace_bytes, stream=None, check=True):
+    st = _lib.uniprefill_fused_lse(ctypes.byref(p), ptr(q), ptr(k), ptr(lse), ctypes.c_int64(lse_row_stride), ptr(hidden),
+                                   ptr(pos), ptr(cu_seqlens_dev), ptr(cu_seqlens_host), ptr(cu_seqlens_k_dev),
+                                   ptr(cu_seqlens_k_host), ptr(block_table), ctypes.c_int64(block_table_stride),
+                                   int(kv_block_size), ptr(keep_ratio_dev), ptr(keep_ratio_host), ptr(hidden_out),
+                                   ptr(pos_out), ptr(kept_idx), ptr(new_cu_seqlens_dev), ptr(scores_out),
+                                   ptr(workspace), workspace_bytes, _stream(stream))
+    return _check(st, "uniprefill_fused_lse", check)
 
 
 def uniprefill_keep_mask(kept_idx, capacity, total_kept_dev, total_tokens, mask_out, stream=None, check=True):

@@ -286,7 +286,7 @@ int fused_impl(const up_params* p, const void* q, const void* k, const void* hid
                const int32_t* cu_dev, const int32_t* cu_host, const KeySide& ks, const float* ratio_dev,
                const float* ratio_host, void* hidden_out, int32_t* pos_out, int32_t* kept_idx,
                int32_t* new_cu_dev, float* scores_out, void* workspace, size_t workspace_bytes,
-               int phase_mask, void* stream) {
+               int phase_mask, void* stream, const float* lse = nullptr, long long lse_stride = 0) {
   const int32_t* cu_k_dev = ks.cu_k_dev;
   const int32_t* cu_k_host = ks.cu_k_host;
   Problem pb;
@@ -298,6 +298,7 @@ int fused_impl(const up_params* p, const void* q, const void* k, const void* hid
   if ((st = check_cu(p, cu_host)) != UP_OK) return st;
   if ((st = check_key_side(p, cu_host, ks)) != UP_OK) return st;
   if ((st = check_ratio(p, ratio_host)) != UP_OK) return st;
+  if (lse != nullptr && lse_stride < pb.T) return UP_ERR_SHAPE;      // the heads of lse would overlap
   if (!aligned16(q) || !aligned16(k) || !aligned16(hidden) || !aligned16(hidden_out))
     return UP_ERR_ALIGN;
   choose_geometry(&pb, cu_host, cu_k_host);
@@ -306,6 +307,12 @@ int fused_impl(const up_params* p, const void* q, const void* k, const void* hid
   if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return UP_ERR_ALIGN;
   if (phase_mask & ~UP_PHASE_ALL) return UP_ERR_RANGE;
   hipStream_t s = (hipStream_t)stream;
+  if (lse != nullptr) {
+    // the rows' normalisers are given: no pass 1, no merge; the plan rides in the conversion
+    if (launch_lse_stats(pb, cu_dev, cu_k_dev, lse, lse_stride, workspace, ratio_dev, new_cu_dev, s) != hipSuccess)
+      return UP_ERR_HIP;
+    phase_mask &= ~(UP_PHASE_PLAN | UP_PHASE_ROW_STATS | UP_PHASE_MERGE_STATS);
+  }
   // the plan rides in the merge kernel when both are asked for (one launch less)
   const bool plan_in_merge = (phase_mask & UP_PHASE_PLAN) && (phase_mask & UP_PHASE_MERGE_STATS);
   if ((phase_mask & UP_PHASE_PLAN) && !plan_in_merge &&
@@ -626,6 +633,26 @@ int uniprefill_fused_chunked(const up_params* p, const void* q, const void* k, c
   return fused_impl(p, q, k, hidden, pos, cu_seqlens_dev, cu_seqlens_host, ks, keep_ratio_dev, keep_ratio_host,
                     hidden_out, pos_out, kept_idx, new_cu_seqlens_dev, scores_out, workspace, workspace_bytes,
                     UP_PHASE_ALL, stream);
+}
+
+int uniprefill_fused_lse(const up_params* p, const void* q, const void* k, const float* lse,
+                         int64_t lse_row_stride, const void* hidden, const int32_t* pos,
+                         const int32_t* cu_seqlens_dev, const int32_t* cu_seqlens_host,
+                         const int32_t* cu_seqlens_k_dev, const int32_t* cu_seqlens_k_host,
+                         const int32_t* block_table, int64_t block_table_stride, int32_t kv_block_size,
+                         const float* keep_ratio_dev, const float* keep_ratio_host, void* hidden_out,
+                         int32_t* pos_out, int32_t* kept_idx, int32_t* new_cu_seqlens_dev,
+                         float* scores_out, void* workspace, size_t workspace_bytes, void* stream) {
+  if (lse == nullptr) return UP_ERR_NULL;
+  if ((reinterpret_cast<uintptr_t>(lse) & 3u) != 0) return UP_ERR_ALIGN;
+  if ((cu_seqlens_k_dev == nullptr) != (cu_seqlens_k_host == nullptr)) return UP_ERR_NULL;
+  const bool ctx = cu_seqlens_k_host != nullptr;
+  if (!ctx && block_table != nullptr) return UP_ERR_NULL;      // a block table needs the key counts
+  const PagedKeys paged{block_table, block_table_stride, kv_block_size};
+  const KeySide ks{cu_seqlens_k_dev, cu_seqlens_k_host, ctx, block_table != nullptr ? &paged : nullptr};
+  return fused_impl(p, q, k, hidden, pos, cu_seqlens_dev, cu_seqlens_host, ks, keep_ratio_dev, keep_ratio_host,
+                    hidden_out, pos_out, kept_idx, new_cu_seqlens_dev, scores_out, workspace, workspace_bytes,
+                    UP_PHASE_ALL, stream, lse, lse_row_stride);
 }
 
 int uniprefill_fused_paged(const up_params* p, const void* q, const void* k_cache, const void* hidden,

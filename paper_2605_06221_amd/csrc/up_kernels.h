@@ -126,6 +126,11 @@ hipError_t launch_row_stats(const Problem& pb, const void* q, const void* k, con
 // the same launch also does what launch_plan does (into plan_new_cu)
 hipError_t launch_merge_stats(const Problem& pb, const int32_t* cu, const int32_t* cu_k, void* workspace,
                               const float* plan_ratio, int32_t* plan_new_cu, hipStream_t s);
+// instead of the two launches above: the rows' normalisers are given (lse[h * lse_stride + t] =
+// natural log of the sum of exponentials of token t's row in head h)
+hipError_t launch_lse_stats(const Problem& pb, const int32_t* cu, const int32_t* cu_k, const float* lse,
+                            long long lse_stride, void* workspace, const float* plan_ratio, int32_t* plan_new_cu,
+                            hipStream_t s);
 // pass 2: normalised weights summed per token; optional scores_out; sel != nullptr runs the
 // block-local top-k (in the same kernel when every key block has one work-group, otherwise in
 // k_finish)

@@ -625,6 +625,46 @@ __global__ __launch_bounds__(32 * LPR) void k_combine(const int32_t* __restrict_
   }
 }
 
+// Row normalisers handed in (the natural log of the row's sum of exponentials, as an attention
+// kernel returns it) instead of pass 1 and the merge: the pair pass 2 reads is (-hi, 2^(hi - L))
+// with L = lse * log2(e) in double and hi = L rounded to float, so that the weight
+// 2^(x - hi) * 2^(hi - L) is exact to float rounding.  One thread per (window row, head); the
+// first work-group also does the plan when asked, as in k_combine.
+__global__ __launch_bounds__(256) void k_lse_stats(const int32_t* __restrict__ cu, const float* __restrict__ lse,
+                                                   long long lse_stride, float2* __restrict__ stat_fin, int R,
+                                                   int Hq, int n_obs, int row_slots, PlanInCombine plan) {
+  if (plan.ratio != nullptr && blockIdx.x == 0 && blockIdx.y == 0) {
+    __shared__ int wave_tot[16];
+    __shared__ int carry;
+    plan_scan<256>(cu, plan.cu_k_sel, plan.ratio, R, plan.G, n_obs, plan.n_sink, plan.new_cu, wave_tot, &carry);
+  }
+  const int u = blockIdx.x * 256 + threadIdx.x;
+  const int h = blockIdx.y;
+  if (u >= row_slots) return;
+  const int r = locate_rowslot(cu, R, n_obs, u);
+  const int c0 = cu[r];
+  const int N = cu[r + 1] - c0;
+  const int n_eff = imin(n_obs, N);
+  const int jj = u - rowslot_base(c0, r, n_obs);
+  if (jj >= n_eff) return;
+  const double L = (double)lse[(long long)h * lse_stride + c0 + (N - n_eff) + jj] * 1.4426950408889634074;
+  const float hi = (float)L;
+  stat_fin[(size_t)h * row_slots + u] = make_float2(-hi, (float)exp2((double)hi - L));
+}
+
+hipError_t launch_lse_stats(const Problem& pb, const int32_t* cu, const int32_t* cu_k, const float* lse,
+                            long long lse_stride, void* workspace, const float* plan_ratio, int32_t* plan_new_cu,
+                            hipStream_t s) {
+  if (pb.T == 0)
+    return plan_ratio != nullptr ? launch_plan(pb, cu, cu_k, plan_ratio, plan_new_cu, s) : hipSuccess;
+  const Workspace w = workspace_layout(pb);
+  const PlanInCombine plan{plan_ratio, plan_new_cu, cu_k, pb.G, pb.n_sink};
+  hipLaunchKernelGGL(k_lse_stats, dim3((unsigned)((pb.row_slots + 255) / 256), (unsigned)pb.Hq), dim3(256), 0, s, cu,
+                     lse, lse_stride, (float2*)((char*)workspace + w.stat_fin_off), pb.R, pb.Hq, pb.n_obs,
+                     pb.row_slots, plan);
+  return hipGetLastError();
+}
+
 Workspace workspace_layout(const Problem& pb) {
   auto al = [](size_t x) { return (x + 255) & ~(size_t)255; };
   Workspace w;

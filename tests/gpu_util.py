@@ -85,6 +85,15 @@ class DeviceBatch:
                                    self.new_cu, self.scores if want_scores else None, self.workspace,
                                    self.ws_bytes, stream=stream)
 
+    def fused_lse(self, lse_dev, want_scores=True):
+        """The fused call with the rows' normalisers given (lse_dev: float [Hq, T] on the device)."""
+        table, stride, B = self.paged if self.paged is not None else (None, 0, 16)
+        return up.uniprefill_fused_lse(self.p, self.q, self.k, lse_dev, int(lse_dev.shape[1]), self.hidden, self.pos,
+                                       self.cu, self.cu_host, self.cu_k if self.ctx else None,
+                                       self.cu_k_host if self.ctx else None, table, stride, B, self.ratio,
+                                       self.ratio_host, self.hidden_out, self.pos_out, self.kept_idx, self.new_cu,
+                                       self.scores if want_scores else None, self.workspace, self.ws_bytes)
+
     def score(self):
         if self.paged is not None:
             return up.uniprefill_score_paged(self.p, self.q, self.k, self.cu, self.cu_host, self.cu_k, self.cu_k_host,

@@ -1026,3 +1026,74 @@ def test_keep_mask_from_the_index_list():
     up.uniprefill_keep_mask(b.kept_idx, 0, None, T, mask)
     torch.cuda.synchronize()
     assert int(mask[:T].sum()) == 0
+
+
+# ---- the rows' normalisers handed in (the log-sum-exp an attention kernel returns)
+
+def _window_lse_f32(w):
+    """float32 [Hq, T]: log-sum-exp of every window row's visible logits (fp64, scipy), rounded to
+    float; entries of other rows are NaN (never read).  An input of the entry under test."""
+    from scipy.special import logsumexp
+    q = _q_f32(w)
+    k = workloads.bf16_bits_to_f32(w.k).astype(np.float64)
+    cq = w.cu_seqlens
+    ck = w.cu_seqlens_k if w.cu_seqlens_k is not None else w.cu_seqlens
+    Hq, group = w.num_q_heads, w.num_q_heads // w.num_kv_heads
+    scale = 1.0 / np.sqrt(w.head_dim)
+    lse = np.full((Hq, w.total_tokens), np.nan, dtype=np.float32)
+    for r in range(w.num_seqs):
+        N, L = int(cq[r + 1] - cq[r]), int(ck[r + 1] - ck[r])
+        n_eff = min(w.n_obs, N)
+        if n_eff == 0:
+            continue
+        Qw = q[int(cq[r + 1]) - n_eff:int(cq[r + 1])].astype(np.float64)
+        for h in range(Hq):
+            S = scale * (Qw[:, h, :] @ k[int(ck[r]):int(ck[r + 1]), h // group, :].T)
+            for j in range(n_eff):
+                lse[h, int(cq[r + 1]) - n_eff + j] = logsumexp(S[j, :L - n_eff + j + 1])
+    return lse
+
+
+@pytest.mark.parametrize("case", [
+    dict(lengths=[3000, 40, 777, 9000], earlier=None),
+    dict(lengths=[3000, 40, 0, 777, 5000], earlier=[1000, 0, 50, 64, 12345]),
+    dict(lengths=[3000, 40, 0, 777, 5000], earlier=[1000, 0, 50, 64, 12345], paged=16),
+    dict(lengths=[40000], earlier=None),
+])
+def test_fused_with_given_normalisers_bit_exact(case):
+    _say("fused from lse", case)
+    R = len(case["lengths"])
+    w = workloads.make_custom(name="lse", seed=26, lengths=case["lengths"], keep_ratio=[0.3, 0.5, 0.7, 0.25, 0.4][:R],
+                              hidden_dim=64, num_q_heads=8, num_kv_heads=2, block_size=64, n_obs=128,
+                              earlier=case["earlier"])
+    lse = _window_lse_f32(w)
+    paged = None
+    if case.get("paged"):
+        cache, table = workloads.make_paged_cache(w.k, w.cu_seqlens_k, case["paged"], seed=7)
+        paged = (cache, table, case["paged"])
+    b = DeviceBatch(w, paged=paged)
+    b.fused_lse(torch.from_numpy(lse).cuda())
+    res = b.results()
+    # the oracle reads the same float32 normalisers
+    ck = w.cu_seqlens_k if w.cu_seqlens_k is not None else w.cu_seqlens
+    o = oracle.importance_scores_from_lse(_q_f32(w), workloads.bf16_bits_to_f32(w.k), lse, w.cu_seqlens, ck, n_obs=w.n_obs)
+    s32 = oracle.quantise_scores(o)
+    ok, worst = _score_close(res["scores"], s32)
+    _say("  worst relative score error", worst)
+    assert ok
+    if w.cu_seqlens_k is not None:
+        kept, new_cu = oracle.select_tokens_with_context(s32, w.cu_seqlens, w.cu_seqlens_k, w.keep_ratio, block_size=w.block_size,
+                                                         n_obs=w.n_obs, n_sink=w.n_sink)
+    else:
+        kept, new_cu = oracle.select_tokens(s32, w.cu_seqlens, w.keep_ratio, block_size=w.block_size, n_obs=w.n_obs,
+                                            n_sink=w.n_sink)
+    np.testing.assert_array_equal(res["new_cu_seqlens"], new_cu)
+    np.testing.assert_array_equal(res["kept_idx"], kept)
+    h_out, p_out = oracle.compact(w.hidden, w.pos, kept)
+    np.testing.assert_array_equal(res["hidden_out"], h_out)
+    np.testing.assert_array_equal(res["pos_out"], p_out)
+    assert b.canaries_intact()
+    # and the two-pass call on the same batch keeps the same tokens (the normalisers were exact to float rounding)
+    two = DeviceBatch(w, paged=paged)
+    two.fused()
+    np.testing.assert_array_equal(two.results()["kept_idx"], res["kept_idx"])

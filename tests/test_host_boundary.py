@@ -320,3 +320,25 @@ def test_keep_mask_rejects_bad_arguments():
     assert call(fake, 0, 0, fake) == up.UP_OK               # nothing to do, nothing launched
     assert call(fake, 5, 10, None) == up.UP_ERR_NULL
     assert call(None, 5, 10, fake) == up.UP_ERR_NULL
+
+
+def test_fused_lse_rejects_bad_arguments():
+    L = up.lib()
+    fake = ctypes.c_void_p(0x1000)
+    odd = ctypes.c_void_p(0x1010)
+    cu = np.array([0, 100, 300], np.int32)
+    cu_k = np.array([0, 1000, 1200], np.int32)
+    ratio = np.array([0.5, 0.5], np.float32)
+    p = _params(num_seqs=2, total_tokens=300)
+    def call(lse=fake, stride=300, ckd=None, ckh=None, table=None, ws=odd):
+        return L.uniprefill_fused_lse(ctypes.byref(p), fake, fake, lse, ctypes.c_int64(stride), fake, None, fake, up.ptr(cu),
+                                      ckd, ckh, table, ctypes.c_int64(64), 16, fake, up.ptr(ratio), fake, None, fake, fake,
+                                      None, ws, ctypes.c_size_t(1 << 30), None)
+    assert call(lse=None) == up.UP_ERR_NULL
+    assert call(lse=ctypes.c_void_p(0x1002)) == up.UP_ERR_ALIGN
+    assert call(ckd=fake) == up.UP_ERR_NULL                       # device offsets without the host copy
+    assert call(table=fake) == up.UP_ERR_NULL                     # a block table without key counts
+    assert call(stride=299) == up.UP_ERR_SHAPE                    # heads of lse overlap
+    assert call(ckd=fake, ckh=up.ptr(np.array([0, 99, 400], np.int32))) == up.UP_ERR_SHAPE
+    assert call(ckd=fake, ckh=up.ptr(cu_k), table=fake) == up.UP_ERR_ALIGN    # all fine up to the odd workspace
+    assert call() == up.UP_ERR_ALIGN
