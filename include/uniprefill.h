@@ -377,6 +377,25 @@ int uniprefill_fused_lse(const up_params* p, const void* q, const void* k, const
                          int32_t* pos_out, int32_t* kept_idx, int32_t* new_cu_seqlens_dev,
                          float* scores_out, void* workspace, size_t workspace_bytes, void* stream);
 
+/* The same source of normalisers for the scores alone, and for the paper's top-p
+ * rule end to end (uniprefill_score / uniprefill_fused_top_p with lse and the
+ * optional key-side arguments of uniprefill_fused_lse). */
+int uniprefill_score_lse(const up_params* p, const void* q, const void* k, const float* lse,
+                         int64_t lse_row_stride, const int32_t* cu_seqlens_dev,
+                         const int32_t* cu_seqlens_host, const int32_t* cu_seqlens_k_dev,
+                         const int32_t* cu_seqlens_k_host, const int32_t* block_table,
+                         int64_t block_table_stride, int32_t kv_block_size, float* scores_out,
+                         void* workspace, size_t workspace_bytes, void* stream);
+int uniprefill_fused_top_p_lse(const up_params* p, const void* q, const void* k, const float* lse,
+                               int64_t lse_row_stride, const void* hidden, const int32_t* pos,
+                               const int32_t* cu_seqlens_dev, const int32_t* cu_seqlens_host,
+                               const int32_t* cu_seqlens_k_dev, const int32_t* cu_seqlens_k_host,
+                               const int32_t* block_table, int64_t block_table_stride,
+                               int32_t kv_block_size, const float* top_p_dev, const float* top_p_host,
+                               void* hidden_out, int32_t* pos_out, int32_t* kept_idx,
+                               int32_t* new_cu_seqlens_dev, float* scores, void* workspace,
+                               size_t workspace_bytes, void* stream);
+
 /* The paper's block-level top-p rule (uniprefill_select_top_p, uniprefill_fused_top_p) for
  * tokens that follow earlier context: the sinks are those that fall inside the
  * tokens (position P_r + i below n_sink), and the threshold is p times the mass

@@ -25,6 +25,7 @@ EXPORTS = ["uniprefill_plan", "uniprefill_score", "uniprefill_select", "uniprefi
            "uniprefill_select_chunked", "uniprefill_fused_chunked", "uniprefill_compact_column", "uniprefill_seqused",
            "uniprefill_score_paged", "uniprefill_fused_paged", "uniprefill_select_top_p_chunked",
            "uniprefill_fused_top_p_chunked", "uniprefill_keep_mask", "uniprefill_fused_lse",
+           "uniprefill_score_lse", "uniprefill_fused_top_p_lse",
            "uniprefill_status_string"]
 
 UP_PHASE_PLAN, UP_PHASE_ROW_STATS, UP_PHASE_MERGE_STATS, UP_PHASE_SWEEP_SELECT, UP_PHASE_GATHER = 1, 2, 4, 8, 16
@@ -194,6 +195,31 @@ def uniprefill_fused_lse(p, q, k, lse, lse_row_stride, hidden, pos, cu_seqlens_d
                                    ptr(pos_out), ptr(kept_idx), ptr(new_cu_seqlens_dev), ptr(scores_out),
                                    ptr(workspace), workspace_bytes, _stream(stream))
     return _check(st, "uniprefill_fused_lse", check)
+
+
+def uniprefill_score_lse(p, q, k, lse, lse_row_stride, cu_seqlens_dev, cu_seqlens_host, cu_seqlens_k_dev,
+                         cu_seqlens_k_host, block_table, block_table_stride, kv_block_size, scores_out, workspace,
+                         workspace_bytes, stream=None, check=True):
+    st = _lib.uniprefill_score_lse(ctypes.byref(p), ptr(q), ptr(k), ptr(lse), ctypes.c_int64(lse_row_stride),
+                                   ptr(cu_seqlens_dev), ptr(cu_seqlens_host), ptr(cu_seqlens_k_dev),
+                                   ptr(cu_seqlens_k_host), ptr(block_table), ctypes.c_int64(block_table_stride),
+                                   int(kv_block_size), ptr(scores_out), ptr(workspace), workspace_bytes,
+                                   _stream(stream))
+    return _check(st, "uniprefill_score_lse", check)
+
+
+def uniprefill_fused_top_p_lse(p, q, k, lse, lse_row_stride, hidden, pos, cu_seqlens_dev, cu_seqlens_host,
+                               cu_seqlens_k_dev, cu_seqlens_k_host, block_table, block_table_stride, kv_block_size,
+                               top_p_dev, top_p_host, hidden_out, pos_out, kept_idx, new_cu_seqlens_dev, scores,
+                               workspace, workspace_bytes, stream=None, check=True):
+    st = _lib.uniprefill_fused_top_p_lse(ctypes.byref(p), ptr(q), ptr(k), ptr(lse), ctypes.c_int64(lse_row_stride),
+                                         ptr(hidden), ptr(pos), ptr(cu_seqlens_dev), ptr(cu_seqlens_host),
+                                         ptr(cu_seqlens_k_dev), ptr(cu_seqlens_k_host), ptr(block_table),
+                                         ctypes.c_int64(block_table_stride), int(kv_block_size), ptr(top_p_dev),
+                                         ptr(top_p_host), ptr(hidden_out), ptr(pos_out), ptr(kept_idx),
+                                         ptr(new_cu_seqlens_dev), ptr(scores), ptr(workspace), workspace_bytes,
+                                         _stream(stream))
+    return _check(st, "uniprefill_fused_top_p_lse", check)
 
 
 def uniprefill_keep_mask(kept_idx, capacity, total_kept_dev, total_tokens, mask_out, stream=None, check=True):

@@ -242,9 +242,19 @@ int check_key_side(const up_params* p, const int32_t* cu_host, const KeySide& ks
   return UP_OK;
 }
 
+// key side of the entries that take it as optional arguments (both offset pointers or neither;
+// a block table only with them)
+int optional_key_side(const int32_t* cu_k_dev, const int32_t* cu_k_host, const PagedKeys* paged, KeySide* ks) {
+  if ((cu_k_dev == nullptr) != (cu_k_host == nullptr)) return UP_ERR_NULL;
+  const bool ctx = cu_k_host != nullptr;
+  if (!ctx && paged->block_table != nullptr) return UP_ERR_NULL;      // a block table needs the key counts
+  *ks = KeySide{cu_k_dev, cu_k_host, ctx, paged->block_table != nullptr ? paged : nullptr};
+  return UP_OK;
+}
+
 int score_impl(const up_params* p, const void* q, const void* k, const int32_t* cu_dev,
                const int32_t* cu_host, const KeySide& ks, float* scores_out, void* workspace,
-               size_t workspace_bytes, void* stream) {
+               size_t workspace_bytes, void* stream, const float* lse = nullptr, long long lse_stride = 0) {
   const int32_t* cu_k_dev = ks.cu_k_dev;
   const int32_t* cu_k_host = ks.cu_k_host;
   Problem pb;
@@ -253,13 +263,19 @@ int score_impl(const up_params* p, const void* q, const void* k, const int32_t* 
   if (!q || !k || !cu_dev || !scores_out) return UP_ERR_NULL;
   if ((st = check_cu(p, cu_host)) != UP_OK) return st;
   if ((st = check_key_side(p, cu_host, ks)) != UP_OK) return st;
+  if (lse != nullptr && lse_stride < pb.T) return UP_ERR_SHAPE;      // the heads of lse would overlap
   if (!aligned16(q) || !aligned16(k)) return UP_ERR_ALIGN;
   choose_geometry(&pb, cu_host, cu_k_host);
   if (workspace == nullptr || workspace_bytes < workspace_layout(pb).total) return UP_ERR_WORKSPACE;
   if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return UP_ERR_ALIGN;
   hipStream_t s = (hipStream_t)stream;
-  if (launch_row_stats(pb, q, k, cu_dev, cu_k_dev, ks.paged, workspace, s) != hipSuccess) return UP_ERR_HIP;
-  if (launch_merge_stats(pb, cu_dev, cu_k_dev, workspace, nullptr, nullptr, s) != hipSuccess) return UP_ERR_HIP;
+  if (lse != nullptr) {      // the rows' normalisers are given: no pass 1, no merge
+    if (launch_lse_stats(pb, cu_dev, cu_k_dev, lse, lse_stride, workspace, nullptr, nullptr, s) != hipSuccess)
+      return UP_ERR_HIP;
+  } else {
+    if (launch_row_stats(pb, q, k, cu_dev, cu_k_dev, ks.paged, workspace, s) != hipSuccess) return UP_ERR_HIP;
+    if (launch_merge_stats(pb, cu_dev, cu_k_dev, workspace, nullptr, nullptr, s) != hipSuccess) return UP_ERR_HIP;
+  }
   if (launch_column_sums(pb, q, k, cu_dev, cu_k_dev, ks.paged, workspace, scores_out, nullptr, s) != hipSuccess)
     return UP_ERR_HIP;
   return UP_OK;
@@ -367,12 +383,14 @@ int select_top_p_impl(const up_params* p, const float* scores, const int32_t* cu
 int fused_top_p_impl(const up_params* p, const void* q, const void* k, const void* hidden, const int32_t* pos,
                      const int32_t* cu_dev, const int32_t* cu_host, const KeySide& ks, const float* top_p_dev,
                      const float* top_p_host, void* hidden_out, int32_t* pos_out, int32_t* kept_idx,
-                     int32_t* new_cu_dev, float* scores, void* workspace, size_t workspace_bytes, void* stream) {
+                     int32_t* new_cu_dev, float* scores, void* workspace, size_t workspace_bytes, void* stream,
+                     const float* lse = nullptr, long long lse_stride = 0) {
   Problem pb;
   int st = check_params(p, true, true, &pb);
   if (st != UP_OK) return st;
   if (!q || !k || !hidden || !cu_dev || !top_p_dev || !hidden_out || !kept_idx || !new_cu_dev || !scores)
     return UP_ERR_NULL;
+  if (lse != nullptr && lse_stride < pb.T) return UP_ERR_SHAPE;
   if ((pos == nullptr) != (pos_out == nullptr)) return UP_ERR_NULL;
   if ((st = check_cu(p, cu_host)) != UP_OK) return st;
   if ((st = check_key_side(p, cu_host, ks)) != UP_OK) return st;
@@ -383,7 +401,8 @@ int fused_top_p_impl(const up_params* p, const void* q, const void* k, const voi
   choose_geometry(&pb, cu_host, ks.cu_k_host);
   if (workspace == nullptr || workspace_bytes < workspace_layout(pb).total) return UP_ERR_WORKSPACE;
   if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return UP_ERR_ALIGN;
-  if ((st = score_impl(p, q, k, cu_dev, cu_host, ks, scores, workspace, workspace_bytes, stream)) != UP_OK) return st;
+  if ((st = score_impl(p, q, k, cu_dev, cu_host, ks, scores, workspace, workspace_bytes, stream, lse, lse_stride)) != UP_OK)
+    return st;
   if ((st = select_top_p_impl(p, scores, cu_dev, cu_host, ks, top_p_dev, top_p_host, kept_idx, new_cu_dev,
                               workspace, workspace_bytes, stream)) != UP_OK)
     return st;
@@ -645,14 +664,49 @@ int uniprefill_fused_lse(const up_params* p, const void* q, const void* k, const
                          float* scores_out, void* workspace, size_t workspace_bytes, void* stream) {
   if (lse == nullptr) return UP_ERR_NULL;
   if ((reinterpret_cast<uintptr_t>(lse) & 3u) != 0) return UP_ERR_ALIGN;
-  if ((cu_seqlens_k_dev == nullptr) != (cu_seqlens_k_host == nullptr)) return UP_ERR_NULL;
-  const bool ctx = cu_seqlens_k_host != nullptr;
-  if (!ctx && block_table != nullptr) return UP_ERR_NULL;      // a block table needs the key counts
   const PagedKeys paged{block_table, block_table_stride, kv_block_size};
-  const KeySide ks{cu_seqlens_k_dev, cu_seqlens_k_host, ctx, block_table != nullptr ? &paged : nullptr};
+  KeySide ks;
+  const int st = optional_key_side(cu_seqlens_k_dev, cu_seqlens_k_host, &paged, &ks);
+  if (st != UP_OK) return st;
   return fused_impl(p, q, k, hidden, pos, cu_seqlens_dev, cu_seqlens_host, ks, keep_ratio_dev, keep_ratio_host,
                     hidden_out, pos_out, kept_idx, new_cu_seqlens_dev, scores_out, workspace, workspace_bytes,
                     UP_PHASE_ALL, stream, lse, lse_row_stride);
+}
+
+int uniprefill_score_lse(const up_params* p, const void* q, const void* k, const float* lse,
+                         int64_t lse_row_stride, const int32_t* cu_seqlens_dev,
+                         const int32_t* cu_seqlens_host, const int32_t* cu_seqlens_k_dev,
+                         const int32_t* cu_seqlens_k_host, const int32_t* block_table,
+                         int64_t block_table_stride, int32_t kv_block_size, float* scores_out,
+                         void* workspace, size_t workspace_bytes, void* stream) {
+  if (lse == nullptr) return UP_ERR_NULL;
+  if ((reinterpret_cast<uintptr_t>(lse) & 3u) != 0) return UP_ERR_ALIGN;
+  const PagedKeys paged{block_table, block_table_stride, kv_block_size};
+  KeySide ks;
+  const int st = optional_key_side(cu_seqlens_k_dev, cu_seqlens_k_host, &paged, &ks);
+  if (st != UP_OK) return st;
+  return score_impl(p, q, k, cu_seqlens_dev, cu_seqlens_host, ks, scores_out, workspace, workspace_bytes, stream,
+                    lse, lse_row_stride);
+}
+
+int uniprefill_fused_top_p_lse(const up_params* p, const void* q, const void* k, const float* lse,
+                               int64_t lse_row_stride, const void* hidden, const int32_t* pos,
+                               const int32_t* cu_seqlens_dev, const int32_t* cu_seqlens_host,
+                               const int32_t* cu_seqlens_k_dev, const int32_t* cu_seqlens_k_host,
+                               const int32_t* block_table, int64_t block_table_stride,
+                               int32_t kv_block_size, const float* top_p_dev, const float* top_p_host,
+                               void* hidden_out, int32_t* pos_out, int32_t* kept_idx,
+                               int32_t* new_cu_seqlens_dev, float* scores, void* workspace,
+                               size_t workspace_bytes, void* stream) {
+  if (lse == nullptr) return UP_ERR_NULL;
+  if ((reinterpret_cast<uintptr_t>(lse) & 3u) != 0) return UP_ERR_ALIGN;
+  const PagedKeys paged{block_table, block_table_stride, kv_block_size};
+  KeySide ks;
+  const int st = optional_key_side(cu_seqlens_k_dev, cu_seqlens_k_host, &paged, &ks);
+  if (st != UP_OK) return st;
+  return fused_top_p_impl(p, q, k, hidden, pos, cu_seqlens_dev, cu_seqlens_host, ks, top_p_dev, top_p_host,
+                          hidden_out, pos_out, kept_idx, new_cu_seqlens_dev, scores, workspace, workspace_bytes,
+                          stream, lse, lse_row_stride);
 }
 
 int uniprefill_fused_paged(const up_params* p, const void* q, const void* k_cache, const void* hidden,

@@ -1097,3 +1097,45 @@ def test_fused_with_given_normalisers_bit_exact(case):
     two = DeviceBatch(w, paged=paged)
     two.fused()
     np.testing.assert_array_equal(two.results()["kept_idx"], res["kept_idx"])
+
+
+def test_score_and_top_p_with_given_normalisers():
+    """uniprefill_score_lse and uniprefill_fused_top_p_lse on chunks after earlier context: the scores
+    are the oracle's from the same float normalisers; the top-p selection is the oracle's rule on them."""
+    _say("score / fused top-p from lse")
+    lengths, earlier = [3000, 150, 0, 1111, 64], [500, 0, 77, 4000, 100]
+    w = workloads.make_custom(name="lsetp", seed=27, lengths=lengths, keep_ratio=[0.5] * 5, hidden_dim=64,
+                              num_q_heads=8, num_kv_heads=2, block_size=64, n_obs=128, earlier=earlier)
+    lse = _window_lse_f32(w)
+    lse_dev = torch.from_numpy(lse).cuda()
+    top_p = np.array([0.9, 0.99, 0.5, 0.8, 0.7], np.float32)
+    b = DeviceBatch(w)
+    T, d = w.total_tokens, w.hidden_dim
+    up.uniprefill_score_lse(b.p, b.q, b.k, lse_dev, T, b.cu, b.cu_host, b.cu_k, b.cu_k_host, None, 0, 16, b.scores,
+                            b.workspace, b.ws_bytes)
+    got_scores = b.results()["scores"]
+    ref = oracle.quantise_scores(oracle.importance_scores_from_lse(_q_f32(w), workloads.bf16_bits_to_f32(w.k), lse,
+                                                                   w.cu_seqlens, w.cu_seqlens_k, n_obs=w.n_obs))
+    ok, worst = _score_close(got_scores, ref)
+    _say("  worst relative score error", worst)
+    assert ok and b.canaries_intact()
+    kept = torch.full((T + 64,), -77, dtype=torch.int32, device="cuda")
+    ncu = torch.full((w.num_seqs + 1,), -77, dtype=torch.int32, device="cuda")
+    hout = torch.full((T + 8, d), -7.0, dtype=torch.bfloat16, device="cuda")
+    pout = torch.full((T + 8,), -77, dtype=torch.int32, device="cuda")
+    sc = torch.empty(T, dtype=torch.float32, device="cuda")
+    up.uniprefill_fused_top_p_lse(b.p, b.q, b.k, lse_dev, T, b.hidden, b.pos, b.cu, b.cu_host, b.cu_k, b.cu_k_host, None, 0,
+                                  16, torch.from_numpy(top_p).cuda(), top_p, hout, pout, kept, ncu, sc, b.workspace,
+                                  b.ws_bytes)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(sc.cpu().numpy(), got_scores)
+    for scores in (got_scores, ref):
+        want_idx, want_cu = oracle.select_tokens_top_p_with_context(scores, w.cu_seqlens, w.cu_seqlens_k, top_p,
+                                                                    block_size=w.block_size, n_obs=w.n_obs, n_sink=w.n_sink)
+        np.testing.assert_array_equal(ncu.cpu().numpy(), want_cu)
+        np.testing.assert_array_equal(kept[:int(want_cu[-1])].cpu().numpy(), want_idx)
+    total = int(ncu[-1].item())
+    wh, wp = oracle.compact(w.hidden, w.pos, kept[:total].cpu().numpy())
+    np.testing.assert_array_equal(host_bits(hout[:total]), wh)
+    np.testing.assert_array_equal(pout[:total].cpu().numpy(), wp)
+    assert (kept[total:] == -77).all() and (pout[total:] == -77).all()
