@@ -146,7 +146,7 @@ __global__ __launch_bounds__(256) void k_seqused(DropLayers drops, const int32_t
                                                  int32_t* __restrict__ out) {
   const int r = blockIdx.x * 256 + threadIdx.x;
   const int layer = blockIdx.y;
-  if (r >= R) return;
+  if (r >= R || layer >= num_layers) return;
   int last = -1;
   for (int k = 0; k < drops.n; ++k)
     if (drops.layer[k] < layer) last = k;

@@ -640,7 +640,7 @@ __global__ __launch_bounds__(256) void k_lse_stats(const int32_t* __restrict__ c
   }
   const int u = blockIdx.x * 256 + threadIdx.x;
   const int h = blockIdx.y;
-  if (u >= row_slots) return;
+  if (u >= row_slots || h >= Hq) return;
   const int r = locate_rowslot(cu, R, n_obs, u);
   const int c0 = cu[r];
   const int N = cu[r + 1] - c0;
