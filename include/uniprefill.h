@@ -37,7 +37,9 @@
  *       UP_ERR_WORKSPACE   workspace is NULL or smaller than uniprefill_plan says
  *       UP_ERR_HIP         a launch failed (hipGetLastError after the launch)
  *   - Zero-length sequences are legal and produce nothing; total_tokens == 0 is
- *     legal and launches nothing.
+ *     legal: the per-token arrays (q, k, hidden, scores, kept_idx, outputs) may
+ *     then be NULL, and only new_cu_seqlens_dev is written (all zero).  A copy
+ *     of zero rows launches nothing and needs no pointers.
  *   - Layouts: q is [T, num_q_heads, head_dim] with row stride q_row_stride
  *     elements between tokens (heads contiguous inside a row); k likewise with
  *     num_kv_heads and k_row_stride; hidden is [T, hidden_dim] with row stride

@@ -260,14 +260,14 @@ int score_impl(const up_params* p, const void* q, const void* k, const int32_t* 
   Problem pb;
   int st = check_params(p, true, false, &pb);
   if (st != UP_OK) return st;
-  if (!q || !k || !cu_dev || !scores_out) return UP_ERR_NULL;
+  if (!cu_dev || (pb.T > 0 && (!q || !k || !scores_out))) return UP_ERR_NULL;
   if ((st = check_cu(p, cu_host)) != UP_OK) return st;
   if ((st = check_key_side(p, cu_host, ks)) != UP_OK) return st;
   if (lse != nullptr && lse_stride < pb.T) return UP_ERR_SHAPE;      // the heads of lse would overlap
   if (!aligned16(q) || !aligned16(k)) return UP_ERR_ALIGN;
   choose_geometry(&pb, cu_host, cu_k_host);
-  if (workspace == nullptr || workspace_bytes < workspace_layout(pb).total) return UP_ERR_WORKSPACE;
-  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return UP_ERR_ALIGN;
+  if (pb.T > 0 && (workspace == nullptr || workspace_bytes < workspace_layout(pb).total)) return UP_ERR_WORKSPACE;
+  if (pb.T > 0 && (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return UP_ERR_ALIGN;
   hipStream_t s = (hipStream_t)stream;
   if (lse != nullptr) {      // the rows' normalisers are given: no pass 1, no merge
     if (launch_lse_stats(pb, cu_dev, cu_k_dev, lse, lse_stride, workspace, nullptr, nullptr, s) != hipSuccess)
@@ -287,7 +287,8 @@ int select_impl(const up_params* p, const float* scores, const int32_t* cu_dev, 
   Problem pb;
   int st = check_params(p, false, false, &pb);
   if (st != UP_OK) return st;
-  if (!scores || !cu_dev || !ratio_dev || !kept_idx || !new_cu_dev || (ctx && !cu_k_dev)) return UP_ERR_NULL;
+  if (!cu_dev || !ratio_dev || !new_cu_dev || (ctx && !cu_k_dev) || (pb.T > 0 && (!scores || !kept_idx)))
+    return UP_ERR_NULL;
   if ((st = check_cu(p, cu_host)) != UP_OK) return st;
   if (ctx && (st = check_cu_k(p, cu_host, cu_k_host)) != UP_OK) return st;
   if ((st = check_ratio(p, ratio_host)) != UP_OK) return st;
@@ -308,9 +309,10 @@ int fused_impl(const up_params* p, const void* q, const void* k, const void* hid
   Problem pb;
   int st = check_params(p, true, true, &pb);
   if (st != UP_OK) return st;
-  if (!q || !k || !hidden || !cu_dev || !ratio_dev || !hidden_out || !kept_idx || !new_cu_dev)
+  // (a batch without tokens touches none of the per-token arrays: they may be NULL then)
+  if (!cu_dev || !ratio_dev || !new_cu_dev || (pb.T > 0 && (!q || !k || !hidden || !hidden_out || !kept_idx)))
     return UP_ERR_NULL;
-  if ((pos == nullptr) != (pos_out == nullptr)) return UP_ERR_NULL;
+  if (pb.T > 0 && (pos == nullptr) != (pos_out == nullptr)) return UP_ERR_NULL;
   if ((st = check_cu(p, cu_host)) != UP_OK) return st;
   if ((st = check_key_side(p, cu_host, ks)) != UP_OK) return st;
   if ((st = check_ratio(p, ratio_host)) != UP_OK) return st;
@@ -319,8 +321,8 @@ int fused_impl(const up_params* p, const void* q, const void* k, const void* hid
     return UP_ERR_ALIGN;
   choose_geometry(&pb, cu_host, cu_k_host);
   const Workspace w = workspace_layout(pb);
-  if (workspace == nullptr || workspace_bytes < w.total) return UP_ERR_WORKSPACE;
-  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return UP_ERR_ALIGN;
+  if (pb.T > 0 && (workspace == nullptr || workspace_bytes < w.total)) return UP_ERR_WORKSPACE;
+  if (pb.T > 0 && (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return UP_ERR_ALIGN;
   if (phase_mask & ~UP_PHASE_ALL) return UP_ERR_RANGE;
   hipStream_t s = (hipStream_t)stream;
   if (lse != nullptr) {
@@ -362,7 +364,7 @@ int select_top_p_impl(const up_params* p, const float* scores, const int32_t* cu
   Problem pb;
   int st = check_params(p, false, false, &pb);
   if (st != UP_OK) return st;
-  if (!scores || !cu_dev || !top_p_dev || !kept_idx || !new_cu_dev) return UP_ERR_NULL;
+  if (!cu_dev || !top_p_dev || !new_cu_dev || (pb.T > 0 && (!scores || !kept_idx))) return UP_ERR_NULL;
   if ((st = check_cu(p, cu_host)) != UP_OK) return st;
   if ((st = check_key_side(p, cu_host, ks)) != UP_OK) return st;
   if ((st = check_ratio(p, top_p_host)) != UP_OK) return st;
@@ -370,8 +372,12 @@ int select_top_p_impl(const up_params* p, const float* scores, const int32_t* cu
   for (int r = 0; r < p->num_seqs; ++r)
     max_blocks = imax(max_blocks, (cu_host[r + 1] - cu_host[r] + pb.G - 1) / pb.G);
   if (max_blocks > kMaxTopPBlocks) return UP_ERR_UNSUPPORTED;
+  if (pb.T == 0) {      // no token: the offsets are all zero (the plan's kernel writes them), no workspace is touched
+    if (launch_plan(pb, cu_dev, ks.cu_k_dev, top_p_dev, new_cu_dev, (hipStream_t)stream) != hipSuccess) return UP_ERR_HIP;
+    return UP_OK;
+  }
   if (workspace == nullptr || workspace_bytes < workspace_layout(pb).tp_total) return UP_ERR_WORKSPACE;
-  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return UP_ERR_ALIGN;
+  if (pb.T > 0 && (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return UP_ERR_ALIGN;
   if (launch_top_p(pb, scores, cu_dev, ks.cu_k_dev, top_p_dev, kept_idx, new_cu_dev, workspace, max_blocks,
                    (hipStream_t)stream) != hipSuccess)
     return UP_ERR_HIP;
@@ -388,10 +394,11 @@ int fused_top_p_impl(const up_params* p, const void* q, const void* k, const voi
   Problem pb;
   int st = check_params(p, true, true, &pb);
   if (st != UP_OK) return st;
-  if (!q || !k || !hidden || !cu_dev || !top_p_dev || !hidden_out || !kept_idx || !new_cu_dev || !scores)
+  if (!cu_dev || !top_p_dev || !new_cu_dev ||
+      (pb.T > 0 && (!q || !k || !hidden || !hidden_out || !kept_idx || !scores)))
     return UP_ERR_NULL;
   if (lse != nullptr && lse_stride < pb.T) return UP_ERR_SHAPE;
-  if ((pos == nullptr) != (pos_out == nullptr)) return UP_ERR_NULL;
+  if (pb.T > 0 && (pos == nullptr) != (pos_out == nullptr)) return UP_ERR_NULL;
   if ((st = check_cu(p, cu_host)) != UP_OK) return st;
   if ((st = check_key_side(p, cu_host, ks)) != UP_OK) return st;
   if ((st = check_ratio(p, top_p_host)) != UP_OK) return st;
@@ -399,8 +406,8 @@ int fused_top_p_impl(const up_params* p, const void* q, const void* k, const voi
     if ((cu_host[r + 1] - cu_host[r] + pb.G - 1) / pb.G > kMaxTopPBlocks) return UP_ERR_UNSUPPORTED;
   if (!aligned16(q) || !aligned16(k) || !aligned16(hidden) || !aligned16(hidden_out)) return UP_ERR_ALIGN;
   choose_geometry(&pb, cu_host, ks.cu_k_host);
-  if (workspace == nullptr || workspace_bytes < workspace_layout(pb).total) return UP_ERR_WORKSPACE;
-  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return UP_ERR_ALIGN;
+  if (pb.T > 0 && (workspace == nullptr || workspace_bytes < workspace_layout(pb).total)) return UP_ERR_WORKSPACE;
+  if (pb.T > 0 && (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return UP_ERR_ALIGN;
   if ((st = score_impl(p, q, k, cu_dev, cu_host, ks, scores, workspace, workspace_bytes, stream, lse, lse_stride)) != UP_OK)
     return st;
   if ((st = select_top_p_impl(p, scores, cu_dev, cu_host, ks, top_p_dev, top_p_host, kept_idx, new_cu_dev,
@@ -495,6 +502,7 @@ int uniprefill_compact_counted(const up_params* p, const void* hidden, const int
   int st = check_params(p, false, true, &pb);
   if (st != UP_OK) return st;
   if (capacity < 0 || capacity > p->total_tokens) return UP_ERR_RANGE;
+  if (capacity == 0) return UP_OK;      // nothing to copy, nothing launched
   if (!hidden || !kept_idx || !hidden_out || !total_kept_dev) return UP_ERR_NULL;
   if ((pos == nullptr) != (pos_out == nullptr)) return UP_ERR_NULL;
   if (!aligned16(hidden) || !aligned16(hidden_out)) return UP_ERR_ALIGN;
@@ -537,6 +545,7 @@ int uniprefill_compact(const up_params* p, const void* hidden, const int32_t* po
   int st = check_params(p, false, true, &pb);
   if (st != UP_OK) return st;
   if (total_kept < 0 || total_kept > p->total_tokens) return UP_ERR_RANGE;
+  if (total_kept == 0) return UP_OK;    // nothing to copy, nothing launched
   if (!hidden || !kept_idx || !hidden_out) return UP_ERR_NULL;
   if ((pos == nullptr) != (pos_out == nullptr)) return UP_ERR_NULL;
   if (!aligned16(hidden) || !aligned16(hidden_out)) return UP_ERR_ALIGN;
@@ -552,6 +561,7 @@ int uniprefill_scatter(const up_params* p, const void* hidden_compact, const int
   int st = check_params(p, false, true, &pb);
   if (st != UP_OK) return st;
   if (total_kept < 0 || total_kept > p->total_tokens) return UP_ERR_RANGE;
+  if (total_kept == 0) return UP_OK;    // nothing to copy, nothing launched
   if (!hidden_compact || !kept_idx || !hidden_full_inout) return UP_ERR_NULL;
   if (!aligned16(hidden_compact) || !aligned16(hidden_full_inout)) return UP_ERR_ALIGN;
   if (launch_scatter(pb, hidden_compact, kept_idx, total_kept, hidden_full_inout,

@@ -1139,3 +1139,42 @@ def test_score_and_top_p_with_given_normalisers():
     np.testing.assert_array_equal(host_bits(hout[:total]), wh)
     np.testing.assert_array_equal(pout[:total].cpu().numpy(), wp)
     assert (kept[total:] == -77).all() and (pout[total:] == -77).all()
+
+
+def test_batches_without_tokens():
+    """Every request empty: legal; nothing but the plan is launched and new_cu_seqlens is all zero.
+    Also a batch whose requests have cached keys but bring no token."""
+    _say("empty batches")
+    for earlier in (None, [100, 0, 7]):
+        w = workloads.make_custom(name="none", seed=28, lengths=[0, 0, 0], keep_ratio=[0.5] * 3, hidden_dim=64,
+                                  num_q_heads=8, num_kv_heads=2, block_size=64, n_obs=128, earlier=earlier)
+        assert w.total_tokens == 0
+        b = DeviceBatch(w)
+        assert b.total_kept == 0
+        b.fused()
+        res = b.results()
+        np.testing.assert_array_equal(res["new_cu_seqlens"], [0, 0, 0, 0])
+        assert res["kept_idx"].size == 0 and b.canaries_intact()
+        b.new_cu.fill_(-77)
+        b.score()
+        b.select(b.scores)
+        np.testing.assert_array_equal(b.results()["new_cu_seqlens"], [0, 0, 0, 0])
+        assert b.canaries_intact()
+        # the per-token arrays and the workspace may be NULL when there is no token
+        b.new_cu.fill_(-77)
+        if earlier is None:
+            up.uniprefill_fused(b.p, None, None, None, None, b.cu, b.cu_host, b.ratio, b.ratio_host, None, None, None,
+                                b.new_cu, None, None, 0)
+        else:
+            up.uniprefill_fused_chunked(b.p, None, None, None, None, b.cu, b.cu_host, b.cu_k, b.cu_k_host, b.ratio,
+                                        b.ratio_host, None, None, None, b.new_cu, None, None, 0)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(b.new_cu[:4].cpu().numpy(), [0, 0, 0, 0])
+        b.new_cu.fill_(-77)
+        up.uniprefill_fused_top_p_lse(b.p, None, None, torch.zeros(8, dtype=torch.float32, device="cuda"), 0, None, None,
+                                      b.cu, b.cu_host, b.cu_k if earlier else None, b.cu_k_host if earlier else None,
+                                      None, 0, 16, b.ratio, b.ratio_host, None, None, None, b.new_cu, None, None, 0)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(b.new_cu[:4].cpu().numpy(), [0, 0, 0, 0])
+        assert up.uniprefill_compact(b.p, None, None, None, 0, None, None) == up.UP_OK
+        assert up.uniprefill_scatter(b.p, None, None, 0, None) == up.UP_OK
