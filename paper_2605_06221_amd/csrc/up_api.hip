@@ -92,6 +92,7 @@ int check_cu_k(const up_params* p, const int32_t* cu_host, const int32_t* cu_k_h
 }
 
 int check_ratio(const up_params* p, const float* ratio_host) {
+  if (p->num_seqs == 0) return UP_OK;       // an empty array may be NULL
   if (ratio_host == nullptr) return UP_ERR_NULL;
   for (int r = 0; r < p->num_seqs; ++r)
     if (!(ratio_host[r] > 0.0f && ratio_host[r] <= 1.0f)) return UP_ERR_RANGE;
@@ -287,7 +288,7 @@ int select_impl(const up_params* p, const float* scores, const int32_t* cu_dev, 
   Problem pb;
   int st = check_params(p, false, false, &pb);
   if (st != UP_OK) return st;
-  if (!cu_dev || !ratio_dev || !new_cu_dev || (ctx && !cu_k_dev) || (pb.T > 0 && (!scores || !kept_idx)))
+  if (!cu_dev || (pb.R > 0 && !ratio_dev) || !new_cu_dev || (ctx && !cu_k_dev) || (pb.T > 0 && (!scores || !kept_idx)))
     return UP_ERR_NULL;
   if ((st = check_cu(p, cu_host)) != UP_OK) return st;
   if (ctx && (st = check_cu_k(p, cu_host, cu_k_host)) != UP_OK) return st;
@@ -310,7 +311,8 @@ int fused_impl(const up_params* p, const void* q, const void* k, const void* hid
   int st = check_params(p, true, true, &pb);
   if (st != UP_OK) return st;
   // (a batch without tokens touches none of the per-token arrays: they may be NULL then)
-  if (!cu_dev || !ratio_dev || !new_cu_dev || (pb.T > 0 && (!q || !k || !hidden || !hidden_out || !kept_idx)))
+  if (!cu_dev || (pb.R > 0 && !ratio_dev) || !new_cu_dev ||
+      (pb.T > 0 && (!q || !k || !hidden || !hidden_out || !kept_idx)))
     return UP_ERR_NULL;
   if (pb.T > 0 && (pos == nullptr) != (pos_out == nullptr)) return UP_ERR_NULL;
   if ((st = check_cu(p, cu_host)) != UP_OK) return st;
@@ -325,6 +327,11 @@ int fused_impl(const up_params* p, const void* q, const void* k, const void* hid
   if (pb.T > 0 && (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return UP_ERR_ALIGN;
   if (phase_mask & ~UP_PHASE_ALL) return UP_ERR_RANGE;
   hipStream_t s = (hipStream_t)stream;
+  if (pb.T == 0) {      // no token: only the offsets (all zero) are written
+    if ((phase_mask & UP_PHASE_PLAN) && launch_plan(pb, cu_dev, cu_k_dev, ratio_dev, new_cu_dev, s) != hipSuccess)
+      return UP_ERR_HIP;
+    return UP_OK;
+  }
   if (lse != nullptr) {
     // the rows' normalisers are given: no pass 1, no merge; the plan rides in the conversion
     if (launch_lse_stats(pb, cu_dev, cu_k_dev, lse, lse_stride, workspace, ratio_dev, new_cu_dev, s) != hipSuccess)
@@ -364,7 +371,7 @@ int select_top_p_impl(const up_params* p, const float* scores, const int32_t* cu
   Problem pb;
   int st = check_params(p, false, false, &pb);
   if (st != UP_OK) return st;
-  if (!cu_dev || !top_p_dev || !new_cu_dev || (pb.T > 0 && (!scores || !kept_idx))) return UP_ERR_NULL;
+  if (!cu_dev || (pb.R > 0 && !top_p_dev) || !new_cu_dev || (pb.T > 0 && (!scores || !kept_idx))) return UP_ERR_NULL;
   if ((st = check_cu(p, cu_host)) != UP_OK) return st;
   if ((st = check_key_side(p, cu_host, ks)) != UP_OK) return st;
   if ((st = check_ratio(p, top_p_host)) != UP_OK) return st;
@@ -394,7 +401,7 @@ int fused_top_p_impl(const up_params* p, const void* q, const void* k, const voi
   Problem pb;
   int st = check_params(p, true, true, &pb);
   if (st != UP_OK) return st;
-  if (!cu_dev || !top_p_dev || !new_cu_dev ||
+  if (!cu_dev || (pb.R > 0 && !top_p_dev) || !new_cu_dev ||
       (pb.T > 0 && (!q || !k || !hidden || !hidden_out || !kept_idx || !scores)))
     return UP_ERR_NULL;
   if (lse != nullptr && lse_stride < pb.T) return UP_ERR_SHAPE;

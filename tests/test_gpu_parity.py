@@ -1178,3 +1178,11 @@ def test_batches_without_tokens():
         np.testing.assert_array_equal(b.new_cu[:4].cpu().numpy(), [0, 0, 0, 0])
         assert up.uniprefill_compact(b.p, None, None, None, 0, None, None) == up.UP_OK
         assert up.uniprefill_scatter(b.p, None, None, 0, None) == up.UP_OK
+    # no request at all
+    p0 = up.make_params(num_seqs=0, total_tokens=0, block_size=64, num_q_heads=8, num_kv_heads=2, hidden_dim=64)
+    cu0_host = np.zeros(1, np.int32)
+    cu0 = torch.zeros(1, dtype=torch.int32, device="cuda")
+    out0 = torch.full((4,), -77, dtype=torch.int32, device="cuda")
+    up.uniprefill_fused(p0, None, None, None, None, cu0, cu0_host, None, None, None, None, None, out0, None, None, 0)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(out0.cpu().numpy(), [0, -77, -77, -77])
