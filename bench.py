@@ -53,6 +53,91 @@ def product_flops(w):
     return f
 
 
+def bench_chunked(args, up, workloads, np, torch):
+    """Chunks that follow earlier context: the two-pass call and the call fed with the rows' log-sum-exp."""
+    if not args.lengths:
+        print("bench.py: --earlier needs --lengths", file=sys.stderr)
+        sys.exit(2)
+    lengths = [int(x) for x in args.lengths.split(",")]
+    earlier = [int(x) for x in args.earlier.split(",")]
+    if len(earlier) == 1:
+        earlier = earlier * len(lengths)
+    w = workloads.make_custom(name=f"llama8b_shape_{len(lengths)}x{max(lengths)}_after_{max(earlier)}_r{args.keep_ratio}",
+                              seed=100, lengths=lengths, keep_ratio=[args.keep_ratio] * len(lengths), hidden_dim=4096,
+                              num_q_heads=32, num_kv_heads=8, block_size=128, head_dim=args.head_dim, earlier=earlier)
+    cu_host = np.ascontiguousarray(w.cu_seqlens, dtype=np.int32)
+    cu_k_host = np.ascontiguousarray(w.cu_seqlens_k, dtype=np.int32)
+    ratio_host = np.ascontiguousarray(w.keep_ratio, dtype=np.float32)
+    p = up.make_params(num_seqs=w.num_seqs, total_tokens=w.total_tokens, block_size=w.block_size, n_obs=w.n_obs,
+                       n_sink=w.n_sink, num_q_heads=w.num_q_heads, num_kv_heads=w.num_kv_heads, head_dim=w.head_dim,
+                       hidden_dim=w.hidden_dim)
+    _, _, total_kept, ws_bytes = up.uniprefill_plan_chunked(p, cu_host, cu_k_host, ratio_host)
+    dev = lambda bits: torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+    q, k, hidden = dev(w.q), dev(w.k), dev(w.hidden)
+    pos, cu, cu_k = torch.from_numpy(w.pos).cuda(), torch.from_numpy(cu_host).cuda(), torch.from_numpy(cu_k_host).cuda()
+    ratio = torch.from_numpy(ratio_host).cuda()
+    workspace = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    hidden_out = torch.empty((total_kept, w.hidden_dim), dtype=torch.bfloat16, device="cuda")
+    pos_out = torch.empty(total_kept, dtype=torch.int32, device="cuda")
+    kept_idx = torch.empty(total_kept, dtype=torch.int32, device="cuda")
+    kept_lse = torch.empty_like(kept_idx)
+    new_cu = torch.empty(w.num_seqs + 1, dtype=torch.int32, device="cuda")
+    stream = torch.cuda.current_stream()
+    # the rows' log-sum-exp over earlier and own keys (an input of the second call; plain torch, fp64)
+    lse = torch.full((w.num_q_heads, w.total_tokens), float("nan"), dtype=torch.float32, device="cuda")
+    group, sc_l = w.num_q_heads // w.num_kv_heads, 1.0 / float(np.sqrt(w.head_dim))
+    for r in range(w.num_seqs):
+        c0, c1, k0, k1 = int(cu_host[r]), int(cu_host[r + 1]), int(cu_k_host[r]), int(cu_k_host[r + 1])
+        n_eff = min(w.n_obs, c1 - c0)
+        if n_eff == 0:
+            continue
+        rows = torch.arange(k1 - k0 - n_eff, k1 - k0, device="cuda")[:, None]
+        cols = torch.arange(k1 - k0, device="cuda")[None, :]
+        for h in range(w.num_q_heads):
+            logits = (q[c1 - n_eff:c1, h, :].double() @ k[k0:k1, h // group, :].double().T) * sc_l
+            logits.masked_fill_(cols > rows, float("-inf"))
+            lse[h, c1 - n_eff:c1] = torch.logsumexp(logits, dim=1).float()
+
+    def two_pass():
+        up.uniprefill_fused_chunked(p, q, k, hidden, pos, cu, cu_host, cu_k, cu_k_host, ratio, ratio_host, hidden_out,
+                                    pos_out, kept_idx, new_cu, None, workspace, ws_bytes, stream=stream)
+
+    def from_lse():
+        up.uniprefill_fused_lse(p, q, k, lse, w.total_tokens, hidden, pos, cu, cu_host, cu_k, cu_k_host, None, 0, 16,
+                                ratio, ratio_host, hidden_out, pos_out, kept_lse, new_cu, None, workspace, ws_bytes,
+                                stream=stream)
+
+    def timed(fn):
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(args.steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t1) / args.steps
+
+    t_lse = timed(from_lse)
+    t_two = timed(two_pass)
+    parity = None
+    if not args.no_cpu_baseline:
+        sys.path.insert(0, os.path.join(ROOT, "tests"))
+        from gpu_util import oracle_run
+        ref = oracle_run(w)
+        parity = bool(np.array_equal(kept_idx.cpu().numpy(), ref["kept_idx"])
+                      and np.array_equal(hidden_out.view(torch.int16).cpu().numpy().view(np.uint16), ref["hidden_out"]))
+    print(json.dumps({
+        "metric": "tokens/s through fused score+select+compact op (chunk after earlier context)",
+        "value": round(w.total_tokens / t_two, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(t_two * 1e3, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "total_tokens": w.total_tokens, "key_tokens": int(cu_k_host[-1]),
+                   "num_seqs": w.num_seqs, "total_kept": int(total_kept)},
+        "roofline": None, "cpu_baseline": None,
+        "fused_from_lse": {"ms_per_step": round(t_lse * 1e3, 4), "same_kept_set_as_fused": bool(torch.equal(kept_lse, kept_idx))},
+        "oracle_parity": parity}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -64,6 +149,10 @@ def main():
                          "128) with these comma-separated sequence lengths, e.g. 8192,8192")
     ap.add_argument("--keep-ratio", type=float, default=0.3, help="keep ratio of a --lengths batch")
     ap.add_argument("--head-dim", type=int, default=128, help="head dimension of a --lengths batch (64, 128, 256)")
+    ap.add_argument("--earlier", type=str, default=None,
+                    help="with --lengths: tokens of earlier context per request whose keys are cached (chunked "
+                         "prefill), e.g. --lengths 8192 --earlier 122880; times uniprefill_fused_chunked and "
+                         "uniprefill_fused_lse on that batch (no per-kernel loop)")
     ap.add_argument("--input-sets", type=int, default=3,
                     help="copies of (q, k, hidden) in HBM that the steps rotate over, so that no step "
                          "finds its inputs in the 256 MB last-level cache (1 = warm)")
@@ -93,6 +182,8 @@ def main():
         sys.exit(2)
 
     t0 = time.time()
+    if args.earlier:
+        return bench_chunked(args, up, workloads, np, torch)
     if args.lengths:
         lengths = [int(x) for x in args.lengths.split(",")]
         w = workloads.make_custom(name=f"llama8b_shape_{len(lengths)}x{max(lengths)}_r{args.keep_ratio}_hd{args.head_dim}", seed=100,
