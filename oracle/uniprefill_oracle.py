@@ -474,6 +474,54 @@ def importance_scores_from_lse(q, k, lse, cu_seqlens_q, cu_seqlens_k, *, n_obs, 
     return o
 
 
+def importance_sums(q, k, cu_seqlens_q, cu_seqlens_k, *, n_obs, scale=None):
+    """What one tensor-parallel rank contributes (section "Tensor parallelism", Eq. 15): the
+    attention weights of Eq. 2 summed over the window rows and over the query heads given (the
+    rank's share), not yet divided by anything.  Same arguments as importance_scores_with_context."""
+    k = np.asarray(k)
+    cq = np.asarray(cu_seqlens_q, dtype=np.int64)
+    ck = np.asarray(cu_seqlens_k, dtype=np.int64)
+    T, Hq, D = q.shape
+    group = Hq // k.shape[1]
+    if scale is None:
+        scale = 1.0 / math.sqrt(D)
+    out = np.zeros(T, dtype=np.float64)
+    for r in range(len(cq) - 1):
+        c0, c1, k0, k1 = int(cq[r]), int(cq[r + 1]), int(ck[r]), int(ck[r + 1])
+        N, L = c1 - c0, k1 - k0
+        if N == 0:
+            continue
+        n_eff = min(int(n_obs), N)
+        Kr = k[k0:k1].astype(np.float64)
+        Qw = np.asarray(q[c1 - n_eff:c1], dtype=np.float64)
+        visible = np.arange(L)[None, :] <= np.arange(L - n_eff, L)[:, None]
+        colsum = np.zeros(L, dtype=np.float64)
+        for h in range(Hq):
+            S = scale * (Qw[:, h, :] @ Kr[:, h // group, :].T)
+            S[~visible] = -np.inf
+            S -= S.max(axis=1, keepdims=True)
+            W = np.exp(S)
+            W /= W.sum(axis=1, keepdims=True)
+            colsum += W.sum(axis=0)
+        out[c0:c1] = colsum[L - N:]
+    return out
+
+
+def scores_from_partial_sums(partials, cu_seqlens, *, n_obs, total_q_heads):
+    """Eq. 15 followed by the means of Eq. 3: the ranks' sums added (in rank order), divided by
+    the window rows and by the query heads of all ranks; float64, not yet quantised."""
+    cu = np.asarray(cu_seqlens, dtype=np.int64)
+    total = np.zeros(int(cu[-1]), dtype=np.float64)
+    for part in partials:
+        total = total + np.asarray(part, dtype=np.float64)
+    o = np.zeros_like(total)
+    for r in range(len(cu) - 1):
+        N = int(cu[r + 1] - cu[r])
+        if N:
+            o[cu[r]:cu[r + 1]] = total[cu[r]:cu[r + 1]] / (min(int(n_obs), N) * int(total_q_heads))
+    return o
+
+
 def gather_paged_keys(k_cache, cu_seqlens_k, block_table, kv_block_size):
     """Keys of every request read out of a paged KV cache into the packed layout that
     ``importance_scores_with_context`` takes: key i of request r is row

@@ -219,3 +219,28 @@ def test_scores_from_normalisers_hand_case_and_scaling():
     lse[0, 2] += math.log(2.0)
     got = oracle.importance_scores_from_lse(q, k, lse, [0, 3], [0, 3], n_obs=2, scale=1.0)
     np.testing.assert_allclose(got, [(1 / 3 + 1 / 12) / 2, (2 / 3 + 2 / 12) / 2, (3 / 12) / 2], rtol=1e-14)
+
+
+def test_partial_sums_of_head_shards_add_up_to_the_scores():
+    """Eq. 15: with the heads split over ranks (each rank its query heads and their kv heads), the
+    ranks' sums add up to n_eff * Hq times the score of the whole model."""
+    rng = np.random.default_rng(15)
+    Ps, Ns = [0, 40, 300], [64, 1, 200]
+    cq = np.concatenate([[0], np.cumsum(Ns)])
+    ck = np.concatenate([[0], np.cumsum(np.add(Ps, Ns))])
+    Hq, Hkv, D = 8, 4, 8
+    q = rng.standard_normal((cq[-1], Hq, D))
+    k = rng.standard_normal((ck[-1], Hkv, D))
+    whole = oracle.importance_scores_with_context(q, k, cq, ck, n_obs=32)
+    parts = [oracle.importance_sums(q[:, 2 * t:2 * t + 2], k[:, t:t + 1], cq, ck, n_obs=32) for t in range(4)]
+    got = oracle.scores_from_partial_sums(parts, cq, n_obs=32, total_q_heads=Hq)
+    np.testing.assert_allclose(got, whole, rtol=1e-13, atol=0)
+    # one rank with all heads: its sums are the scores times rows times heads
+    all_heads = oracle.importance_sums(q, k, cq, ck, n_obs=32)
+    for r in range(3):
+        n_eff = min(32, Ns[r])
+        np.testing.assert_allclose(all_heads[cq[r]:cq[r + 1]], whole[cq[r]:cq[r + 1]] * n_eff * Hq, rtol=1e-13)
+    # hand case: one head, weights 1:2:3 over two rows -> column sums [1/2, 1, 1/2]
+    qh = np.ones((3, 1, 1))
+    kh = np.log(np.array([1.0, 2.0, 3.0])).reshape(3, 1, 1)
+    np.testing.assert_allclose(oracle.importance_sums(qh, kh, [0, 3], [0, 3], n_obs=2, scale=1.0), [1 / 2, 1.0, 1 / 2], rtol=1e-14)
