@@ -398,6 +398,28 @@ int uniprefill_fused_top_p_lse(const up_params* p, const void* q, const void* k,
                                int32_t* new_cu_seqlens_dev, float* scores, void* workspace,
                                size_t workspace_bytes, void* stream);
 
+/* One tensor-parallel rank's share (section "Tensor parallelism", Eq. 15).  A rank
+ * holds num_q_heads / num_kv_heads of the model's heads (up_params describes the
+ * rank's share; q and k may be views into wider rows through the row strides) and
+ * leaves, per token, the attention weights summed over the window rows and over
+ * its heads -- not divided, not floored -- as doubles: colsum_out [T], device,
+ * 8-byte aligned.  cu_seqlens_k_dev/_host: both NULL, or the key-side offsets of
+ * tokens after earlier context.  Workspace from uniprefill_plan(_chunked) with
+ * the rank's up_params.
+ * uniprefill_scores_from_partials then forms the scores from the ranks' sums
+ * once they sit side by side on one device (partials[p * part_stride + t], after
+ * an all-gather): added in rank order, divided by the window rows min(n_obs, N_r)
+ * and by the query heads of all ranks, means below 2^-64 written as +0 -- what
+ * uniprefill_score writes on one device, so that uniprefill_select (or the
+ * top-p rule) takes the same decision on every rank. */
+int uniprefill_score_partial(const up_params* p, const void* q, const void* k,
+                             const int32_t* cu_seqlens_dev, const int32_t* cu_seqlens_host,
+                             const int32_t* cu_seqlens_k_dev, const int32_t* cu_seqlens_k_host,
+                             double* colsum_out, void* workspace, size_t workspace_bytes, void* stream);
+int uniprefill_scores_from_partials(const double* partials, int32_t num_parts, int64_t part_stride,
+                                    const int32_t* cu_seqlens_dev, int32_t num_seqs, int32_t total_tokens,
+                                    int32_t n_obs, int32_t total_q_heads, float* scores_out, void* stream);
+
 /* The paper's block-level top-p rule (uniprefill_select_top_p, uniprefill_fused_top_p) for
  * tokens that follow earlier context: the sinks are those that fall inside the
  * tokens (position P_r + i below n_sink), and the threshold is p times the mass

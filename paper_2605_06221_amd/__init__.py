@@ -7,7 +7,7 @@ from .binding import (  # noqa: F401
     uniprefill_compact_counted, uniprefill_fused_top_p, uniprefill_compose_index, uniprefill_slot_mapping,
     uniprefill_compact_column, uniprefill_seqused, uniprefill_score_paged, uniprefill_fused_paged, uniprefill_select_top_p_chunked,
     uniprefill_fused_top_p_chunked, uniprefill_keep_mask, uniprefill_fused_lse, uniprefill_score_lse,
-    uniprefill_fused_top_p_lse, uniprefill_plan_chunked, uniprefill_score_chunked, uniprefill_select_chunked, uniprefill_fused_chunked,
+    uniprefill_fused_top_p_lse, uniprefill_score_partial, uniprefill_scores_from_partials, uniprefill_plan_chunked, uniprefill_score_chunked, uniprefill_select_chunked, uniprefill_fused_chunked,
     UP_PHASE_PLAN, UP_PHASE_ROW_STATS, UP_PHASE_MERGE_STATS, UP_PHASE_SWEEP_SELECT, UP_PHASE_GATHER,
     UP_PHASE_ALL,
 )

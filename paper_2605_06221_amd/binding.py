@@ -25,7 +25,8 @@ EXPORTS = ["uniprefill_plan", "uniprefill_score", "uniprefill_select", "uniprefi
            "uniprefill_select_chunked", "uniprefill_fused_chunked", "uniprefill_compact_column", "uniprefill_seqused",
            "uniprefill_score_paged", "uniprefill_fused_paged", "uniprefill_select_top_p_chunked",
            "uniprefill_fused_top_p_chunked", "uniprefill_keep_mask", "uniprefill_fused_lse",
-           "uniprefill_score_lse", "uniprefill_fused_top_p_lse",
+           "uniprefill_score_lse", "uniprefill_fused_top_p_lse", "uniprefill_score_partial",
+           "uniprefill_scores_from_partials",
            "uniprefill_status_string"]
 
 UP_PHASE_PLAN, UP_PHASE_ROW_STATS, UP_PHASE_MERGE_STATS, UP_PHASE_SWEEP_SELECT, UP_PHASE_GATHER = 1, 2, 4, 8, 16
@@ -220,6 +221,22 @@ def uniprefill_fused_top_p_lse(p, q, k, lse, lse_row_stride, hidden, pos, cu_seq
                                          ptr(new_cu_seqlens_dev), ptr(scores), ptr(workspace), workspace_bytes,
                                          _stream(stream))
     return _check(st, "uniprefill_fused_top_p_lse", check)
+
+
+def uniprefill_score_partial(p, q, k, cu_seqlens_dev, cu_seqlens_host, cu_seqlens_k_dev, cu_seqlens_k_host, colsum_out,
+                             workspace, workspace_bytes, stream=None, check=True):
+    st = _lib.uniprefill_score_partial(ctypes.byref(p), ptr(q), ptr(k), ptr(cu_seqlens_dev), ptr(cu_seqlens_host),
+                                       ptr(cu_seqlens_k_dev), ptr(cu_seqlens_k_host), ptr(colsum_out), ptr(workspace),
+                                       workspace_bytes, _stream(stream))
+    return _check(st, "uniprefill_score_partial", check)
+
+
+def uniprefill_scores_from_partials(partials, num_parts, part_stride, cu_seqlens_dev, num_seqs, total_tokens, n_obs,
+                                    total_q_heads, scores_out, stream=None, check=True):
+    st = _lib.uniprefill_scores_from_partials(ptr(partials), int(num_parts), ctypes.c_int64(part_stride),
+                                              ptr(cu_seqlens_dev), int(num_seqs), int(total_tokens), int(n_obs),
+                                              int(total_q_heads), ptr(scores_out), _stream(stream))
+    return _check(st, "uniprefill_scores_from_partials", check)
 
 
 def uniprefill_keep_mask(kept_idx, capacity, total_kept_dev, total_tokens, mask_out, stream=None, check=True):

@@ -255,13 +255,14 @@ int optional_key_side(const int32_t* cu_k_dev, const int32_t* cu_k_host, const P
 
 int score_impl(const up_params* p, const void* q, const void* k, const int32_t* cu_dev,
                const int32_t* cu_host, const KeySide& ks, float* scores_out, void* workspace,
-               size_t workspace_bytes, void* stream, const float* lse = nullptr, long long lse_stride = 0) {
+               size_t workspace_bytes, void* stream, const float* lse = nullptr, long long lse_stride = 0,
+               double* colsum_out = nullptr) {
   const int32_t* cu_k_dev = ks.cu_k_dev;
   const int32_t* cu_k_host = ks.cu_k_host;
   Problem pb;
   int st = check_params(p, true, false, &pb);
   if (st != UP_OK) return st;
-  if (!cu_dev || (pb.T > 0 && (!q || !k || !scores_out))) return UP_ERR_NULL;
+  if (!cu_dev || (pb.T > 0 && (!q || !k || (!scores_out && !colsum_out)))) return UP_ERR_NULL;
   if ((st = check_cu(p, cu_host)) != UP_OK) return st;
   if ((st = check_key_side(p, cu_host, ks)) != UP_OK) return st;
   if (lse != nullptr && lse_stride < pb.T) return UP_ERR_SHAPE;      // the heads of lse would overlap
@@ -277,7 +278,8 @@ int score_impl(const up_params* p, const void* q, const void* k, const int32_t* 
     if (launch_row_stats(pb, q, k, cu_dev, cu_k_dev, ks.paged, workspace, s) != hipSuccess) return UP_ERR_HIP;
     if (launch_merge_stats(pb, cu_dev, cu_k_dev, workspace, nullptr, nullptr, s) != hipSuccess) return UP_ERR_HIP;
   }
-  if (launch_column_sums(pb, q, k, cu_dev, cu_k_dev, ks.paged, workspace, scores_out, nullptr, s) != hipSuccess)
+  if (launch_column_sums(pb, q, k, cu_dev, cu_k_dev, ks.paged, workspace, scores_out, nullptr, s, colsum_out) !=
+      hipSuccess)
     return UP_ERR_HIP;
   return UP_OK;
 }
@@ -724,6 +726,35 @@ int uniprefill_fused_top_p_lse(const up_params* p, const void* q, const void* k,
   return fused_top_p_impl(p, q, k, hidden, pos, cu_seqlens_dev, cu_seqlens_host, ks, top_p_dev, top_p_host,
                           hidden_out, pos_out, kept_idx, new_cu_seqlens_dev, scores, workspace, workspace_bytes,
                           stream, lse, lse_row_stride);
+}
+
+int uniprefill_score_partial(const up_params* p, const void* q, const void* k,
+                             const int32_t* cu_seqlens_dev, const int32_t* cu_seqlens_host,
+                             const int32_t* cu_seqlens_k_dev, const int32_t* cu_seqlens_k_host,
+                             double* colsum_out, void* workspace, size_t workspace_bytes, void* stream) {
+  if (p != nullptr && p->total_tokens > 0 && colsum_out == nullptr) return UP_ERR_NULL;
+  if ((reinterpret_cast<uintptr_t>(colsum_out) & 7u) != 0) return UP_ERR_ALIGN;
+  const PagedKeys none{nullptr, 0, 1};
+  KeySide ks;
+  const int st = optional_key_side(cu_seqlens_k_dev, cu_seqlens_k_host, &none, &ks);
+  if (st != UP_OK) return st;
+  return score_impl(p, q, k, cu_seqlens_dev, cu_seqlens_host, ks, nullptr, workspace, workspace_bytes, stream,
+                    nullptr, 0, colsum_out);
+}
+
+int uniprefill_scores_from_partials(const double* partials, int32_t num_parts, int64_t part_stride,
+                                    const int32_t* cu_seqlens_dev, int32_t num_seqs, int32_t total_tokens,
+                                    int32_t n_obs, int32_t total_q_heads, float* scores_out, void* stream) {
+  if (num_parts < 1 || num_seqs < 0 || total_tokens < 0 || n_obs < 1 || total_q_heads < 1 ||
+      part_stride < total_tokens)
+    return UP_ERR_RANGE;
+  if (total_tokens == 0) return UP_OK;
+  if (!partials || !cu_seqlens_dev || !scores_out) return UP_ERR_NULL;
+  if ((reinterpret_cast<uintptr_t>(partials) & 7u) != 0) return UP_ERR_ALIGN;
+  if (launch_scores_from_partials(partials, num_parts, part_stride, cu_seqlens_dev, num_seqs, total_tokens, n_obs,
+                                  total_q_heads, scores_out, (hipStream_t)stream) != hipSuccess)
+    return UP_ERR_HIP;
+  return UP_OK;
 }
 
 int uniprefill_fused_paged(const up_params* p, const void* q, const void* k_cache, const void* hidden,

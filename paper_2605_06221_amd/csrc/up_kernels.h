@@ -134,8 +134,13 @@ hipError_t launch_lse_stats(const Problem& pb, const int32_t* cu, const int32_t*
 // pass 2: normalised weights summed per token; optional scores_out; sel != nullptr runs the
 // block-local top-k (in the same kernel when every key block has one work-group, otherwise in
 // k_finish)
+// colsum_out != nullptr: also the raw column sums in double (always through k_finish)
 hipError_t launch_column_sums(const Problem& pb, const void* q, const void* k, const int32_t* cu,
                               const int32_t* cu_k, const PagedKeys* paged, void* workspace, float* scores_out,
-                              const SelectArgs* sel, hipStream_t s);
+                              const SelectArgs* sel, hipStream_t s, double* colsum_out = nullptr);
+// scores from the tensor-parallel ranks' partial column sums (Eq. 15): parts added in rank order
+hipError_t launch_scores_from_partials(const double* partials, int num_parts, long long part_stride,
+                                       const int32_t* cu, int R, int T, int n_obs, int total_q_heads,
+                                       float* scores, hipStream_t s);
 
 }  // namespace up

@@ -74,6 +74,7 @@ struct SweepArgs {
   float2* stat_part;   // [key_block_slots][Hq * n_obs]  (reference in log2 units, sum)
   float2* stat_fin;    // [Hq][row_slots]                 (negative reference, 1/sum)
   float* scores_out;   // pass 2: optional
+  double* colsum_out;  // pass 2 through k_finish: optional, the raw column sums (a rank's share, Eq. 15)
   double* o_part;      // pass 2, via_finish: [pass-2 slots][split][keys per block] partial column sums
   long long q_stride_b, k_stride_b;   // bytes between tokens
   float c;             // scale * log2(e)
@@ -532,6 +533,7 @@ __global__ __launch_bounds__(256) void k_finish(SweepArgs a, int key_block) {   
       const double* part0 = a.o_part + (size_t)slot2 * a.split * key_block + (key - kblock * key_block);
       double sum = 0.0;
       for (int pp = 0; pp < a.split; ++pp) sum += part0[(size_t)pp * key_block];
+      if (a.colsum_out != nullptr) a.colsum_out[c0 + tok] = sum;
       const double o = sum / (double)(imin(a.n_obs, N) * a.Hq);
       sc = o < 0x1p-64 ? 0.0f : (float)o;
       if (a.scores_out != nullptr) a.scores_out[c0 + tok] = sc;
@@ -665,6 +667,31 @@ hipError_t launch_lse_stats(const Problem& pb, const int32_t* cu, const int32_t*
   return hipGetLastError();
 }
 
+// Scores from the ranks' partial column sums (Eq. 15, then the means of Eq. 3 and the floor):
+// the parts are added in rank order, so every rank that runs this gets the same bits.
+__global__ __launch_bounds__(256) void k_scores_from_partials(const double* __restrict__ partials, int num_parts,
+                                                              long long part_stride, const int32_t* __restrict__ cu,
+                                                              int R, int T, int n_obs, int total_q_heads,
+                                                              float* __restrict__ scores) {
+  const int t = blockIdx.x * 256 + threadIdx.x;
+  if (t >= T) return;
+  const int r = locate_token(cu, R, t);
+  const int N = cu[r + 1] - cu[r];
+  double sum = 0.0;
+  for (int pp = 0; pp < num_parts; ++pp) sum += partials[(long long)pp * part_stride + t];
+  const double o = sum / (double)((long long)imin(n_obs, N) * total_q_heads);
+  scores[t] = o < 0x1p-64 ? 0.0f : (float)o;
+}
+
+hipError_t launch_scores_from_partials(const double* partials, int num_parts, long long part_stride,
+                                       const int32_t* cu, int R, int T, int n_obs, int total_q_heads,
+                                       float* scores, hipStream_t s) {
+  if (T == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_scores_from_partials, dim3((unsigned)((T + 255) / 256)), dim3(256), 0, s, partials, num_parts,
+                     part_stride, cu, R, T, n_obs, total_q_heads, scores);
+  return hipGetLastError();
+}
+
 Workspace workspace_layout(const Problem& pb) {
   auto al = [](size_t x) { return (x + 255) & ~(size_t)255; };
   Workspace w;
@@ -688,7 +715,8 @@ Workspace workspace_layout(const Problem& pb) {
   w.stat_fin_off = off;
   off = al(off + (size_t)pb.row_slots * pb.Hq * sizeof(float2));
   w.o_part_off = off;
-  if (pb.via_finish) off = al(off + (size_t)pb.key_block_slots2 * pb.split2 * pb.key_block2 * sizeof(double));
+  // (always there: a call that wants the raw column sums goes through k_finish whatever the split)
+  off = al(off + (size_t)pb.key_block_slots2 * pb.split2 * pb.key_block2 * sizeof(double));
   w.total = off;
   return w;
 }
@@ -770,16 +798,18 @@ hipError_t launch_merge_stats(const Problem& pb, const int32_t* cu, const int32_
 
 hipError_t launch_column_sums(const Problem& pb, const void* q, const void* k, const int32_t* cu,
                               const int32_t* cu_k, const PagedKeys* paged, void* workspace, float* scores_out,
-                              const SelectArgs* sel, hipStream_t s) {
+                              const SelectArgs* sel, hipStream_t s, double* colsum_out) {
   if (pb.T == 0) return hipSuccess;
   SweepArgs a = make_sweep_args(pb, q, k, cu, cu_k, workspace, paged);
   a.split = pb.split2;
   a.scores_out = scores_out;
+  a.colsum_out = colsum_out;
+  if (colsum_out != nullptr) a.via_finish = 1;
   if (sel != nullptr) { a.sel = *sel; a.do_select = 1; }
   else { a.sel.G = pb.G; a.sel.cu_k = nullptr; }
   const hipError_t e = launch_sweep<2>(pb, a, s);
   if (e != hipSuccess) return e;
-  if (pb.via_finish)
+  if (a.via_finish)
     hipLaunchKernelGGL(k_finish, dim3((unsigned)(pb.T / pb.G + pb.R)), dim3(256), 0, s, a, pb.key_block2);
   return hipGetLastError();
 }

@@ -1186,3 +1186,70 @@ def test_batches_without_tokens():
     up.uniprefill_fused(p0, None, None, None, None, cu0, cu0_host, None, None, None, None, None, out0, None, None, 0)
     torch.cuda.synchronize()
     np.testing.assert_array_equal(out0.cpu().numpy(), [0, -77, -77, -77])
+
+
+@pytest.mark.parametrize("earlier", [None, [700, 0, 64]])
+def test_tensor_parallel_shares_add_up_to_the_single_device_result(earlier):
+    """Eq. 15 on one device: the heads are split over four ranks (two query heads and their kv head
+    each, read as views into the full rows), every rank leaves its partial sums, the sums are
+    combined in rank order, and the scores and the selection are those of the whole model."""
+    _say("tensor-parallel shares", earlier)
+    lengths = [3000, 40, 2500]
+    Hq, Hkv, D, ranks = 8, 4, 128, 4
+    w = workloads.make_custom(name="tp", seed=29, lengths=lengths, keep_ratio=[0.3, 0.5, 0.4], hidden_dim=64,
+                              num_q_heads=Hq, num_kv_heads=Hkv, block_size=64, n_obs=128, earlier=earlier)
+    T = w.total_tokens
+    whole = DeviceBatch(w)
+    q_all, k_all = whole.q, whole.k
+    p_rank = up.make_params(num_seqs=w.num_seqs, total_tokens=T, block_size=w.block_size, n_obs=w.n_obs, n_sink=w.n_sink,
+                            num_q_heads=Hq // ranks, num_kv_heads=Hkv // ranks, head_dim=D, hidden_dim=w.hidden_dim,
+                            q_row_stride=Hq * D, k_row_stride=Hkv * D)
+    cu_k_host = whole.cu_k_host if earlier else None
+    cu_k = whole.cu_k if earlier else None
+    if earlier:
+        _, _, _, ws_bytes = up.uniprefill_plan_chunked(p_rank, whole.cu_host, cu_k_host, whole.ratio_host)
+    else:
+        _, _, _, ws_bytes = up.uniprefill_plan(p_rank, whole.cu_host, whole.ratio_host)
+    workspace = torch.empty(ws_bytes + 256, dtype=torch.uint8, device="cuda")
+    partials = torch.full((ranks, T + 8), -7.0, dtype=torch.float64, device="cuda")
+    for t in range(ranks):
+        q_view = q_all[:, t * (Hq // ranks):, :]          # the rank's heads start here; the row stride stays the full row
+        k_view = k_all[:, t * (Hkv // ranks):, :]
+        up.uniprefill_score_partial(p_rank, q_view, k_view, whole.cu, whole.cu_host, cu_k, cu_k_host, partials[t],
+                                    workspace, ws_bytes)
+    torch.cuda.synchronize()
+    assert bool((partials[:, T:] == -7.0).all())
+    # every rank's sums against the oracle's for that share
+    kf = workloads.bf16_bits_to_f32(w.k)
+    ck = w.cu_seqlens_k if earlier else w.cu_seqlens
+    refs = []
+    for t in range(ranks):
+        ref = oracle.importance_sums(_ShardQ(w.q, t * (Hq // ranks), Hq // ranks), kf[:, t:t + 1, :], w.cu_seqlens, ck, n_obs=w.n_obs)
+        refs.append(ref)
+        got = partials[t, :T].cpu().numpy()
+        assert (np.abs(got - ref) <= 1e-5 * ref + 2.0 ** -64).all()
+    scores = torch.full((T + 64,), -7.0, dtype=torch.float32, device="cuda")
+    up.uniprefill_scores_from_partials(partials, ranks, T + 8, whole.cu, w.num_seqs, T, w.n_obs, Hq, scores)
+    torch.cuda.synchronize()
+    want = oracle.quantise_scores(oracle.scores_from_partial_sums(refs, w.cu_seqlens, n_obs=w.n_obs, total_q_heads=Hq))
+    ok, worst = _score_close(scores[:T].cpu().numpy(), want)
+    _say("  worst relative score error", worst)
+    assert ok and bool((scores[T:] == -7.0).all())
+    # the selection on the combined scores is the single-device selection
+    whole.fused()
+    single = whole.results()
+    whole.kept_idx.fill_(-77)
+    whole.select(scores[:T])
+    np.testing.assert_array_equal(whole.results()["kept_idx"], single["kept_idx"])
+    np.testing.assert_array_equal(single["kept_idx"], oracle_run(w)["kept_idx"])
+
+
+class _ShardQ:
+    """Window rows of a head shard of w.q, upcast on demand (the oracle slices rows only)."""
+
+    def __init__(self, bits, h0, nh):
+        self.bits, self.h0, self.nh = bits, h0, nh
+        self.shape = (bits.shape[0], nh, bits.shape[2])
+
+    def __getitem__(self, item):
+        return workloads.bf16_bits_to_f32(self.bits[item][:, self.h0:self.h0 + self.nh, :])

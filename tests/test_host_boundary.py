@@ -342,3 +342,17 @@ def test_fused_lse_rejects_bad_arguments():
     assert call(ckd=fake, ckh=up.ptr(np.array([0, 99, 400], np.int32))) == up.UP_ERR_SHAPE
     assert call(ckd=fake, ckh=up.ptr(cu_k), table=fake) == up.UP_ERR_ALIGN    # all fine up to the odd workspace
     assert call() == up.UP_ERR_ALIGN
+
+
+def test_scores_from_partials_rejects_bad_arguments():
+    L = up.lib()
+    fake = ctypes.c_void_p(0x1000)
+    call = lambda parts, n, stride, T, heads, out: L.uniprefill_scores_from_partials(parts, n, ctypes.c_int64(stride), fake, 2, T,
+                                                                                      128, heads, out, None)
+    assert call(fake, 0, 100, 100, 8, fake) == up.UP_ERR_RANGE
+    assert call(fake, 2, 99, 100, 8, fake) == up.UP_ERR_RANGE       # the parts would overlap
+    assert call(fake, 2, 100, 100, 0, fake) == up.UP_ERR_RANGE
+    assert call(fake, 2, 100, 0, 8, fake) == up.UP_OK               # nothing to do, nothing launched
+    assert call(None, 2, 100, 100, 8, fake) == up.UP_ERR_NULL
+    assert call(fake, 2, 100, 100, 8, None) == up.UP_ERR_NULL
+    assert call(ctypes.c_void_p(0x1004), 2, 100, 100, 8, fake) == up.UP_ERR_ALIGN
