@@ -60,19 +60,41 @@ def _load():
     lib = ctypes.CDLL(LIB_PATH)
     vp, i32p, f32p = ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p
     P = ctypes.POINTER(up_params)
-    lib.uniprefill_plan.argtypes = [P, i32p, f32p, i32p, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_size_t)]
-    lib.uniprefill_score.argtypes = [P, vp, vp, i32p, i32p, f32p, vp, ctypes.c_size_t, vp]
+    i64, i32, sz = ctypes.c_int64, ctypes.c_int32, ctypes.c_size_t
+    ws = [vp, sz]                                   # workspace, workspace_bytes
+    keys = [i32p, i32p]                             # cu_seqlens_k_dev, cu_seqlens_k_host
+    table = [i32p, i64, i32]                        # block_table, block_table_stride, kv_block_size
+    outs = [vp, i32p, i32p, i32p, f32p]             # hidden_out, pos_out, kept_idx, new_cu_seqlens_dev, scores
+    lib.uniprefill_plan.argtypes = [P, i32p, f32p, i32p, ctypes.POINTER(i64), ctypes.POINTER(sz)]
+    lib.uniprefill_plan_chunked.argtypes = [P, i32p, i32p, f32p, i32p, ctypes.POINTER(i64), ctypes.POINTER(sz)]
+    lib.uniprefill_score.argtypes = [P, vp, vp, i32p, i32p, f32p] + ws + [vp]
+    lib.uniprefill_score_chunked.argtypes = [P, vp, vp, i32p, i32p] + keys + [f32p] + ws + [vp]
+    lib.uniprefill_score_paged.argtypes = [P, vp, vp, i32p, i32p] + keys + table + [f32p] + ws + [vp]
+    lib.uniprefill_score_lse.argtypes = [P, vp, vp, f32p, i64, i32p, i32p] + keys + table + [f32p] + ws + [vp]
+    lib.uniprefill_score_partial.argtypes = [P, vp, vp, i32p, i32p] + keys + [vp] + ws + [vp]
+    lib.uniprefill_scores_from_partials.argtypes = [vp, i32, i64, i32p, i32, i32, i32, i32, f32p, vp]
     lib.uniprefill_select.argtypes = [P, f32p, i32p, i32p, f32p, f32p, i32p, i32p, vp]
-    lib.uniprefill_compact.argtypes = [P, vp, i32p, i32p, ctypes.c_int64, vp, i32p, vp]
-    lib.uniprefill_scatter.argtypes = [P, vp, i32p, ctypes.c_int64, vp, vp]
-    lib.uniprefill_fused.argtypes = [P, vp, vp, vp, i32p, i32p, i32p, f32p, f32p, vp, i32p, i32p, i32p, f32p, vp, ctypes.c_size_t, vp]
-    lib.uniprefill_fused_phases.argtypes = lib.uniprefill_fused.argtypes[:-1] + [ctypes.c_int, vp]
-    lib.uniprefill_select_top_p.argtypes = [P, f32p, i32p, i32p, f32p, f32p, i32p, i32p, vp, ctypes.c_size_t, vp]
-    lib.uniprefill_compact_counted.argtypes = [P, vp, i32p, i32p, i32p, ctypes.c_int64, vp, i32p, vp]
-    lib.uniprefill_fused_top_p.argtypes = lib.uniprefill_fused.argtypes
-    lib.uniprefill_compose_index.argtypes = [i32p, ctypes.c_int64, i32p, i32p, ctypes.c_int64, i32p, vp]
-    lib.uniprefill_slot_mapping.argtypes = [i32p, i32p, ctypes.c_int32, i32p, ctypes.c_int64, ctypes.c_int32,
-                                            ctypes.c_int64, vp, vp]
+    lib.uniprefill_select_chunked.argtypes = [P, f32p, i32p, i32p] + keys + [f32p, f32p, i32p, i32p, vp]
+    lib.uniprefill_select_top_p.argtypes = [P, f32p, i32p, i32p, f32p, f32p, i32p, i32p] + ws + [vp]
+    lib.uniprefill_select_top_p_chunked.argtypes = [P, f32p, i32p, i32p] + keys + [f32p, f32p, i32p, i32p] + ws + [vp]
+    lib.uniprefill_compact.argtypes = [P, vp, i32p, i32p, i64, vp, i32p, vp]
+    lib.uniprefill_compact_counted.argtypes = [P, vp, i32p, i32p, i32p, i64, vp, i32p, vp]
+    lib.uniprefill_compact_column.argtypes = [vp, i32, i32p, i64, i32p, vp, vp]
+    lib.uniprefill_scatter.argtypes = [P, vp, i32p, i64, vp, vp]
+    fused_in = [P, vp, vp, vp, i32p, i32p, i32p]    # params, q, k, hidden, pos, cu_seqlens_dev, cu_seqlens_host
+    lib.uniprefill_fused.argtypes = fused_in + [f32p, f32p] + outs + ws + [vp]
+    lib.uniprefill_fused_phases.argtypes = fused_in + [f32p, f32p] + outs + ws + [ctypes.c_int, vp]
+    lib.uniprefill_fused_chunked.argtypes = fused_in + keys + [f32p, f32p] + outs + ws + [vp]
+    lib.uniprefill_fused_paged.argtypes = fused_in + keys + table + [f32p, f32p] + outs + ws + [vp]
+    lib.uniprefill_fused_top_p.argtypes = fused_in + [f32p, f32p] + outs + ws + [vp]
+    lib.uniprefill_fused_top_p_chunked.argtypes = fused_in + keys + table + [f32p, f32p] + outs + ws + [vp]
+    lse_in = [P, vp, vp, f32p, i64, vp, i32p, i32p, i32p]   # params, q, k, lse, lse_row_stride, hidden, pos, cu dev/host
+    lib.uniprefill_fused_lse.argtypes = lse_in + keys + table + [f32p, f32p] + outs + ws + [vp]
+    lib.uniprefill_fused_top_p_lse.argtypes = lse_in + keys + table + [f32p, f32p] + outs + ws + [vp]
+    lib.uniprefill_compose_index.argtypes = [i32p, i64, i32p, i32p, i64, i32p, vp]
+    lib.uniprefill_slot_mapping.argtypes = [i32p, i32p, i32, i32p, i64, i32, i64, vp, vp]
+    lib.uniprefill_keep_mask.argtypes = [i32p, i64, i32p, i64, vp, vp]
+    lib.uniprefill_seqused.argtypes = [i32p, i32, i32p, i32p, i32p, i32, i32, i32p, vp]
     for name in EXPORTS[:-1]:
         getattr(lib, name).restype = ctypes.c_int
     lib.uniprefill_status_string.argtypes = [ctypes.c_int]

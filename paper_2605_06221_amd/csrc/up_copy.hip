@@ -46,8 +46,9 @@ __global__ __launch_bounds__(256) void k_rows(const char* __restrict__ src, char
                                               const int32_t* __restrict__ count_dev) {
   const int lane = threadIdx.x & 63;
   const long long t = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
-  // (count_dev: the number of rows lives on the device; the launch covers the capacity)
-  if (t >= (count_dev != nullptr ? (long long)count_dev[0] : total_kept)) return;
+  // (count_dev: the number of rows lives on the device; the launch covers the capacity, which
+  // also bounds the output buffers whatever the device count says)
+  if (t >= total_kept || (count_dev != nullptr && t >= (long long)count_dev[0])) return;
   const long long row = idx[t];
   if (SCATTER) {
     copy_row_wave(src + t * stride_bytes, dst + row * stride_bytes, row_bytes, lane);
@@ -63,7 +64,7 @@ __global__ __launch_bounds__(256) void k_compose(const int32_t* __restrict__ out
                                                  const int32_t* __restrict__ count_dev,
                                                  int32_t* __restrict__ out) {
   const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
-  if (t >= (count_dev != nullptr ? (long long)count_dev[0] : n)) return;
+  if (t >= n || (count_dev != nullptr && t >= (long long)count_dev[0])) return;
   out[t] = outer[inner[t]];
 }
 

@@ -80,6 +80,42 @@ def test_compact_with_padded_row_stride_and_empty_selection():
     torch.cuda.synchronize()
 
 
+def test_counted_copies_never_write_past_the_capacity():
+    """The row count on the device may exceed the capacity the caller sized its buffers for
+    (a stale or foreign counter): the copies stop at the capacity, whose launch is rounded up to
+    whole work-groups (4 rows, 256 index entries)."""
+    _say("counted copies clamp to the capacity")
+    rng = np.random.default_rng(7)
+    T, d, cap = 300, 64, 37                                  # 37 % 4 != 0
+    h = rng.integers(0, 65536, (T, d)).astype(np.uint16)
+    pos = rng.integers(0, 1 << 20, T).astype(np.int32)
+    kept = np.sort(rng.choice(T, 64, replace=False)).astype(np.int32)
+    p = up.make_params(num_seqs=1, total_tokens=T, block_size=32, hidden_dim=d)
+    count = torch.tensor([50], dtype=torch.int32, device="cuda")     # more than the capacity
+    out = torch.full((cap + 8, d), -7.0, dtype=torch.bfloat16, device="cuda")
+    pos_out = torch.full((cap + 8,), -77, dtype=torch.int32, device="cuda")
+    kd = torch.from_numpy(kept).cuda()
+    up.uniprefill_compact_counted(p, dev_bf16(h), torch.from_numpy(pos).cuda(), kd, count, cap, out, pos_out)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(host_bits(out[:cap]), oracle.compact(h, pos, kept[:cap])[0])
+    np.testing.assert_array_equal(pos_out[:cap].cpu().numpy(), pos[kept[:cap]])
+    assert (out[cap:] == -7.0).all() and (pos_out[cap:] == -77).all()
+    # index-map composition: capacity 37 of a 256-entry launch, device count above it
+    outer = rng.integers(0, 1 << 20, T).astype(np.int32)
+    composed = torch.full((cap + 300,), -77, dtype=torch.int32, device="cuda")
+    up.uniprefill_compose_index(torch.from_numpy(outer).cuda(), T, kd, count, cap, composed)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(composed[:cap].cpu().numpy(), oracle.compose_index(outer, kept[:cap]))
+    assert (composed[cap:] == -77).all()
+    # a device count below the capacity still wins
+    count.fill_(5)
+    out.fill_(-7.0)
+    up.uniprefill_compact_counted(p, dev_bf16(h), None, kd, count, cap, out, None)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(host_bits(out[:5]), h[kept[:5]])
+    assert (out[5:] == -7.0).all()
+
+
 # ----------------------------------------------------------------------------- select
 def _select_case(rng, G, n_obs, n_sink, R, maxlen, kind):
     lengths = rng.integers(0, maxlen, R)

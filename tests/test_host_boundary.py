@@ -356,3 +356,52 @@ def test_scores_from_partials_rejects_bad_arguments():
     assert call(None, 2, 100, 100, 8, fake) == up.UP_ERR_NULL
     assert call(fake, 2, 100, 100, 8, None) == up.UP_ERR_NULL
     assert call(ctypes.c_void_p(0x1004), 2, 100, 100, 8, fake) == up.UP_ERR_ALIGN
+
+
+def test_every_export_declares_its_argument_types():
+    """No entry point is left to ctypes' default int conversion (which would truncate a
+    size_t or an int64 argument to 32 bits)."""
+    L = up.lib()
+    for name in up.EXPORTS:
+        fn = getattr(L, name)
+        assert fn.argtypes is not None, name
+    header = open(os.path.join(ROOT, "include", "uniprefill.h")).read()
+    # the number of declared parameters equals the number of argtypes
+    for name in up.EXPORTS:
+        m = re.search(r"\b" + name + r"\s*\(([^;]*?)\)\s*;", header, re.S)
+        assert m, name
+        n_params = len([a for a in m.group(1).split(",") if a.strip()])
+        assert n_params == len(getattr(L, name).argtypes), (name, n_params, len(getattr(L, name).argtypes))
+
+
+def test_a_short_workspace_is_refused_through_every_wrapper_that_takes_one():
+    """Sizes of 2 GiB and more reach the library intact (size_t), and a workspace that is too
+    small comes back as UP_ERR_WORKSPACE through the chunked, paged and lse wrappers too."""
+    cu = np.array([0, 1000], np.int32)
+    cu_k = np.array([0, 3000], np.int32)
+    ratio = np.array([0.5], np.float32)
+    fake = 0x1000
+    table = 0x2000
+    p = _params()
+    W = up.UP_ERR_WORKSPACE
+    big = (1 << 32) + 16            # would read as 16 if truncated to 32 bits: the library must see the real size
+    for ws_bytes in (16,):            # (only refusals are exercised: a call that passed every check would launch)
+        assert up.uniprefill_score_chunked(p, fake, fake, fake, cu, fake, cu_k, fake, fake, ws_bytes, stream=0, check=False) == W
+        assert up.uniprefill_score_paged(p, fake, fake, fake, cu, fake, cu_k, table, 256, 16, fake, fake, ws_bytes,
+                                         stream=0, check=False) == W
+        assert up.uniprefill_fused_chunked(p, fake, fake, fake, None, fake, cu, fake, cu_k, fake, ratio, fake, None, fake,
+                                           fake, None, fake, ws_bytes, stream=0, check=False) == W
+        assert up.uniprefill_fused_paged(p, fake, fake, fake, None, fake, cu, fake, cu_k, table, 256, 16, fake, ratio, fake,
+                                         None, fake, fake, None, fake, ws_bytes, stream=0, check=False) == W
+        assert up.uniprefill_score_lse(p, fake, fake, fake, 1000, fake, cu, None, None, None, 0, 16, fake, fake, ws_bytes,
+                                       stream=0, check=False) == W
+        assert up.uniprefill_fused_lse(p, fake, fake, fake, 1000, fake, None, fake, cu, None, None, None, 0, 16, fake, ratio,
+                                       fake, None, fake, fake, None, fake, ws_bytes, stream=0, check=False) == W
+        assert up.uniprefill_score_partial(p, fake, fake, fake, cu, None, None, fake, fake, ws_bytes, stream=0,
+                                           check=False) == W
+        assert up.uniprefill_select_top_p_chunked(p, fake, fake, cu, fake, cu_k, fake, ratio, fake, fake, fake, 8,
+                                                  stream=0, check=False) == W
+    # a size above 4 GiB is not truncated on its way in: with a misaligned workspace pointer the
+    # call gets past the size check (truncated it would fail it) and is refused for the alignment
+    assert up.uniprefill_score_chunked(p, fake, fake, fake, cu, fake, cu_k, fake, 0x1010, big, stream=0,
+                                       check=False) == up.UP_ERR_ALIGN
