@@ -232,21 +232,20 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem<NW, F3
   // per-row tables of a unit: threads 0..127 take one row each; fetched with the rows, written with them
   float2 pre_cst = make_float2(-INFINITY, 0.0f);
   int pre_pos = -1;
-  // (every thread issues the load -- threads 128.. repeat rows 0..127 -- so that the number of
-  // loads in flight is the same on every path and the wait for the key operands, which are
-  // older, does not have to cover them)
+  // (every thread issues the load -- threads 128.. repeat rows 0..127, a unit's missing rows read
+  // row 0 -- and nothing looks at the value before stash_meta: the load's latency stays behind
+  // the unit's matrix work, and the number of loads in flight is the same on every path, so the
+  // wait for the key operands, which are older, does not have to cover them)
   auto fetch_meta = [&](const UnitCursor& uc) {
     int hh, jj;
     const bool have = unit_row(uc, tid & (kUnit - 1), hh, jj);
     pre_pos = have ? first_pos + jj : -1;
-    if (PASS == 2) {
-      const float2 v = a.stat_fin[(size_t)(uc.g * a.Gq + hh) * a.row_slots + rs0 + jj];
-      pre_cst = have ? v : make_float2(-INFINITY, 0.0f);   // no such row: weight exactly zero
-    }
+    if (PASS == 2) pre_cst = a.stat_fin[(size_t)(uc.g * a.Gq + hh) * a.row_slots + rs0 + jj];
   };
   auto stash_meta = [&](int tb) {
     if (tid < kUnit) {
-      if (PASS == 2) sm.cst[tb][tid] = pre_cst;
+      // no such row: weight exactly zero
+      if (PASS == 2) sm.cst[tb][tid] = pre_pos >= 0 ? pre_cst : make_float2(-INFINITY, 0.0f);
       sm.rowpos[tb][tid] = pre_pos;
     }
   };
@@ -255,7 +254,9 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem<NW, F3
 
   // ---- one tile = 32 staged rows (row tile rt of buffer buf, tables tb) against the wave's 32 keys;
   // MASK: some (row, key) pairs of the tile are not visible (key after the row, or past the end)
-  auto tile = [&](auto mask_tag, int buf, int tb, int rt) {
+  // (reload: this is the kv head's last tile; once its MFMAs are issued the key registers are free
+  // and the next head's keys are fetched under this tile's vector work)
+  auto tile = [&](auto mask_tag, int buf, int tb, int rt, bool reload, int next_g) {
     constexpr bool MASK = decltype(mask_tag)::value;
     u32x4 qv[KREG];
 #pragma unroll
@@ -285,6 +286,7 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem<NW, F3
         acc = PASS == 1 ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kf[kk]), as_bf16x8(qv[kk]), acc, 0, 0, 0)
                         : __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(qv[kk]), as_bf16x8(kf[kk]), acc, 0, 0, 0);
     }
+    if (reload) load_keys(next_g);
     if (PASS == 1) {
       // element e = key 8*(e/4) + 4*half + e%4 of the wave's keys, query row rt*32 + l32
       if (MASK) {
@@ -406,8 +408,9 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem<NW, F3
       // for unit f+1 only after the barrier below, which every wave reaches after its merge)
       if (PASS == 1 && f > 0 && rt == 1) merge_load(buf ^ 1);
       if (PASS == 1 && f > 0 && rt == 2) merge_finish(prev);
+      const bool reload = head_ends && rt == 3;
       if (!EDGE) {
-        tile(std::false_type{}, buf, buf, rt);
+        tile(std::false_type{}, buf, buf, rt, reload, cur.g + 1);
       } else {
         // the wave's 32 keys against the tile's rows: all visible, none visible, or mixed.  When a
         // unit holds consecutive window rows of one head the row positions of a tile are a known
@@ -425,10 +428,11 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem<NW, F3
             if (HS) sm.wstat[buf][2 * wave + half][rt * 32 + l32] = make_float2(-INFINITY, 0.0f);
             else if (half == 0) sm.wstat[buf][wave][rt * 32 + l32] = make_float2(-INFINITY, 0.0f);
           }
+          if (reload) load_keys(cur.g + 1);
         } else if (mixed) {
-          tile(std::true_type{}, buf, buf, rt);
+          tile(std::true_type{}, buf, buf, rt, reload, cur.g + 1);
         } else {
-          tile(std::false_type{}, buf, buf, rt);
+          tile(std::false_type{}, buf, buf, rt, reload, cur.g + 1);
         }
       }
       // tiles stay apart: neither the compiler nor the scheduler may pull the next tile's table
@@ -437,7 +441,6 @@ __device__ __forceinline__ void sweep_block(const SweepArgs& a, SweepSmem<NW, F3
       __builtin_amdgcn_sched_barrier(0);
     }
     if (more) { stash_unit(buf ^ 1); stash_meta(buf ^ 1); }
-    if (head_ends) load_keys(cur.g + 1);                    // this head's last MFMA has been issued
     __syncthreads();     // unit f+1 is visible; every read of unit f's rows and tables has completed
     prev = cur;
     cur = nxt;
