@@ -36,6 +36,8 @@
  *                          in bytes is not a multiple of 16
  *       UP_ERR_WORKSPACE   workspace is NULL or smaller than uniprefill_plan says
  *       UP_ERR_HIP         a launch failed (hipGetLastError after the launch)
+ *       UP_ERR_SCRATCH     uniprefill_fused_static only: the call needs more scratch
+ *                          memory than the library's static buffer holds
  *   - Zero-length sequences are legal and produce nothing; total_tokens == 0 is
  *     legal: the per-token arrays (q, k, hidden, scores, kept_idx, outputs) may
  *     then be NULL, and only new_cu_seqlens_dev is written (all zero).  A copy
@@ -65,7 +67,8 @@ typedef enum {
   UP_ERR_UNSUPPORTED = 4,
   UP_ERR_ALIGN = 5,
   UP_ERR_WORKSPACE = 6,
-  UP_ERR_HIP = 7
+  UP_ERR_HIP = 7,
+  UP_ERR_SCRATCH = 8
 } up_status;
 
 typedef enum { UP_BF16 = 0, UP_F32 = 1 } up_dtype;
@@ -160,6 +163,28 @@ int uniprefill_fused(const up_params* p, const void* q, const void* k, const voi
                      const float* keep_ratio_host, void* hidden_out, int32_t* pos_out,
                      int32_t* kept_idx, int32_t* new_cu_seqlens_dev, float* scores_out,
                      void* workspace, size_t workspace_bytes, void* stream);
+
+/* uniprefill_fused for callers that cannot allocate device memory (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the same call, the
+ * same kernels and the same results, with the workspace inside the library instead of an
+ * argument -- a static device array of UNIPREFILL_STATIC_SCRATCH_BYTES that every GPU the
+ * library runs on holds until the process ends.  The call allocates and frees nothing.
+ *   - A batch whose workspace (what uniprefill_plan reports) exceeds that size is refused
+ *     with UP_ERR_SCRATCH before anything is launched: use uniprefill_fused then.
+ *   - `stream` must belong to the current device.  The first call on a device looks the
+ *     array's address up (no allocation; not to be made under stream capture); later
+ *     calls only enqueue.
+ *   - All calls on one GPU share that GPU's array: calls that may overlap there (two
+ *     streams, two threads) race and must be serialised by the caller.  Nothing in the
+ *     array has to start at zero or survive between calls: every word a kernel reads was
+ *     written earlier in the same call. */
+#define UNIPREFILL_STATIC_SCRATCH_BYTES (32u << 20)
+int uniprefill_fused_static(const up_params* p, const void* q, const void* k, const void* hidden,
+                            const int32_t* pos, const int32_t* cu_seqlens_dev,
+                            const int32_t* cu_seqlens_host, const float* keep_ratio_dev,
+                            const float* keep_ratio_host, void* hidden_out, int32_t* pos_out,
+                            int32_t* kept_idx, int32_t* new_cu_seqlens_dev, float* scores_out,
+                            void* stream);
 
 /* Block-level top-p selection, the rule of Eq. 4-6: inside each sequence the
  * blocks of G tokens are ordered by their mass (sum of the token scores; packed

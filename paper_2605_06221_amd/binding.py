@@ -15,7 +15,8 @@ import numpy as np
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libuniprefill.so")
 
-UP_OK, UP_ERR_NULL, UP_ERR_SHAPE, UP_ERR_RANGE, UP_ERR_UNSUPPORTED, UP_ERR_ALIGN, UP_ERR_WORKSPACE, UP_ERR_HIP = range(8)
+UP_OK, UP_ERR_NULL, UP_ERR_SHAPE, UP_ERR_RANGE, UP_ERR_UNSUPPORTED, UP_ERR_ALIGN, UP_ERR_WORKSPACE, UP_ERR_HIP, UP_ERR_SCRATCH = range(9)
+STATIC_SCRATCH_BYTES = 32 << 20
 UP_BF16, UP_F32 = 0, 1
 
 EXPORTS = ["uniprefill_plan", "uniprefill_score", "uniprefill_select", "uniprefill_compact",
@@ -26,7 +27,7 @@ EXPORTS = ["uniprefill_plan", "uniprefill_score", "uniprefill_select", "uniprefi
            "uniprefill_score_paged", "uniprefill_fused_paged", "uniprefill_select_top_p_chunked",
            "uniprefill_fused_top_p_chunked", "uniprefill_keep_mask", "uniprefill_fused_lse",
            "uniprefill_score_lse", "uniprefill_fused_top_p_lse", "uniprefill_score_partial",
-           "uniprefill_scores_from_partials",
+           "uniprefill_scores_from_partials", "uniprefill_fused_static",
            "uniprefill_status_string"]
 
 UP_PHASE_PLAN, UP_PHASE_ROW_STATS, UP_PHASE_MERGE_STATS, UP_PHASE_SWEEP_SELECT, UP_PHASE_GATHER = 1, 2, 4, 8, 16
@@ -83,6 +84,7 @@ def _load():
     lib.uniprefill_scatter.argtypes = [P, vp, i32p, i64, vp, vp]
     fused_in = [P, vp, vp, vp, i32p, i32p, i32p]    # params, q, k, hidden, pos, cu_seqlens_dev, cu_seqlens_host
     lib.uniprefill_fused.argtypes = fused_in + [f32p, f32p] + outs + ws + [vp]
+    lib.uniprefill_fused_static.argtypes = fused_in + [f32p, f32p] + outs + [vp]
     lib.uniprefill_fused_phases.argtypes = fused_in + [f32p, f32p] + outs + ws + [ctypes.c_int, vp]
     lib.uniprefill_fused_chunked.argtypes = fused_in + keys + [f32p, f32p] + outs + ws + [vp]
     lib.uniprefill_fused_paged.argtypes = fused_in + keys + table + [f32p, f32p] + outs + ws + [vp]
@@ -198,6 +200,15 @@ def uniprefill_fused(p, q, k, hidden, pos, cu_seqlens_dev, cu_seqlens_host, keep
                                ptr(hidden_out), ptr(pos_out), ptr(kept_idx), ptr(new_cu_seqlens_dev),
                                ptr(scores_out), ptr(workspace), workspace_bytes, _stream(stream))
     return _check(st, "uniprefill_fused", check)
+
+
+def uniprefill_fused_static(p, q, k, hidden, pos, cu_seqlens_dev, cu_seqlens_host, keep_ratio_dev, keep_ratio_host,
+                            hidden_out, pos_out, kept_idx, new_cu_seqlens_dev, scores_out, stream=None, check=True):
+    st = _lib.uniprefill_fused_static(ctypes.byref(p), ptr(q), ptr(k), ptr(hidden), ptr(pos), ptr(cu_seqlens_dev),
+                                      ptr(cu_seqlens_host), ptr(keep_ratio_dev), ptr(keep_ratio_host),
+                                      ptr(hidden_out), ptr(pos_out), ptr(kept_idx), ptr(new_cu_seqlens_dev),
+                                      ptr(scores_out), _stream(stream))
+    return _check(st, "uniprefill_fused_static", check)
 
 
 def uniprefill_compact_column(column, elem_bytes, kept_idx, capacity, total_kept_dev, column_out, stream=None,

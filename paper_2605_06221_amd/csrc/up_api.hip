@@ -5,6 +5,8 @@
 
 #include <math.h>
 
+#include <atomic>
+
 #include "up_common.h"
 #include "up_kernels.h"
 #include "up_select.h"
@@ -426,6 +428,27 @@ int fused_top_p_impl(const up_params* p, const void* q, const void* k, const voi
                                     pos_out, stream);
 }
 
+// ---- scratch memory of the call that allocates nothing (uniprefill_fused_static): a static
+// device array; every GPU holds its own copy at its own address, looked up once per device.
+// In host code the array's name is only a handle for hipGetSymbolAddress -- kernels get the
+// address that call returns.
+static __device__ __align__(256) unsigned char scratch[UNIPREFILL_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+int static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return UP_ERR_HIP;
+  void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (ptr == nullptr) {
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return UP_ERR_HIP;
+    g_scratch_ptr[dev].store(ptr, std::memory_order_release);     // (a racing first call stores the same address)
+  }
+  *out = ptr;
+  return UP_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -784,6 +807,27 @@ int uniprefill_fused(const up_params* p, const void* q, const void* k, const voi
                                  UP_PHASE_ALL, stream);
 }
 
+int uniprefill_fused_static(const up_params* p, const void* q, const void* k, const void* hidden,
+                            const int32_t* pos, const int32_t* cu_seqlens_dev,
+                            const int32_t* cu_seqlens_host, const float* keep_ratio_dev,
+                            const float* keep_ratio_host, void* hidden_out, int32_t* pos_out,
+                            int32_t* kept_idx, int32_t* new_cu_seqlens_dev, float* scores_out,
+                            void* stream) {
+  // what the call needs, from the same closed forms as uniprefill_plan (host only)
+  size_t need = 0;
+  const int st = plan_impl(p, cu_seqlens_host, nullptr, false, keep_ratio_host, nullptr, nullptr, &need);
+  if (st != UP_OK) return st;
+  if (need > (size_t)UNIPREFILL_STATIC_SCRATCH_BYTES) return UP_ERR_SCRATCH;
+  void* ws = nullptr;
+  if (p->total_tokens > 0) {      // (a batch without tokens touches no workspace)
+    const int sw = static_scratch(&ws);
+    if (sw != UP_OK) return sw;
+  }
+  return fused_impl(p, q, k, hidden, pos, cu_seqlens_dev, cu_seqlens_host, kOwnKeys, keep_ratio_dev, keep_ratio_host,
+                    hidden_out, pos_out, kept_idx, new_cu_seqlens_dev, scores_out, ws,
+                    (size_t)UNIPREFILL_STATIC_SCRATCH_BYTES, UP_PHASE_ALL, stream);
+}
+
 const char* uniprefill_status_string(int status) {
   switch (status) {
     case UP_OK: return "ok";
@@ -794,6 +838,7 @@ const char* uniprefill_status_string(int status) {
     case UP_ERR_ALIGN: return "pointer or row stride not 16-byte aligned";
     case UP_ERR_WORKSPACE: return "workspace missing or too small";
     case UP_ERR_HIP: return "kernel launch failed";
+    case UP_ERR_SCRATCH: return "the library's static scratch buffer is too small for this call";
     default: return "unknown status";
   }
 }

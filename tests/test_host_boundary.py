@@ -30,8 +30,8 @@ def test_library_exports_every_symbol_declared_in_the_header():
 
 
 def test_status_strings():
-    seen = {up.status_string(i) for i in range(8)}
-    assert len(seen) == 8 and up.status_string(0) == "ok"
+    seen = {up.status_string(i) for i in range(9)}
+    assert len(seen) == 9 and up.status_string(0) == "ok"
     assert up.status_string(99) == "unknown status"
 
 
@@ -405,3 +405,27 @@ def test_a_short_workspace_is_refused_through_every_wrapper_that_takes_one():
     # call gets past the size check (truncated it would fail it) and is refused for the alignment
     assert up.uniprefill_score_chunked(p, fake, fake, fake, cu, fake, cu_k, fake, 0x1010, big, stream=0,
                                        check=False) == up.UP_ERR_ALIGN
+
+
+def test_fused_static_refuses_what_its_scratch_cannot_hold():
+    """The call that allocates nothing checks its arguments and the size of its static scratch
+    buffer on the host, before it touches the device."""
+    fake = 0x1000
+    # 3000 short sequences of 350 tokens: the plan asks for more than the static buffer
+    R = 3000
+    cu = (np.arange(R + 1) * 350).astype(np.int32)
+    ratio = np.full(R, 0.5, np.float32)
+    p = _params(num_seqs=R, total_tokens=int(cu[-1]), num_q_heads=32, num_kv_heads=8, hidden_dim=256)
+    _, _, _, ws = up.uniprefill_plan(p, cu, ratio)
+    assert ws > up.STATIC_SCRATCH_BYTES
+    call = lambda p_, cu_, ratio_: up.uniprefill_fused_static(p_, fake, fake, fake, None, fake, cu_, fake, ratio_, fake, None,
+                                                              fake, fake, None, stream=0, check=False)
+    assert call(p, cu, ratio) == up.UP_ERR_SCRATCH
+    # argument errors come first, as in the other entries
+    small = _params()
+    cu1 = np.array([0, 1000], np.int32)
+    assert call(small, np.array([0, 999], np.int32), np.array([0.5], np.float32)) == up.UP_ERR_SHAPE
+    assert call(small, cu1, np.array([1.5], np.float32)) == up.UP_ERR_RANGE
+    assert call(_params(head_dim=96), cu1, np.array([0.5], np.float32)) == up.UP_ERR_UNSUPPORTED
+    with pytest.raises(up.UniPrefillError, match="static scratch"):
+        up.uniprefill_fused_static(p, fake, fake, fake, None, fake, cu, fake, ratio, fake, None, fake, fake, None, stream=0)
