@@ -347,8 +347,11 @@ int fused_impl(const up_params* p, const void* q, const void* k, const void* hid
   if ((phase_mask & UP_PHASE_PLAN) && !plan_in_merge &&
       launch_plan(pb, cu_dev, cu_k_dev, ratio_dev, new_cu_dev, s) != hipSuccess)
     return UP_ERR_HIP;
+  // sequences that are kept whole (every token a sink or in the window: decode rows, short requests)
+  // are not scored when the caller wants no scores
+  const bool skip_forced = scores_out == nullptr;
   if ((phase_mask & UP_PHASE_ROW_STATS) &&
-      launch_row_stats(pb, q, k, cu_dev, cu_k_dev, ks.paged, workspace, s) != hipSuccess)
+      launch_row_stats(pb, q, k, cu_dev, cu_k_dev, ks.paged, workspace, s, skip_forced) != hipSuccess)
     return UP_ERR_HIP;
   if ((phase_mask & UP_PHASE_MERGE_STATS) &&
       launch_merge_stats(pb, cu_dev, cu_k_dev, workspace, plan_in_merge ? ratio_dev : nullptr,
@@ -356,7 +359,8 @@ int fused_impl(const up_params* p, const void* q, const void* k, const void* hid
     return UP_ERR_HIP;
   if (phase_mask & UP_PHASE_SWEEP_SELECT) {
     const SelectArgs sa = make_select_args(pb, nullptr, cu_dev, cu_k_dev, ratio_dev, new_cu_dev, kept_idx);
-    if (launch_column_sums(pb, q, k, cu_dev, cu_k_dev, ks.paged, workspace, scores_out, &sa, s) != hipSuccess)
+    if (launch_column_sums(pb, q, k, cu_dev, cu_k_dev, ks.paged, workspace, scores_out, &sa, s, nullptr, skip_forced) !=
+        hipSuccess)
       return UP_ERR_HIP;
   }
   if (phase_mask & UP_PHASE_GATHER) {

@@ -120,8 +120,11 @@ struct PagedKeys {
 // pass 1: softmax statistics of every window row per key block (into the workspace)
 // (cu_k as above; the kernels take cu itself where it is nullptr)
 // (paged: nullptr when the keys are packed by cu / cu_k)
+// (skip_forced: sequences that are kept whole whatever their scores are left out -- for a call
+// that selects and returns no scores; both passes must agree on it)
 hipError_t launch_row_stats(const Problem& pb, const void* q, const void* k, const int32_t* cu,
-                            const int32_t* cu_k, const PagedKeys* paged, void* workspace, hipStream_t s);
+                            const int32_t* cu_k, const PagedKeys* paged, void* workspace, hipStream_t s,
+                            bool skip_forced = false);
 // merge of the per-block statistics into one (reference, 1/sum) per row; with plan_ratio given
 // the same launch also does what launch_plan does (into plan_new_cu)
 hipError_t launch_merge_stats(const Problem& pb, const int32_t* cu, const int32_t* cu_k, void* workspace,
@@ -137,7 +140,8 @@ hipError_t launch_lse_stats(const Problem& pb, const int32_t* cu, const int32_t*
 // colsum_out != nullptr: also the raw column sums in double (always through k_finish)
 hipError_t launch_column_sums(const Problem& pb, const void* q, const void* k, const int32_t* cu,
                               const int32_t* cu_k, const PagedKeys* paged, void* workspace, float* scores_out,
-                              const SelectArgs* sel, hipStream_t s, double* colsum_out = nullptr);
+                              const SelectArgs* sel, hipStream_t s, double* colsum_out = nullptr,
+                              bool skip_forced = false);
 // scores from the tensor-parallel ranks' partial column sums (Eq. 15): parts added in rank order
 hipError_t launch_scores_from_partials(const double* partials, int num_parts, long long part_stride,
                                        const int32_t* cu, int R, int T, int n_obs, int total_q_heads,

@@ -83,6 +83,9 @@ struct SweepArgs {
   int spare2;          // pass 2 numbers its key blocks by the tokens: slots per sequence beyond N / KB
   int via_finish;      // pass 2 ends with the partial column sums; k_finish forms scores and selects
   int do_select;       // pass 2: run the block-local top-k
+  int skip_forced;     // sequences kept whole whatever their scores (N <= sinks + window; never set with earlier
+                       // context) are not scored: the caller selects and wants no scores
+  int n_sink;
   SelectArgs sel;
 };
 
@@ -475,11 +478,17 @@ __global__ __launch_bounds__(64 * NW) void k_sweep(SweepArgs a) {
                                : (Lk - N) / KB + slot - slot_base(c0, r, KB, a.spare2);
   if (kblock * KB >= Lk || N == 0) return;
   const int n_eff = imin(a.n_obs, N);
+  // a sequence of which every token is a sink or in the window (a decode row, a short request) is
+  // kept whole whatever its scores: when only the selection is wanted it is not scored at all
+  const bool unscored = a.skip_forced && N <= a.n_sink + a.n_obs;
+  if (unscored && (PASS == 1 || a.via_finish)) return;
   // causal masking and the ragged end only matter where keys reach the query window
   const bool edge = (kblock + 1) * KB - 1 > Lk - n_eff;
   const int n_heads = a.Hkv / a.split;
-  if (edge) sweep_block<PASS, true, NW, F32, D>(a, sm, r, c0, N, ck0, Lk, kblock, slot, part * n_heads, n_heads);
-  else sweep_block<PASS, false, NW, F32, D>(a, sm, r, c0, N, ck0, Lk, kblock, slot, part * n_heads, n_heads);
+  if (!unscored) {
+    if (edge) sweep_block<PASS, true, NW, F32, D>(a, sm, r, c0, N, ck0, Lk, kblock, slot, part * n_heads, n_heads);
+    else sweep_block<PASS, false, NW, F32, D>(a, sm, r, c0, N, ck0, Lk, kblock, slot, part * n_heads, n_heads);
+  }
 
   if (PASS == 2) {
     __syncthreads();
@@ -494,7 +503,7 @@ __global__ __launch_bounds__(64 * NW) void k_sweep(SweepArgs a) {
     float sc = 0.0f;
     if (tid < KB) {
       const int key = kblock * KB + tid;
-      if (key < N) {
+      if (key < N && !unscored) {
         const double o = sm.tail.o64[tid] / (double)(n_eff * a.Hq);
         sc = o < 0x1p-64 ? 0.0f : (float)o;
         if (a.scores_out != nullptr) a.scores_out[c0 + key] = sc;
@@ -527,7 +536,7 @@ __global__ __launch_bounds__(256) void k_finish(SweepArgs a, int key_block) {   
   const int tok = g * G + tid;
   if (tid < G) {
     float sc = 0.0f;
-    if (tok < N) {
+    if (tok < N && !(a.skip_forced && N <= a.n_sink + a.n_obs)) {      // (an unscored sequence left no sums)
       const int ck0 = a.cu_k[r];
       const int earlier = (a.cu_k[r + 1] - ck0) - N;
       const int key = earlier + tok;                       // the token's place among the sequence's keys
@@ -735,6 +744,7 @@ static SweepArgs make_sweep_args(const Problem& pb, const void* q, const void* k
   a.stat_fin = (float2*)(ws + w.stat_fin_off);
   a.scores_out = nullptr;
   a.o_part = (double*)(ws + w.o_part_off);
+  a.n_sink = pb.n_sink;
   a.split = pb.split;              // (pass 2 overwrites it)
   a.spare2 = pb.spare2;
   a.via_finish = pb.via_finish;
@@ -775,9 +785,11 @@ static hipError_t launch_sweep(const Problem& pb, const SweepArgs& a, hipStream_
 }
 
 hipError_t launch_row_stats(const Problem& pb, const void* q, const void* k, const int32_t* cu,
-                            const int32_t* cu_k, const PagedKeys* paged, void* workspace, hipStream_t s) {
+                            const int32_t* cu_k, const PagedKeys* paged, void* workspace, hipStream_t s,
+                            bool skip_forced) {
   if (pb.T == 0) return hipSuccess;
-  const SweepArgs a = make_sweep_args(pb, q, k, cu, cu_k, workspace, paged);
+  SweepArgs a = make_sweep_args(pb, q, k, cu, cu_k, workspace, paged);
+  a.skip_forced = skip_forced && !pb.has_ctx;
   return launch_sweep<1>(pb, a, s);
 }
 
@@ -801,13 +813,14 @@ hipError_t launch_merge_stats(const Problem& pb, const int32_t* cu, const int32_
 
 hipError_t launch_column_sums(const Problem& pb, const void* q, const void* k, const int32_t* cu,
                               const int32_t* cu_k, const PagedKeys* paged, void* workspace, float* scores_out,
-                              const SelectArgs* sel, hipStream_t s, double* colsum_out) {
+                              const SelectArgs* sel, hipStream_t s, double* colsum_out, bool skip_forced) {
   if (pb.T == 0) return hipSuccess;
   SweepArgs a = make_sweep_args(pb, q, k, cu, cu_k, workspace, paged);
   a.split = pb.split2;
   a.scores_out = scores_out;
   a.colsum_out = colsum_out;
   if (colsum_out != nullptr) a.via_finish = 1;
+  a.skip_forced = skip_forced && sel != nullptr && scores_out == nullptr && colsum_out == nullptr && !pb.has_ctx;
   if (sel != nullptr) { a.sel = *sel; a.do_select = 1; }
   else { a.sel.G = pb.G; a.sel.cu_k = nullptr; }
   const hipError_t e = launch_sweep<2>(pb, a, s);

@@ -428,14 +428,88 @@ def test_fused_without_scores_and_repeatability():
     ref = oracle_run(w)
     np.testing.assert_array_equal(first["kept_idx"], ref["kept_idx"])
     np.testing.assert_array_equal(first["hidden_out"], ref["hidden_out"])
-    for _ in range(5):
+    b.fused(want_scores=True)
+    s1 = b.results()["scores"].copy()
+    for _ in range(100):       # the same call a hundred times: the same bits every time (no float atomics, fixed orders)
         b.fused(want_scores=True)
         again = b.results()
         np.testing.assert_array_equal(again["kept_idx"], first["kept_idx"])
         np.testing.assert_array_equal(again["hidden_out"], first["hidden_out"])
-    s1 = again["scores"].copy()
-    b.fused(want_scores=True)
-    np.testing.assert_array_equal(b.results()["scores"], s1)    # bitwise repeatable, no float atomics
+        np.testing.assert_array_equal(again["scores"].view(np.uint32), s1.view(np.uint32))
+
+
+def test_sequences_kept_whole_are_not_scored_when_no_scores_are_wanted():
+    """Decode rows and short requests (every token a sink or in the window) are kept verbatim by the
+    forced-retention rule; with scores_out = NULL the call must not even read their q and k --
+    they are poisoned with NaN here -- and the other sequences must come out as the oracle says."""
+    _say("sequences kept whole: not scored")
+    lengths = [1, 1, 3000, 256, 1, 200, 0, 1300, 255, 1]
+    ratio = [0.5, 1.0, 0.3, 0.25, 0.4, 0.6, 0.5, 0.45, 0.2, 0.3]
+    w = workloads.make_custom(name="forced", seed=33, lengths=lengths, keep_ratio=ratio, hidden_dim=128,
+                              num_q_heads=8, num_kv_heads=4, block_size=64, n_obs=128, n_sink=128)
+    ref = oracle_run(w)
+    q, k = w.q.copy(), w.k.copy()
+    cu = w.cu_seqlens
+    for r, N in enumerate(lengths):
+        if N <= 256:
+            q[cu[r]:cu[r + 1]] = 0x7FC0
+            k[cu[r]:cu[r + 1]] = 0x7FC0
+    w.q, w.k = q, k
+    b = DeviceBatch(w)
+    b.fused(want_scores=False)
+    res = b.results()
+    np.testing.assert_array_equal(res["new_cu_seqlens"], ref["new_cu_seqlens"])
+    np.testing.assert_array_equal(res["kept_idx"], ref["kept_idx"])
+    np.testing.assert_array_equal(res["hidden_out"], ref["hidden_out"])
+    np.testing.assert_array_equal(res["pos_out"], ref["pos_out"])
+    assert b.canaries_intact()
+    for r, N in enumerate(lengths):          # ... and those sequences are there whole
+        if N <= 256:
+            got = res["kept_idx"][ref["new_cu_seqlens"][r]:ref["new_cu_seqlens"][r + 1]]
+            np.testing.assert_array_equal(got, np.arange(cu[r], cu[r + 1]))
+
+
+def test_fused_with_fp32_hidden_rows_and_padded_row_strides():
+    """The fused call with every row stride larger than the row (q, k and hidden are views into wider
+    buffers) and hidden states in float32: indices, rows and positions bit for bit, scores in tolerance;
+    the padding of the outputs is never written."""
+    _say("fused: fp32 hidden rows, padded strides")
+    w = workloads.make_custom(name="strides", seed=44, lengths=[2500, 70, 1100], keep_ratio=[0.3, 0.5, 0.6],
+                              hidden_dim=96, num_q_heads=8, num_kv_heads=2, block_size=64, n_obs=128)
+    ref = oracle_run(w)
+    T, Hq, Hkv, D, d = w.total_tokens, 8, 2, 128, 96
+    rng = np.random.default_rng(5)
+    qs, ks, hs = Hq * D + 64, Hkv * D + 8, d + 12             # row strides in elements (multiples of 16 bytes)
+    q_wide = np.full((T, qs), 0x7FC0, np.uint16); q_wide[:, :Hq * D] = w.q.reshape(T, -1)
+    k_wide = np.full((T, ks), 0x7FC0, np.uint16); k_wide[:, :Hkv * D] = w.k.reshape(T, -1)
+    hidden_f32 = rng.standard_normal((T, d)).astype(np.float32)
+    h_wide = np.full((T, hs), np.nan, np.float32); h_wide[:, :d] = hidden_f32
+    p = up.make_params(num_seqs=w.num_seqs, total_tokens=T, block_size=64, n_obs=128, n_sink=128, num_q_heads=Hq,
+                       num_kv_heads=Hkv, head_dim=D, hidden_dim=d, q_row_stride=qs, k_row_stride=ks,
+                       hidden_row_stride=hs, hidden_dtype=up.UP_F32)
+    cu_host = np.ascontiguousarray(w.cu_seqlens, np.int32)
+    ratio_host = np.ascontiguousarray(w.keep_ratio, np.float32)
+    _, new_cu_plan, K, ws_bytes = up.uniprefill_plan(p, cu_host, ratio_host)
+    assert K == len(ref["kept_idx"])
+    out = torch.full((K + 8, hs), -7.0, dtype=torch.float32, device="cuda")
+    pos_out = torch.full((K + 8,), -77, dtype=torch.int32, device="cuda")
+    kept = torch.full((K + 8,), -77, dtype=torch.int32, device="cuda")
+    new_cu = torch.full((w.num_seqs + 1 + 8,), -77, dtype=torch.int32, device="cuda")
+    scores = torch.full((T + 8,), -7.0, dtype=torch.float32, device="cuda")
+    workspace = torch.empty(ws_bytes + 256, dtype=torch.uint8, device="cuda")
+    up.uniprefill_fused(p, dev_bf16(q_wide), dev_bf16(k_wide), torch.from_numpy(h_wide).cuda(), torch.from_numpy(w.pos).cuda(),
+                        torch.from_numpy(cu_host).cuda(), cu_host, torch.from_numpy(ratio_host).cuda(), ratio_host, out,
+                        pos_out, kept, new_cu, scores, workspace, ws_bytes)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(kept[:K].cpu().numpy(), ref["kept_idx"])
+    np.testing.assert_array_equal(new_cu[:w.num_seqs + 1].cpu().numpy(), ref["new_cu_seqlens"])
+    np.testing.assert_array_equal(pos_out[:K].cpu().numpy(), ref["pos_out"])
+    got = out.cpu().numpy()
+    np.testing.assert_array_equal(got[:K, :d].view(np.uint32), hidden_f32[ref["kept_idx"]].view(np.uint32))
+    assert (got[:K, d:] == -7.0).all() and (got[K:] == -7.0).all()          # padding and canary rows untouched
+    assert (kept[K:] == -77).all() and (pos_out[K:] == -77).all() and (scores[T:] == -7.0).all()
+    want = ref["scores"].astype(np.float64)
+    assert (np.abs(scores[:T].cpu().numpy() - want) <= SCORE_RTOL * want + SCORE_ATOL).all()
 
 
 def test_fused_identity_at_ratio_one_and_varlen_concat():
