@@ -24,18 +24,37 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 
-# HBM bytes per launch (reads + writes) from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE, each scaled by
-# what the same counter reads for an identity gather of known size in the same run; the summaries
-# with the commands are under profiles/.  Keyed by (workload, kernel); absent = not measured.
-MEASURED_TRAFFIC_BYTES = {
-    ("c4_128k_d5120_h40x8_G128_r0.25_heavytail", "sweep_select"): 278641119,
-    ("c4_128k_d5120_h40x8_G128_r0.25_heavytail", "gather"): 675674297,
-    ("c4_128k_d5120_h40x8_G128_r0.25_heavytail", "row_stats"): 299183924,
-    ("c2_32k_d4096_h32x8_G128_r0.3", "row_stats"): 75373459,
-    ("c2_32k_d4096_h32x8_G128_r0.3", "sweep_select"): 71325158,      # pass 2 and k_finish
-    ("c3_16varlen_d4096_h32x8_G128", "row_stats"): 661189224,
-    ("c3_16varlen_d4096_h32x8_G128", "sweep_select"): 627980771,     # pass 2 and k_finish
-}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+
+
+def csrc_digest():
+    """SHA-256 over the kernel sources: what a counter measurement is valid for."""
+    import hashlib
+    d = os.path.join(ROOT, "paper_2605_06221_amd", "csrc")
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(d)):
+        if name.endswith((".hip", ".h")):
+            h.update(name.encode())
+            h.update(open(os.path.join(d, name), "rb").read())
+    return h.hexdigest()
+
+
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch (reads + writes) of one kernel on one workload, from the rocprofv3 counter
+    runs recorded in profiles/hbm_traffic.json (FETCH_SIZE and WRITE_SIZE, each scaled by what the same
+    counter reads for an identity gather of known size in the same run).  The record names the profile
+    summary it comes from and the digest of the kernel sources it was measured on; a record taken on
+    other sources is not reported.  Returns (bytes or None, provenance dict or None)."""
+    try:
+        rec = json.load(open(TRAFFIC_FILE))
+    except (OSError, ValueError):
+        return None, None
+    ent = rec.get("bytes", {}).get(workload, {}).get(kernel)
+    if ent is None:
+        return None, None
+    prov = {"profile": rec.get("profiles", {}).get(workload), "csrc_sha256": rec.get("csrc_sha256"),
+            "stale": rec.get("csrc_sha256") != csrc_digest()}
+    return (None if prov["stale"] else int(ent)), prov
 
 
 def algorithmic_bytes(w, total_kept):
@@ -142,6 +161,172 @@ def bench_chunked(args, up, workloads, np, torch):
         "oracle_parity": parity}), flush=True)
 
 
+class Resident:
+    """One workload in HBM with its outputs and workspace, and the fused call on it."""
+
+    def __init__(self, w, up, np, torch, input_sets):
+        self.w, self.up, self.np, self.torch = w, up, np, torch
+        self.cu_host = np.ascontiguousarray(w.cu_seqlens, dtype=np.int32)
+        self.ratio_host = np.ascontiguousarray(w.keep_ratio, dtype=np.float32)
+        self.p = up.make_params(num_seqs=w.num_seqs, total_tokens=w.total_tokens, block_size=w.block_size,
+                                n_obs=w.n_obs, n_sink=w.n_sink, num_q_heads=w.num_q_heads,
+                                num_kv_heads=w.num_kv_heads, head_dim=w.head_dim, hidden_dim=w.hidden_dim)
+        _, self.new_cu_plan, self.total_kept, self.ws_bytes = up.uniprefill_plan(self.p, self.cu_host, self.ratio_host)
+        dev_bf16 = lambda bits: torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+        self.q, self.k, self.hidden = dev_bf16(w.q), dev_bf16(w.k), dev_bf16(w.hidden)
+        self.pos = torch.from_numpy(w.pos).cuda()
+        self.cu = torch.from_numpy(self.cu_host).cuda()
+        self.ratio = torch.from_numpy(self.ratio_host).cuda()
+        self.workspace = torch.empty(self.ws_bytes, dtype=torch.uint8, device="cuda")
+        self.hidden_out = torch.empty((self.total_kept, w.hidden_dim), dtype=torch.bfloat16, device="cuda")
+        self.pos_out = torch.empty(self.total_kept, dtype=torch.int32, device="cuda")
+        self.kept_idx = torch.empty(self.total_kept, dtype=torch.int32, device="cuda")
+        self.new_cu = torch.empty(w.num_seqs + 1, dtype=torch.int32, device="cuda")
+        self.scores = torch.empty(w.total_tokens, dtype=torch.float32, device="cuda")
+        self.stream = torch.cuda.current_stream()
+        # identical copies of the large inputs: step i reads copy i % n, which the steps in between
+        # have pushed out of the caches
+        self.n_sets = max(1, input_sets)
+        self.sets = [(self.q, self.k, self.hidden)] + [(self.q.clone(), self.k.clone(), self.hidden.clone())
+                                                       for _ in range(self.n_sets - 1)]
+
+    def call_args(self, i):
+        qi, ki, hi = self.sets[i % self.n_sets]
+        return (self.p, qi, ki, hi, self.pos, self.cu, self.cu_host, self.ratio, self.ratio_host, self.hidden_out,
+                self.pos_out, self.kept_idx, self.new_cu, self.scores, self.workspace, self.ws_bytes)
+
+    def time_fused(self, steps, warmup):
+        """W untimed calls, then exactly K calls between two synchronisations (wall clock), with an event
+        after every call for the spread of the single steps."""
+        torch, up = self.torch, self.up
+        for i in range(warmup):
+            up.uniprefill_fused(*self.call_args(i), stream=self.stream)
+        torch.cuda.synchronize()
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+        t_start = time.perf_counter()
+        marks[0].record(self.stream)
+        for i in range(steps):
+            up.uniprefill_fused(*self.call_args(warmup + i), stream=self.stream)
+            marks[i + 1].record(self.stream)
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t_start
+        per_step_us = sorted(marks[i].elapsed_time(marks[i + 1]) * 1e3 for i in range(steps))
+        pick = lambda f: round(per_step_us[min(len(per_step_us) - 1, int(f * len(per_step_us)))], 2)
+        return elapsed / steps, {"median": pick(0.5), "p10": pick(0.1), "p90": pick(0.9)}
+
+    def time_phases(self, steps):
+        """The launches of the fused call one by one (uniprefill_fused_phases), each bracketed by events on
+        the launch stream: average microseconds per kernel, launch gap included."""
+        torch, up = self.torch, self.up
+        phases = [("plan", up.UP_PHASE_PLAN), ("row_stats", up.UP_PHASE_ROW_STATS),
+                  ("merge_stats", up.UP_PHASE_MERGE_STATS),
+                  ("sweep_select", up.UP_PHASE_SWEEP_SELECT), ("gather", up.UP_PHASE_GATHER)]
+        acc = {name: 0.0 for name, _ in phases}
+        for it in range(steps):
+            evs = [torch.cuda.Event(enable_timing=True) for _ in range(len(phases) + 1)]
+            evs[0].record(self.stream)
+            for i, (name, mask) in enumerate(phases):
+                up.uniprefill_fused_phases(*self.call_args(it), mask, stream=self.stream)
+                evs[i + 1].record(self.stream)
+            torch.cuda.synchronize()
+            for i, (name, _) in enumerate(phases):
+                acc[name] += evs[i].elapsed_time(evs[i + 1])
+        return {name: acc[name] / steps * 1e3 for name, _ in phases}
+
+    def kernel_table(self, phase_us):
+        """Per-kernel figures: the sweeps against the dense bf16 MFMA peak (flops of one Q.K^T pass) and
+        against HBM (K once; pass 2 also scores and kept ids), the gather against HBM."""
+        w = self.w
+        flops = product_flops(w)
+        gather_only_bytes = self.total_kept * (2 * w.hidden_dim * 2 + 12)      # rows in and out, pos in/out, index
+        score_bytes = w.total_tokens * 4 + self.total_kept * 4
+        k_bytes = w.total_tokens * w.num_kv_heads * w.head_dim * 2
+        kernels = {}
+        for name, us in phase_us.items():
+            ent = {"avg_us": round(us, 2)}
+            if name in ("row_stats", "sweep_select"):
+                ent.update(bound="mfma", tflops=round(flops / (us * 1e-6) / 1e12, 1),
+                           frac_mfma=round(flops / (us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4))
+                moved = k_bytes + (score_bytes if name == "sweep_select" else 0)
+                ent.update(gbs=round(moved / (us * 1e-6) / 1e9, 1),
+                           frac_hbm=round(moved / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4))
+            if name == "gather":
+                ent.update(bound="hbm", gbs=round(gather_only_bytes / (us * 1e-6) / 1e9, 1),
+                           frac_hbm=round(gather_only_bytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4))
+            kernels[name] = ent
+        return kernels
+
+    def against_oracle(self):
+        """The results of the last fused call against the fp64 CPU oracle on the same inputs: bit-exact
+        kept rows / compacted tensors / positions / offsets, the worst relative score error, and the
+        margin the exactness rests on -- the smallest relative gap, over all selection blocks, between
+        the last kept and the first dropped oracle score (exact ties of the quantised scores aside)."""
+        np, torch = self.np, self.torch
+        sys.path.insert(0, os.path.join(ROOT, "tests"))
+        from gpu_util import oracle_run, score_margin_report      # test infrastructure: the fp64 numpy oracle
+        t1 = time.perf_counter()
+        ref = oracle_run(self.w)
+        cpu_s = time.perf_counter() - t1
+        torch.cuda.synchronize()
+        K, R = self.total_kept, self.w.num_seqs
+        parity = bool(np.array_equal(self.kept_idx.cpu().numpy(), ref["kept_idx"])
+                      and np.array_equal(self.hidden_out.view(torch.int16).cpu().numpy().view(np.uint16), ref["hidden_out"])
+                      and np.array_equal(self.pos_out.cpu().numpy(), ref["pos_out"])
+                      and np.array_equal(self.new_cu.cpu().numpy(), ref["new_cu_seqlens"]))
+        got = self.scores.cpu().numpy().astype(np.float64)
+        want = ref["scores"].astype(np.float64)
+        nz = want > 0
+        rel = float(np.max(np.abs(got[nz] - want[nz]) / want[nz])) if nz.any() else 0.0
+        zeros_agree = bool(np.array_equal(got[~nz], want[~nz]))
+        margin = float(score_margin_report(ref, self.w))
+        return {"oracle_parity": parity, "max_score_rel_err": rel, "floored_scores_agree": zeros_agree,
+                "min_selection_margin": (None if margin == float("inf") else margin),
+                "oracle_seconds": round(cpu_s, 2)}, ref
+
+
+def summarise(res, sec_per_step):
+    w = res.w
+    alg_bytes = algorithmic_bytes(w, res.total_kept)
+    flops = product_flops(w)
+    return {
+        "total_tokens": w.total_tokens, "num_seqs": w.num_seqs, "total_kept": int(res.total_kept),
+        "ms_per_step": round(sec_per_step * 1e3, 4),
+        "tokens_per_s": round(w.total_tokens / sec_per_step, 1),
+        "algorithmic_bytes": int(alg_bytes),
+        "hbm_frac": round(alg_bytes / sec_per_step / 1e9 / HBM_PEAK_GBS, 4),
+        # the larger of (algorithmic bytes at HBM peak, the two product passes at the dense bf16 MFMA
+        # peak) over the measured step time
+        "binding_roofline_frac": round(max(alg_bytes / (HBM_PEAK_GBS * 1e9), 2.0 * flops / (MFMA_BF16_PEAK_TFLOPS * 1e12))
+                                       / sec_per_step, 4),
+    }
+
+
+def bench_sweep(args, up, workloads, np, torch):
+    """Operator-only timing tables (the shapes of the paper's block-size, window and context/batch
+    studies): block size G x observation window n on one 32768-token Llama-3-8B-shaped sequence, and
+    the context-length / batch-size grid.  One JSON object with both tables."""
+    def run(lengths, G, n_obs, ratio=0.3):
+        w = workloads.make_custom(name=f"llama8b_{len(lengths)}x{max(lengths)}_G{G}_n{n_obs}", seed=100, lengths=lengths,
+                                  keep_ratio=[ratio] * len(lengths), hidden_dim=4096, num_q_heads=32, num_kv_heads=8,
+                                  block_size=G, n_obs=n_obs)
+        res = Resident(w, up, np, torch, 1 if w.total_tokens >= 131072 else 2)
+        sec, _ = res.time_fused(args.steps, args.warmup)
+        ph = res.time_phases(max(3, args.steps // 4))
+        row = summarise(res, sec)
+        row.update(G=G, n_obs=n_obs, lengths=f"{len(lengths)}x{max(lengths)}",
+                   kernels_us={k: round(v, 1) for k, v in ph.items()})
+        del res
+        torch.cuda.empty_cache()
+        print(f"[bench] sweep {row['lengths']} G={G} n={n_obs}: {row['ms_per_step'] * 1e3:.1f} us", file=sys.stderr, flush=True)
+        return row
+    block_window = [run([32768], G, n) for G in (32, 64, 128) for n in (32, 128, 512)]
+    grid = [run(ls, 128, 128) for ls in ([4096], [8192], [16384], [32768], [65536], [131072], [8192] * 4, [8192] * 16,
+                                         [8192] * 64)]
+    print(json.dumps({"metric": "fused score+select+compact operator, microseconds per call", "dtype": "bf16",
+                      "data": "synthetic", "steps": args.steps, "warmup": args.warmup,
+                      "block_size_x_window_32k": block_window, "context_and_batch_grid": grid}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -163,10 +348,19 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-phases", action="store_true", help="skip the per-kernel timing loop")
     ap.add_argument("--no-entry-points", action="store_true", help="skip timing the stand-alone entry points")
+    ap.add_argument("--no-workloads", action="store_true",
+                    help="skip the table of the other four workloads (the headline workload only)")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the benchmark line: operator timing over block size x window and over "
+                         "context length / batch size, as one JSON object")
+    ap.add_argument("--csrc-digest", action="store_true", help="print the digest of the kernel sources and exit")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one identity gather of the whole hidden tensor (a plain copy of known "
                          "size): the reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
+    if args.csrc_digest:
+        print(csrc_digest())
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (no sharding or collectives are built)",
               file=sys.stderr)
@@ -188,6 +382,8 @@ def main():
     t0 = time.time()
     if args.earlier:
         return bench_chunked(args, up, workloads, np, torch)
+    if args.sweep:
+        return bench_sweep(args, up, workloads, np, torch)
     if args.lengths:
         lengths = [int(x) for x in args.lengths.split(",")]
         w = workloads.make_custom(name=f"llama8b_shape_{len(lengths)}x{max(lengths)}_r{args.keep_ratio}_hd{args.head_dim}", seed=100,
@@ -198,110 +394,35 @@ def main():
     print(f"[bench] generated {w.name}: T={w.total_tokens} R={w.num_seqs} in {time.time() - t0:.1f}s",
           file=sys.stderr, flush=True)
 
-    cu_host = np.ascontiguousarray(w.cu_seqlens, dtype=np.int32)
-    ratio_host = np.ascontiguousarray(w.keep_ratio, dtype=np.float32)
-    p = up.make_params(num_seqs=w.num_seqs, total_tokens=w.total_tokens, block_size=w.block_size,
-                       n_obs=w.n_obs, n_sink=w.n_sink, num_q_heads=w.num_q_heads,
-                       num_kv_heads=w.num_kv_heads, head_dim=w.head_dim, hidden_dim=w.hidden_dim)
-    _, new_cu_plan, total_kept, ws_bytes = up.uniprefill_plan(p, cu_host, ratio_host)
+    res = Resident(w, up, np, torch, args.input_sets)
+    p, q, k, hidden, pos, cu, cu_host = res.p, res.q, res.k, res.hidden, res.pos, res.cu, res.cu_host
+    ratio, ratio_host, hidden_out, pos_out, kept_idx, new_cu = (res.ratio, res.ratio_host, res.hidden_out, res.pos_out,
+                                                                res.kept_idx, res.new_cu)
+    scores, workspace, ws_bytes, total_kept, stream = res.scores, res.workspace, res.ws_bytes, res.total_kept, res.stream
 
-    def dev_bf16(bits):
-        return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+    sec_per_step, step_us = res.time_fused(args.steps, args.warmup)
+    ms_per_step = sec_per_step * 1e3
+    tokens_per_s = w.total_tokens / sec_per_step
+    headline = summarise(res, sec_per_step)
 
-    q, k, hidden = dev_bf16(w.q), dev_bf16(w.k), dev_bf16(w.hidden)
-    pos = torch.from_numpy(w.pos).cuda()
-    cu = torch.from_numpy(cu_host).cuda()
-    ratio = torch.from_numpy(ratio_host).cuda()
-    workspace = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
-    hidden_out = torch.empty((total_kept, w.hidden_dim), dtype=torch.bfloat16, device="cuda")
-    pos_out = torch.empty(total_kept, dtype=torch.int32, device="cuda")
-    kept_idx = torch.empty(total_kept, dtype=torch.int32, device="cuda")
-    new_cu = torch.empty(w.num_seqs + 1, dtype=torch.int32, device="cuda")
-    scores = torch.empty(w.total_tokens, dtype=torch.float32, device="cuda")
-    stream = torch.cuda.current_stream()
-
-    # identical copies of the large inputs: step i reads copy i % n, which the steps in between
-    # have pushed out of the caches
-    n_sets = max(1, args.input_sets)
-    sets = [(q, k, hidden)] + [(q.clone(), k.clone(), hidden.clone()) for _ in range(n_sets - 1)]
-
-    def call_args(i):
-        qi, ki, hi = sets[i % n_sets]
-        return (p, qi, ki, hi, pos, cu, cu_host, ratio, ratio_host, hidden_out, pos_out, kept_idx, new_cu,
-                scores, workspace, ws_bytes)
-
-    common = call_args(0)
-
-    for i in range(args.warmup):
-        up.uniprefill_fused(*call_args(i), stream=stream)
-    torch.cuda.synchronize()
-    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
-    t_start = time.perf_counter()
-    marks[0].record(stream)
-    for i in range(args.steps):
-        up.uniprefill_fused(*call_args(args.warmup + i), stream=stream)
-        marks[i + 1].record(stream)      # spread of the single steps (the headline is the wall clock below)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t_start
-    ms_per_step = elapsed / args.steps * 1e3
-    tokens_per_s = w.total_tokens / (elapsed / args.steps)
-
-    per_step_us = sorted(marks[i].elapsed_time(marks[i + 1]) * 1e3 for i in range(args.steps))
-    pick = lambda f: round(per_step_us[min(len(per_step_us) - 1, int(f * len(per_step_us)))], 2)
-    step_us = {"median": pick(0.5), "p10": pick(0.1), "p90": pick(0.9)}
-
-    alg_bytes = algorithmic_bytes(w, total_kept)
-    flops = product_flops(w)
-
-    # ---- per-kernel durations: the same five launches, each bracketed by events on the stream
-    phases = [("plan", up.UP_PHASE_PLAN), ("row_stats", up.UP_PHASE_ROW_STATS),
-              ("merge_stats", up.UP_PHASE_MERGE_STATS),
-              ("sweep_select", up.UP_PHASE_SWEEP_SELECT), ("gather", up.UP_PHASE_GATHER)]
+    # ---- per-kernel durations: the same launches one by one, each bracketed by events on the stream
     kernels = {}
+    roofline = None
     if not args.no_phases:
-        acc = {name: 0.0 for name, _ in phases}
-        for it in range(args.steps):
-            evs = [torch.cuda.Event(enable_timing=True) for _ in range(len(phases) + 1)]
-            evs[0].record(stream)
-            for i, (name, mask) in enumerate(phases):
-                up.uniprefill_fused_phases(*call_args(it), mask, stream=stream)
-                evs[i + 1].record(stream)
-            torch.cuda.synchronize()
-            for i, (name, _) in enumerate(phases):
-                acc[name] += evs[i].elapsed_time(evs[i + 1])
-        gather_only_bytes = total_kept * (2 * w.hidden_dim * 2 + 12)      # rows in and out, pos in/out, index
-        score_bytes = w.total_tokens * 4 + total_kept * 4
-        k_bytes = w.total_tokens * w.num_kv_heads * w.head_dim * 2
-        for name, _ in phases:
-            us = acc[name] / args.steps * 1e3
-            ent = {"avg_us": round(us, 2)}
-            if name in ("row_stats", "sweep_select"):
-                # one Q.K^T pass each: the product's flops against the dense bf16 MFMA peak, and the
-                # bytes the pass has to move (K once; pass 2 also the scores and kept ids)
-                ent.update(bound="mfma", tflops=round(flops / (us * 1e-6) / 1e12, 1),
-                           frac_mfma=round(flops / (us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4))
-                moved = k_bytes + (score_bytes if name == "sweep_select" else 0)
-                ent.update(gbs=round(moved / (us * 1e-6) / 1e9, 1),
-                           frac_hbm=round(moved / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4))
-            if name == "gather":
-                ent.update(bound="hbm", gbs=round(gather_only_bytes / (us * 1e-6) / 1e9, 1),
-                           frac_hbm=round(gather_only_bytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4))
-            kernels[name] = ent
+        kernels = res.kernel_table(res.time_phases(args.steps))
         # the dominant kernel against the roofline it gets closest to (its algorithmic bytes
         # against HBM peak, or its product flops against the dense bf16 MFMA peak)
         dom = max(kernels, key=lambda n: kernels[n]["avg_us"])
         ent = kernels[dom]
-        traffic = MEASURED_TRAFFIC_BYTES.get((w.name, dom))
+        traffic, provenance = measured_traffic(w.name, dom)
         if ent.get("frac_mfma", 0.0) > ent.get("frac_hbm", 0.0):
             roofline = {"kernel": dom, "bound": "mfma", "achieved": ent["tflops"],
                         "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ent["frac_mfma"],
-                        "traffic": traffic}
+                        "traffic": traffic, "traffic_source": provenance}
         else:
             roofline = {"kernel": dom, "bound": "hbm", "achieved": ent.get("gbs"),
                         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ent.get("frac_hbm"),
-                        "traffic": traffic}
-    else:
-        roofline = None
+                        "traffic": traffic, "traffic_source": provenance}
 
     # ---- the stand-alone entry points and a plain device copy of the gather's byte count
     entry_points = {}
@@ -393,26 +514,27 @@ def main():
               f"(reads and writes {w.total_tokens * w.hidden_dim * 2} bytes each)", file=sys.stderr, flush=True)
         del ident, full, fpos
 
-    # ---- the oracle on this machine's host cores (a reported baseline, not a target)
+    # ---- the oracle on this machine's host cores (a reported baseline, not a target), and the
+    # ---- results of the timed calls against it
     cpu_baseline = None
-    parity = None
+    checks = {}
     if not args.no_cpu_baseline:
-        sys.path.insert(0, os.path.join(ROOT, "tests"))
-        from gpu_util import oracle_run           # test infrastructure: the fp64 numpy oracle
+        up.uniprefill_fused(*res.call_args(0), stream=stream)
         try:
             from threadpoolctl import threadpool_info
             threads = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
         except Exception:
             threads = os.cpu_count() or 1
-        t1 = time.perf_counter()
-        ref = oracle_run(w)
-        cpu_s = time.perf_counter() - t1
+        checks, _ = res.against_oracle()
+        cpu_s = checks["oracle_seconds"]
         cpu_baseline = {"value": round(w.total_tokens / cpu_s, 1), "unit": "tokens/s", "cores": int(threads),
-                        "kind": "oracle", "seconds": round(cpu_s, 2),
+                        "kind": "oracle", "seconds": cpu_s,
                         "sample": f"the full {w.name} batch, one pass (BLAS threads = cores; numpy exp is single-threaded)"}
         # the same pass on one thread (how much of the figure above is the BLAS library's threading)
         try:
             from threadpoolctl import threadpool_limits
+            sys.path.insert(0, os.path.join(ROOT, "tests"))
+            from gpu_util import oracle_run
             with threadpool_limits(limits=1):
                 t1 = time.perf_counter()
                 oracle_run(w)
@@ -420,10 +542,34 @@ def main():
             cpu_baseline["single_thread"] = {"value": round(w.total_tokens / cpu_1, 1), "seconds": round(cpu_1, 2)}
         except Exception:
             pass
-        torch.cuda.synchronize()
-        parity = bool(np.array_equal(kept_idx.cpu().numpy(), ref["kept_idx"])
-                      and np.array_equal(hidden_out.view(torch.int16).cpu().numpy().view(np.uint16), ref["hidden_out"])
-                      and np.array_equal(pos_out.cpu().numpy(), ref["pos_out"]))
+
+    # ---- all five workloads in the same run: time, rooflines, parity, score error and margin
+    table = {}
+    if not args.no_workloads and not args.lengths:
+        row = dict(headline)
+        row.update(checks)
+        row["kernels_us"] = {n: kernels[n]["avg_us"] for n in kernels}
+        table[w.name] = row
+        del res, q, k, hidden, hidden_out, scores, workspace
+        torch.cuda.empty_cache()
+        for idx in (1, 2, 3, 4, 5):
+            if workloads.CONFIG_NAMES[idx] == w.name:
+                continue
+            t1 = time.time()
+            wi = workloads.make_config(idx)
+            ri = Resident(wi, up, np, torch, args.input_sets if wi.total_tokens >= 100000 else max(args.input_sets, 8))
+            steps_i = max(5, min(args.steps, 20))
+            sec_i, _ = ri.time_fused(steps_i, max(3, min(args.warmup, 5)))
+            row = summarise(ri, sec_i)
+            if not args.no_phases:
+                row["kernels_us"] = {n: round(v, 2) for n, v in ri.time_phases(max(3, steps_i // 2)).items()}
+            if not args.no_cpu_baseline:
+                up.uniprefill_fused(*ri.call_args(0), stream=ri.stream)
+                row.update(ri.against_oracle()[0])
+            table[wi.name] = row
+            print(f"[bench] {wi.name}: {row['ms_per_step'] * 1e3:.1f} us per step ({time.time() - t1:.1f}s)", file=sys.stderr, flush=True)
+            del ri, wi
+            torch.cuda.empty_cache()
 
     out = {
         "metric": "tokens/s through fused score+select+compact op; % of MI355X HBM peak",
@@ -440,21 +586,19 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": w.name, "total_tokens": w.total_tokens, "num_seqs": w.num_seqs,
-                   "total_kept": int(total_kept), "hidden_dim": w.hidden_dim, "q_heads": w.num_q_heads,
-                   "kv_heads": w.num_kv_heads, "block_size": w.block_size, "n_obs": w.n_obs, "n_sink": w.n_sink,
-                   "input_sets": n_sets},
-        "algorithmic_bytes": int(alg_bytes),
-        "hbm_frac_fused": round(alg_bytes / (elapsed / args.steps) / 1e9 / HBM_PEAK_GBS, 4),
-        "product_flops_per_pass": int(flops),
-        # the larger of (algorithmic bytes at HBM peak, the two product passes at the dense bf16 MFMA
-        # peak) over the measured step time
-        "binding_roofline_frac": round(max(alg_bytes / (HBM_PEAK_GBS * 1e9), 2.0 * flops / (MFMA_BF16_PEAK_TFLOPS * 1e12))
-                                       / (elapsed / args.steps), 4),
+                   "total_kept": int(total_kept), "input_sets": max(1, args.input_sets)},
+        "algorithmic_bytes": headline["algorithmic_bytes"],
+        "hbm_frac_fused": headline["hbm_frac"],
+        "product_flops_per_pass": int(product_flops(w)),
+        "binding_roofline_frac": headline["binding_roofline_frac"],
         "roofline": roofline,
         "kernels": kernels,
         "entry_points": entry_points,
         "cpu_baseline": cpu_baseline,
-        "oracle_parity": parity,
+        "oracle_parity": checks.get("oracle_parity"),
+        "max_score_rel_err": checks.get("max_score_rel_err"),
+        "min_selection_margin": checks.get("min_selection_margin"),
+        "workloads": table,
     }
     print(json.dumps(out), flush=True)
 
