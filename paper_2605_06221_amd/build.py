@@ -9,6 +9,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libuniprefill.so")
+PIPES_BENCH_PATH = os.path.join(HERE, "up_pipes_bench.exe")
 SOURCES = ["up_api.hip", "up_copy.hip", "up_select.hip", "up_sweep.hip", "up_topp.hip"]
 
 HIPCC_FLAGS = [
@@ -53,7 +54,20 @@ def build_library(verbose: bool = False, extra_flags=()) -> str:
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if res.returncode != 0:
         raise RuntimeError(f"link failed:\n{res.stdout}")
+    build_pipes_bench(verbose)
     return LIB_PATH
+
+
+def build_pipes_bench(verbose: bool = False) -> str:
+    """The stand-alone measurement program of the matrix / vector pipes (not part of the library)."""
+    flags = [f for f in HIPCC_FLAGS if f != "-fPIC"]
+    cmd = [hipcc_path(), *flags, os.path.join(CSRC, "up_pipes_bench.hip"), "-o", PIPES_BENCH_PATH]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode != 0:
+        raise RuntimeError(f"hipcc failed on up_pipes_bench.hip:\n{res.stdout}")
+    return PIPES_BENCH_PATH
 
 
 if __name__ == "__main__":
