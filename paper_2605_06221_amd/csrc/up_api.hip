@@ -13,6 +13,50 @@
 
 using namespace up;
 
+// ---- host-only pieces of the launch plumbing (this file holds no device code apart from the
+// static scratch array: everything in it also builds with a plain C++ compiler, which is how the
+// argument checks and the geometry are run under the address and undefined-behaviour sanitizers)
+namespace up {
+
+Workspace workspace_layout(const Problem& pb) {
+  auto al = [](size_t x) { return (x + 255) & ~(size_t)255; };
+  Workspace w;
+  size_t off = 0;
+  // block-level top-p selection: flags and offsets per selection block, totals per sequence.
+  // First in the buffer: their place depends on T, G and R only, not on the scoring geometry.
+  const size_t sel_slots = (size_t)(pb.T / pb.G + pb.R);
+  w.tp_keep_off = off;
+  off = al(off + sel_slots * sizeof(int32_t));
+  w.tp_off_off = off;
+  off = al(off + sel_slots * sizeof(int32_t));
+  w.tp_seq_off = off;
+  off = al(off + (size_t)(pb.R + 1) * sizeof(int32_t));
+  w.tp_mass_off = off;
+  off = al(off + sel_slots * sizeof(float));
+  w.tp_rank_off = off;
+  off = al(off + sel_slots * sizeof(int32_t));
+  w.tp_total = off;
+  w.stat_part_off = off;
+  off = al(off + (size_t)pb.key_block_slots * pb.Hq * pb.n_obs * 2 * sizeof(float));
+  w.stat_fin_off = off;
+  off = al(off + (size_t)pb.row_slots * pb.Hq * 2 * sizeof(float));
+  w.o_part_off = off;
+  // (always there: a call that wants the raw column sums goes through k_finish whatever the split)
+  off = al(off + (size_t)pb.key_block_slots2 * pb.split2 * pb.key_block2 * sizeof(double));
+  w.total = off;
+  return w;
+}
+
+SelectArgs make_select_args(const Problem& pb, const float* scores, const int32_t* cu, const int32_t* cu_k,
+                            const float* ratio, const int32_t* new_cu, int32_t* kept_idx) {
+  SelectArgs a;
+  a.scores = scores; a.cu = cu; a.cu_k = cu_k; a.ratio = ratio; a.new_cu = new_cu; a.kept_idx = kept_idx;
+  a.R = pb.R; a.T = pb.T; a.G = pb.G; a.n_obs = pb.n_obs; a.n_sink = pb.n_sink;
+  return a;
+}
+
+}  // namespace up
+
 namespace {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }

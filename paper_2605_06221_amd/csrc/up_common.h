@@ -12,9 +12,11 @@
 
 namespace up {
 
+#if defined(__HIPCC__)      // (device vector types; the host-only build of the argument checks never names them)
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+#endif
 
 constexpr int kMaxNObs = 1024;
 

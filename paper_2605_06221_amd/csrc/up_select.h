@@ -34,6 +34,7 @@ struct SelectSmem {
   int cnt0, base;
 };
 
+#if defined(__HIPCC__)
 // Sinks among the N tokens of sequence r: the first A tokens of the sequence so far, of which
 // the earlier context (cu_k given: keys minus tokens) already holds some or all.
 __device__ __forceinline__ int sinks_of(const int32_t* cu_k, int n_sink, int r, int N) {
@@ -123,5 +124,7 @@ __device__ __forceinline__ void select_block(const SelectArgs& a, SelectSmem& sm
   if (keep) a.kept_idx[sm.base + before + (wave == 1 ? sm.cnt0 : 0)] = c0 + lo + tid;
   __syncthreads();   // the shared arrays are reused by the next block
 }
+
+#endif  // __HIPCC__
 
 }  // namespace up

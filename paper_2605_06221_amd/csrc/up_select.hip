@@ -27,14 +27,6 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
   select_block(a, sm, r, c0, N, g, a.scores + c0 + g * a.G);
 }
 
-SelectArgs make_select_args(const Problem& pb, const float* scores, const int32_t* cu, const int32_t* cu_k,
-                            const float* ratio, const int32_t* new_cu, int32_t* kept_idx) {
-  SelectArgs a;
-  a.scores = scores; a.cu = cu; a.cu_k = cu_k; a.ratio = ratio; a.new_cu = new_cu; a.kept_idx = kept_idx;
-  a.R = pb.R; a.T = pb.T; a.G = pb.G; a.n_obs = pb.n_obs; a.n_sink = pb.n_sink;
-  return a;
-}
-
 hipError_t launch_plan(const Problem& pb, const int32_t* cu, const int32_t* cu_k, const float* ratio,
                        int32_t* new_cu, hipStream_t s) {
   hipLaunchKernelGGL(k_plan, dim3(1), dim3(1024), 0, s, cu, cu_k, ratio, pb.R, pb.G, pb.n_obs, pb.n_sink,

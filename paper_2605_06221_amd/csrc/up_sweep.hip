@@ -704,35 +704,6 @@ hipError_t launch_scores_from_partials(const double* partials, int num_parts, lo
   return hipGetLastError();
 }
 
-Workspace workspace_layout(const Problem& pb) {
-  auto al = [](size_t x) { return (x + 255) & ~(size_t)255; };
-  Workspace w;
-  size_t off = 0;
-  // block-level top-p selection: flags and offsets per selection block, totals per sequence.
-  // First in the buffer: their place depends on T, G and R only, not on the scoring geometry.
-  const size_t sel_slots = (size_t)(pb.T / pb.G + pb.R);
-  w.tp_keep_off = off;
-  off = al(off + sel_slots * sizeof(int32_t));
-  w.tp_off_off = off;
-  off = al(off + sel_slots * sizeof(int32_t));
-  w.tp_seq_off = off;
-  off = al(off + (size_t)(pb.R + 1) * sizeof(int32_t));
-  w.tp_mass_off = off;
-  off = al(off + sel_slots * sizeof(float));
-  w.tp_rank_off = off;
-  off = al(off + sel_slots * sizeof(int32_t));
-  w.tp_total = off;
-  w.stat_part_off = off;
-  off = al(off + (size_t)pb.key_block_slots * pb.Hq * pb.n_obs * sizeof(float2));
-  w.stat_fin_off = off;
-  off = al(off + (size_t)pb.row_slots * pb.Hq * sizeof(float2));
-  w.o_part_off = off;
-  // (always there: a call that wants the raw column sums goes through k_finish whatever the split)
-  off = al(off + (size_t)pb.key_block_slots2 * pb.split2 * pb.key_block2 * sizeof(double));
-  w.total = off;
-  return w;
-}
-
 static SweepArgs make_sweep_args(const Problem& pb, const void* q, const void* k, const int32_t* cu,
                                  const int32_t* cu_k, void* workspace, const PagedKeys* paged = nullptr) {
   const Workspace w = workspace_layout(pb);

@@ -560,6 +560,26 @@ def test_fused_full_size_configs_bit_exact(idx):
     _assert_fused_exact(w, b, ref)
 
 
+def test_fused_128k_shape_with_plain_normal_keys_bit_exact():
+    """The headline workload's shape (one 131072-token sequence, 40/8 heads, block 128, ratio 0.25) with
+    plain N(0,1) keys instead of the lognormal-scaled ones: on the headline data every block's
+    boundary falls among floored zeros (the index rule decides), here the score ranking decides every
+    block, at the same launch configuration.  The margin is printed."""
+    _say("fused 128k shape, plain keys")
+    w = workloads.make_custom(name="c4_shape_plain_keys", seed=77, lengths=[131072], keep_ratio=[0.25], hidden_dim=512,
+                              num_q_heads=40, num_kv_heads=8, block_size=128)
+    b = DeviceBatch(w)
+    b.fused()
+    torch.cuda.synchronize()
+    ref = oracle_run(w)
+    _assert_fused_exact(w, b, ref)
+    margin = score_margin_report(ref, w)
+    assert np.isfinite(margin) and margin > 0          # blocks whose boundary is decided by the scores exist
+    nz = int(np.count_nonzero(ref["scores"]))
+    _say(f"  non-zero scores {nz} of {w.total_tokens}, smallest selection margin {margin:.3g}")
+    assert nz == w.total_tokens
+
+
 # ----------------------------------------------------------------------------- block-level top-p (Eq. 4-6)
 def _top_p_buffers(w):
     p = up.make_params(num_seqs=w.num_seqs, total_tokens=w.total_tokens, block_size=w.block_size, n_obs=w.n_obs,
