@@ -273,15 +273,37 @@ def top_p_block_keys(mass_f32):
     return (phi(b).astype(np.uint64) << np.uint64(32)) | (np.uint64(nb - 1) - np.arange(nb, dtype=np.uint64))
 
 
+TOP_P_CHUNK = 64      # positions per chunk of the running sum below
+
+
+def chunked_running_sum(values_f32):
+    """Running sum in double of float32 values taken in the given order, in a fixed two-level
+    shape (the paper thresholds "a cumulative sum" and states no precision, Eq. 5): the positions
+    are cut into chunks of 64; inside a chunk the sum runs from zero, one addition after the
+    other; the chunks' totals are added one after the other; the running sum at a position is
+    (the sum of the earlier chunks' totals) + (its sum inside its chunk).  Up to 64 values this
+    is the plain sequential sum.  Pure-Python loops: every addition is spelled out."""
+    v = [float(x) for x in np.asarray(values_f32, dtype=np.float32)]
+    run = []
+    offset = 0.0                                  # total of the earlier chunks
+    for lo in range(0, len(v), TOP_P_CHUNK):
+        inside = 0.0
+        for x in v[lo:lo + TOP_P_CHUNK]:
+            inside = inside + x
+            run.append(offset + inside)
+        offset = offset + inside
+    return np.array(run, dtype=np.float64)
+
+
 def top_p_kept_blocks(mass_f32, p):
     """Boolean keep flag per block under Eq. 5: blocks in descending key order, running sum
-    of their masses in double (one addition after the other, in that order), k* the first
-    position where the running sum reaches p times the total.  p is a float32 widened to
-    double."""
+    of their masses in double in that order (``chunked_running_sum``), k* the first
+    position where the running sum reaches p times the total (the last running sum).  p is a
+    float32 widened to double."""
     b = np.asarray(mass_f32, dtype=np.float32)
     nb = b.shape[0]
     order = np.argsort(top_p_block_keys(b), kind="stable")[::-1]
-    run = np.add.accumulate(b[order].astype(np.float64))          # sequential by definition
+    run = chunked_running_sum(b[order])
     thr = float(np.float32(p)) * float(run[-1])
     kstar = int(np.count_nonzero(run < thr)) + 1                   # run is non-decreasing (masses >= 0)
     kstar = min(kstar, nb)

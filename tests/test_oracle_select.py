@@ -304,6 +304,68 @@ def test_quantised_top_p_blocks_against_enumeration(seed):
             assert kept_mass - float(mass[keep].min()) < float(np.float32(p)) * float(mass.astype(np.float64).sum())
 
 
+def test_chunked_running_sum_against_exact_rationals_and_its_shape():
+    """The running sum that the top-p threshold is taken on: exact where every partial sum is
+    representable (checked against rational arithmetic at every position, across chunk borders),
+    the plain sequential sum up to one chunk, never decreasing, within n * 2^-53 of the exact sum
+    otherwise -- and a hand case in which the two-level shape shows: a chunk's small values are
+    added among themselves before they meet the large earlier total."""
+    from fractions import Fraction
+    rng = np.random.default_rng(21)
+    # (a) dyadic values with few significant bits: every partial sum is exact in double
+    v = (rng.integers(0, 1 << 12, size=300) / 1024.0).astype(np.float32)
+    run = oracle.chunked_running_sum(v)
+    exact, acc = [], Fraction(0)
+    for x in v:
+        acc += Fraction(float(x))
+        exact.append(acc)
+    assert all(Fraction(float(r)) == e for r, e in zip(run, exact))
+    # (b) up to one chunk: the sequential double sum, bit for bit
+    w = (rng.random(64) ** 9).astype(np.float32)
+    np.testing.assert_array_equal(oracle.chunked_running_sum(w), np.add.accumulate(w.astype(np.float64)))
+    # (c) random heavy-tailed values over several chunks: monotone, close to exact, last = total
+    z = np.exp(rng.standard_normal(1000) * 8 - 20).astype(np.float32)
+    run = oracle.chunked_running_sum(z)
+    assert (np.diff(run) >= 0).all() and len(run) == 1000
+    acc = Fraction(0)
+    for k, x in enumerate(z):
+        acc += Fraction(float(x))
+        assert abs(Fraction(float(run[k])) - acc) <= acc * Fraction(k + 1, 2 ** 53)
+    # (d) hand case: 1, then 63 zeros | 64 values of 2^-54.  One after the other each 2^-54 would be
+    # rounded away against 1 (ties to even); inside their chunk they add up to 2^-48 first.
+    h = np.zeros(128, np.float32)
+    h[0] = 1.0
+    h[64:] = 2.0 ** -54
+    run = oracle.chunked_running_sum(h)
+    assert run[63] == 1.0 and run[64] == 1.0 and run[127] == 1.0 + 2.0 ** -48
+    assert np.add.accumulate(h.astype(np.float64))[-1] == 1.0          # (the sequential sum differs)
+    assert len(oracle.chunked_running_sum(np.zeros(0, np.float32))) == 0
+
+
+def test_top_p_threshold_across_chunk_borders_against_exact_rationals():
+    """More blocks than one chunk of the running sum, masses whose sums are exact: the kept set is
+    the one rational arithmetic gives, for thresholds that fall before, on and after a chunk border."""
+    from fractions import Fraction
+    rng = np.random.default_rng(22)
+    nb = 200
+    mass = (rng.integers(1, 1 << 10, size=nb) / 256.0).astype(np.float32)
+    order = sorted(range(nb), key=lambda g: (-float(mass[g]), g))
+    total = sum(Fraction(float(m)) for m in mass)
+    for p in [0.05, 0.3, 0.5, 0.75, 0.9, 0.999, 1.0]:
+        thr = Fraction(float(np.float32(p))) * total
+        # (p * total in double, as the oracle takes it, equals the rational product here: few bits)
+        acc, want = Fraction(0), None
+        for k, g in enumerate(order, 1):
+            acc += Fraction(float(mass[g]))
+            if acc >= Fraction(float(np.float32(p)) * float(total)):
+                want = set(order[:k])
+                break
+        keep = oracle.top_p_kept_blocks(mass, p)
+        assert set(np.nonzero(keep)[0]) == want, p
+    ks = [int(oracle.top_p_kept_blocks(mass, p).sum()) for p in (0.3, 0.5, 0.75, 0.9)]
+    assert ks == sorted(ks) and ks[0] < 64 < ks[-1]          # thresholds on both sides of the first border
+
+
 def test_block_mass_f32_is_the_rounded_exact_sum():
     rng = np.random.default_rng(9)
     s = (rng.random(1000) ** 8).astype(np.float32)
