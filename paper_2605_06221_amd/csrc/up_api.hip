@@ -35,6 +35,8 @@ Workspace workspace_layout(const Problem& pb) {
   off = al(off + sel_slots * sizeof(float));
   w.tp_rank_off = off;
   off = al(off + sel_slots * sizeof(int32_t));
+  w.tp_sorted_off = off;
+  off = al(off + sel_slots * sizeof(float));
   w.tp_total = off;
   w.stat_part_off = off;
   off = al(off + (size_t)pb.key_block_slots * pb.Hq * pb.n_obs * 2 * sizeof(float));

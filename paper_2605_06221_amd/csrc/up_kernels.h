@@ -41,7 +41,7 @@ struct Problem {
 // Workspace carve-up (byte offsets, each 256-aligned).
 struct Workspace {
   size_t stat_part_off, stat_fin_off, o_part_off, total;
-  size_t tp_keep_off, tp_off_off, tp_seq_off, tp_mass_off, tp_rank_off, tp_total;   // top-p selection part (first tp_total bytes)
+  size_t tp_keep_off, tp_off_off, tp_seq_off, tp_mass_off, tp_rank_off, tp_sorted_off, tp_total;   // top-p selection part (first tp_total bytes)
 };
 Workspace workspace_layout(const Problem& pb);
 
@@ -84,7 +84,7 @@ SelectArgs make_select_args(const Problem& pb, const float* scores, const int32_
 hipError_t launch_select(const Problem& pb, const SelectArgs& a, hipStream_t s);
 
 // --- block-level top-p selection (Eq. 4-6); kept_idx needs room for T entries
-constexpr int kMaxTopPBlocks = 4096;   // blocks of one sequence that the top-p kernel orders in LDS
+constexpr int kMaxTopPBlocks = 65536;   // blocks of one sequence that the top-p kernels order (1024 chunks of the running sum)
 struct TopPArgs {
   const float* scores;
   const int32_t* cu;
@@ -97,6 +97,7 @@ struct TopPArgs {
   int32_t* seq_kept;     // [R] kept tokens per sequence
   float* blk_mass;       // [T/G + R] block masses
   int32_t* blk_rank;     // [T/G + R] place of the block in the descending order of its sequence
+  float* blk_sorted;     // [T/G + R] the masses of a sequence's blocks in that order
   int R, T, G, n_obs, n_sink;
 };
 // (max_blocks: selection blocks of the longest sequence, at most kMaxTopPBlocks)

@@ -9,15 +9,20 @@
 //   k_block_mass     one wave per block: its mass
 //   k_top_p_rank     place of every block in the descending order of the keys, by counting the
 //                    larger keys: 256 x 256 pairs per work-group, spread over the chip
-//   k_top_p_blocks   one work-group per sequence: running sum in that order, threshold, keep
-//                    flags and in-sequence output offsets of the blocks
+//   k_top_p_blocks   one work-group per sequence: the masses put in that order, their running sum
+//                    (chunks of 64 positions, one wave each), threshold, keep flags and in-sequence
+//                    output offsets of the blocks
 //   k_top_p_offsets  prefix sum of the per-sequence totals
 //   k_top_p_emit     one work-group per block: kept token ids, ascending
 //
 // Arithmetic that decides integers is fixed so that it can be matched bit for
 // bit: a block's mass is the double sum of its float scores in index order,
-// rounded to float; the running sum over the ordered blocks is a double sum in
-// that order; the threshold is (double)p times the total.
+// rounded to float; the running sum over the ordered blocks is a double sum of a
+// fixed two-level shape -- the positions are cut into chunks of 64, inside a chunk
+// the sum runs from zero one addition after the other, the chunks' totals are added
+// one after the other, and a position's running sum is (the total of the earlier
+// chunks) + (its sum inside its chunk) -- so that the chunks can be summed by
+// different waves at once; the threshold is (double)p times the last running sum.
 #include <type_traits>
 
 #include "up_common.h"
@@ -28,10 +33,12 @@ namespace up {
 
 constexpr int kTopPThreads = 1024;
 
+constexpr int kTopPChunk = 64;                                  // positions per chunk of the running sum
+constexpr int kMaxTopPChunks = kMaxTopPBlocks / kTopPChunk;
+
 struct TopPSmem {
-  float sorted_mass[kMaxTopPBlocks];
-  int rank[kMaxTopPBlocks];
-  double run[kMaxTopPBlocks];     // running sum over the ordered blocks
+  double chunk_tot[kMaxTopPChunks];   // sum of every chunk's masses
+  double chunk_off[kMaxTopPChunks];   // total of the chunks before it
   int wave_tot[16];
   int kstar_part[16];
   double thr;
@@ -116,38 +123,48 @@ __global__ __launch_bounds__(kTopPThreads) void k_top_p_blocks(TopPArgs a) {
   const int nb = ceil_div(N, G);
   const int slot0 = slot_base(c0, r, G);
 
-  // 1.-2. every block's place in the descending order of the keys (counted by k_top_p_rank) and
-  // the masses in that order
-  for (int g = tid; g < nb; g += kTopPThreads) {
-    const int rk = a.blk_rank[slot0 + g];
-    sm.rank[g] = rk;
-    sm.sorted_mass[rk] = a.blk_mass[slot0 + g];
-  }
-  // 3. running sum in that order, one addition after the other (sixteen reads in flight, then
-  // the sixteen additions; the list is padded with zeros to a multiple of sixteen so that the
-  // loop has no conditions in it)
-  const int nb16 = (nb + 15) & ~15;
-  if (tid < nb16 - nb) sm.sorted_mass[nb + tid] = 0.0f;
-  __syncthreads();
-  if (tid == 0) {
+  // 1. the masses in the descending order of the keys (every block's place was counted by
+  // k_top_p_rank); the list lives in the workspace: a sequence may have more blocks than LDS holds
+  float* sorted = a.blk_sorted + slot0;
+  for (int g = tid; g < nb; g += kTopPThreads) sorted[a.blk_rank[slot0 + g]] = a.blk_mass[slot0 + g];
+  __syncthreads();      // (the work-group's own global writes are visible to it after the barrier)
+  // 2. every chunk's total: a wave per chunk, the lanes fetch the chunk's 64 masses and every lane
+  // adds them in order through broadcasts (the same sequence of double additions as a plain loop)
+  const int nchunks = ceil_div(nb, kTopPChunk);
+  for (int c = wave; c < nchunks; c += kTopPThreads / 64) {
+    const int k = c * kTopPChunk + lane;
+    const float v = k < nb ? sorted[k] : 0.0f;            // (+0 leaves a sum of non-negative terms as it is)
     double acc = 0.0;
-    for (int k0 = 0; k0 < nb16; k0 += 16) {
-      float v[16];
 #pragma unroll
-      for (int j = 0; j < 16; ++j) v[j] = sm.sorted_mass[k0 + j];
-#pragma unroll
-      for (int j = 0; j < 16; ++j) {
-        acc += (double)v[j];
-        sm.run[k0 + j] = acc;
-      }
-    }
-    sm.thr = (double)a.top_p[r] * acc;
+    for (int i = 0; i < kTopPChunk; ++i) acc += (double)__shfl(v, i);
+    if (lane == 0) sm.chunk_tot[c] = acc;
   }
   __syncthreads();
-  // 4. k* = 1 + number of prefixes still below the threshold (the running sum never decreases)
+  // 3. the chunks' totals added one after the other; the threshold on the last running sum
+  if (tid == 0) {
+    double off = 0.0;
+    for (int c = 0; c < nchunks; ++c) {
+      sm.chunk_off[c] = off;
+      off += sm.chunk_tot[c];
+    }
+    sm.thr = (double)a.top_p[r] * off;
+  }
+  __syncthreads();
+  // 4. k* = 1 + number of positions whose running sum is still below the threshold (it never
+  // decreases).  The sums inside the chunks are formed again, lane j stopping after its own position.
   const double thr = sm.thr;
   int below = 0;
-  for (int k = tid; k < nb; k += kTopPThreads) below += sm.run[k] < thr ? 1 : 0;
+  for (int c = wave; c < nchunks; c += kTopPThreads / 64) {
+    const int k = c * kTopPChunk + lane;
+    const float v = k < nb ? sorted[k] : 0.0f;
+    double acc = 0.0;
+#pragma unroll
+    for (int i = 0; i < kTopPChunk; ++i) {
+      const double vi = (double)__shfl(v, i);
+      if (i <= lane) acc += vi;
+    }
+    below += (k < nb && sm.chunk_off[c] + acc < thr) ? 1 : 0;
+  }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) below += __shfl_xor(below, o);
   if (lane == 0) sm.kstar_part[wave] = below;
@@ -163,7 +180,7 @@ __global__ __launch_bounds__(kTopPThreads) void k_top_p_blocks(TopPArgs a) {
     int cnt = 0, keep = 0;
     if (g < nb) {
       const int lo = g * G, hi = imin(N, lo + G);
-      keep = sm.rank[g] < kstar ? 1 : 0;
+      keep = a.blk_rank[slot0 + g] < kstar ? 1 : 0;
       cnt = keep ? hi - lo : forced_in(sg, lo, hi);
     }
     int incl = cnt;
@@ -250,6 +267,7 @@ hipError_t launch_top_p(const Problem& pb, const float* scores, const int32_t* c
   a.seq_kept = (int32_t*)(ws + w.tp_seq_off);
   a.blk_mass = (float*)(ws + w.tp_mass_off);
   a.blk_rank = (int32_t*)(ws + w.tp_rank_off);
+  a.blk_sorted = (float*)(ws + w.tp_sorted_off);
   a.R = pb.R; a.T = pb.T; a.G = pb.G; a.n_obs = pb.n_obs; a.n_sink = pb.n_sink;
   if (pb.T > 0)
     hipLaunchKernelGGL(k_block_mass, dim3((unsigned)((pb.T / pb.G + pb.R + 3) / 4)), dim3(256), 0, s, a);

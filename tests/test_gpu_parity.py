@@ -638,14 +638,67 @@ def test_select_top_p_long_sequence_and_many_sequences():
     torch.cuda.synchronize()
     np.testing.assert_array_equal(b["new_cu"][:w.num_seqs + 1].cpu().numpy(), want_cu)
     np.testing.assert_array_equal(b["kept_idx"][:len(want_idx)].cpu().numpy(), want_idx)
-    # one block too many for the in-LDS ordering: refused on the host, nothing launched
-    w2 = workloads.make_custom(name="tpx", seed=6, lengths=[32 * 4096 + 1], keep_ratio=[0.5], hidden_dim=8,
-                               num_q_heads=2, num_kv_heads=1, block_size=32, n_obs=128, n_sink=128)
-    b2 = _top_p_buffers(w2)
-    st = up.uniprefill_select_top_p(b2["p"], torch.zeros(w2.total_tokens, device="cuda"), b2["cu"], b2["cu_host"],
-                                    torch.ones(1, device="cuda"), np.ones(1, np.float32), b2["kept_idx"], b2["new_cu"],
-                                    b2["workspace"], b2["ws_bytes"], check=False)
-    assert st == up.UP_ERR_UNSUPPORTED
+
+
+def test_select_top_p_one_million_tokens_at_block_32():
+    """32768 blocks in one sequence (1 M tokens at G = 32, the paper's smallest block at its longest
+    context and beyond): the blocks are ordered across the chip and the running sum is formed chunk by
+    chunk; bit for bit the oracle's selection."""
+    _say("top-p select, 1M tokens, G = 32")
+    rng = np.random.default_rng(45)
+    T = 1 << 20
+    w = workloads.make_custom(name="tp1m", seed=6, lengths=[T], keep_ratio=[0.5], hidden_dim=8, num_q_heads=2,
+                              num_kv_heads=1, block_size=32, n_obs=128, n_sink=128)
+    s = (rng.random(T) ** 24).astype(np.float32)
+    s[rng.random(T) < 0.3] = 0.0
+    top_p = np.array([0.97], np.float32)
+    want_idx, want_cu = oracle.select_tokens_top_p(s, w.cu_seqlens, top_p, block_size=32, n_obs=128, n_sink=128)
+    b = _top_p_buffers(w)
+    up.uniprefill_select_top_p(b["p"], torch.from_numpy(s).cuda(), b["cu"], b["cu_host"], torch.from_numpy(top_p).cuda(),
+                               top_p, b["kept_idx"], b["new_cu"], b["workspace"], b["ws_bytes"])
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(b["new_cu"][:2].cpu().numpy(), want_cu)
+    np.testing.assert_array_equal(b["kept_idx"][:len(want_idx)].cpu().numpy(), want_idx)
+    assert 0 < len(want_idx) < T and (b["kept_idx"][len(want_idx):] == -77).all()
+
+
+@pytest.mark.parametrize("idx", [2, 4])
+def test_fused_top_p_full_size_configs(idx):
+    """The paper's own rule (p = 0.99) end to end on the 32768- and the 131072-token workload at full
+    size: the selection is the oracle's rule on the scores the GPU produced, bit for bit, and equals the
+    selection of the fp64-scored oracle; rows and positions are the gathered ones."""
+    _say("fused top-p, full size", idx)
+    w = workloads.make_config(idx)
+    top_p = np.full(w.num_seqs, 0.99, np.float32)
+    b = _top_p_buffers(w)
+    T, d = w.total_tokens, w.hidden_dim
+    q, k, hidden = dev_bf16(w.q), dev_bf16(w.k), dev_bf16(w.hidden)
+    pos = torch.from_numpy(w.pos).cuda()
+    hidden_out = torch.full((T + 8, d), -7.0, dtype=torch.bfloat16, device="cuda")
+    pos_out = torch.full((T + 8,), -77, dtype=torch.int32, device="cuda")
+    scores = torch.empty(T, dtype=torch.float32, device="cuda")
+    up.uniprefill_fused_top_p(b["p"], q, k, hidden, pos, b["cu"], b["cu_host"], torch.from_numpy(top_p).cuda(), top_p,
+                              hidden_out, pos_out, b["kept_idx"], b["new_cu"], scores, b["workspace"], b["ws_bytes"])
+    torch.cuda.synchronize()
+    got_scores = scores.cpu().numpy()
+    got_cu = b["new_cu"][:w.num_seqs + 1].cpu().numpy()
+    total = int(got_cu[-1])
+    got_idx = b["kept_idx"][:total].cpu().numpy()
+    want_idx, want_cu = oracle.select_tokens_top_p(got_scores, w.cu_seqlens, top_p, block_size=w.block_size,
+                                                   n_obs=w.n_obs, n_sink=w.n_sink)
+    np.testing.assert_array_equal(got_cu, want_cu)
+    np.testing.assert_array_equal(got_idx, want_idx)
+    ref = oracle_run(w)
+    ok, worst = _score_close(got_scores, ref["scores"])
+    assert ok
+    ref_idx, ref_cu = oracle.select_tokens_top_p(ref["scores"], w.cu_seqlens, top_p, block_size=w.block_size,
+                                                 n_obs=w.n_obs, n_sink=w.n_sink)
+    _say(f"  kept {total} of {T}; worst score error {worst:.3g}")
+    np.testing.assert_array_equal(ref_cu, got_cu)
+    np.testing.assert_array_equal(ref_idx, got_idx)
+    np.testing.assert_array_equal(host_bits(hidden_out[:total]), w.hidden[got_idx])
+    np.testing.assert_array_equal(pos_out[:total].cpu().numpy(), w.pos[got_idx])
+    assert (hidden_out[total:] == -7.0).all() and (pos_out[total:] == -77).all() and (b["kept_idx"][total:] == -77).all()
 
 
 def test_fused_top_p_matches_oracle_end_to_end():

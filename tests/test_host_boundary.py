@@ -178,9 +178,9 @@ def test_top_p_entries_reject_bad_arguments_before_any_launch():
     assert sel(v(fake), v(fake), up.ptr(cu), v(fake), up.ptr(top_p), v(fake), v(fake), None, 0, None) == up.UP_ERR_WORKSPACE
     assert sel(v(fake), v(fake), up.ptr(cu), v(fake), up.ptr(top_p), v(fake), v(fake), v(fake), 8, None) == up.UP_ERR_WORKSPACE
     assert sel(v(fake), v(fake), up.ptr(cu), v(fake), up.ptr(top_p), v(fake), v(fake), v(0x1010), big, None) == up.UP_ERR_ALIGN
-    # a sequence with more blocks than the kernel orders in LDS
-    p_long = _params(total_tokens=32 * 4096 + 1, block_size=32)
-    cu_long = np.array([0, 32 * 4096 + 1], np.int32)
+    # a sequence with more blocks than the kernels order (65536)
+    p_long = _params(total_tokens=32 * 65536 + 1, block_size=32)
+    cu_long = np.array([0, 32 * 65536 + 1], np.int32)
     assert L.uniprefill_select_top_p(B(p_long), v(fake), v(fake), up.ptr(cu_long), v(fake), up.ptr(top_p), v(fake),
                                      v(fake), v(fake), big, None) == up.UP_ERR_UNSUPPORTED
     # compact with the count on the device
