@@ -235,16 +235,37 @@ __global__ __launch_bounds__(1024) void k_top_p_offsets(const int32_t* __restric
 
 // Expansion to tokens: block g of sequence r keeps all its tokens if the block was chosen,
 // otherwise only its sinks / window tokens; ids are written in ascending order.
+// FOLD: there is no k_top_p_offsets launch (batches of few sequences): every work-group adds up
+// the kept totals of the sequences before its own, and the first slot of a sequence -- which exists
+// for empty sequences too -- writes the sequence's entry of new_cu.
+template <bool FOLD>
 __global__ __launch_bounds__(128) void k_top_p_emit(TopPArgs a) {
   __shared__ int cnt0;
+  __shared__ int part[2];
   const int G = a.G;
   const int slot = blockIdx.x;
   const int r = locate_slot(a.cu, a.R, G, slot);
   const int c0 = a.cu[r];
   const int N = a.cu[r + 1] - c0;
   const int g = slot - slot_base(c0, r, G);
-  if (g * G >= N) return;   // slack slot (also every slot of an empty sequence)
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int seq_base;
+  if (FOLD) {
+    int acc = 0;
+    for (int q = tid; q < r; q += 128) acc += a.seq_kept[q];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
+    if (lane == 0) part[wave] = acc;
+    __syncthreads();
+    seq_base = part[0] + part[1];
+    if (g == 0 && tid == 0) {
+      a.new_cu[r] = seq_base;
+      if (r == a.R - 1) a.new_cu[a.R] = seq_base + a.seq_kept[r];
+    }
+  } else {
+    seq_base = a.new_cu[r];
+  }
+  if (g * G >= N) return;   // slack slot (also every slot of an empty sequence)
   const int i = g * G + tid;
   const bool in_block = tid < G && i < N;
   const bool keep = in_block && (a.blk_keep[slot] != 0 || i < sinks_of(a.cu_k, a.n_sink, r, N) || i >= N - a.n_obs);
@@ -252,7 +273,7 @@ __global__ __launch_bounds__(128) void k_top_p_emit(TopPArgs a) {
   const int before = __popcll(bal & ((1ull << lane) - 1ull));
   if (wave == 0 && lane == 0) cnt0 = __popcll(bal);
   __syncthreads();
-  if (keep) a.kept_idx[a.new_cu[r] + a.blk_off[slot] + before + (wave == 1 ? cnt0 : 0)] = c0 + i;
+  if (keep) a.kept_idx[seq_base + a.blk_off[slot] + before + (wave == 1 ? cnt0 : 0)] = c0 + i;
 }
 
 hipError_t launch_top_p(const Problem& pb, const float* scores, const int32_t* cu, const int32_t* cu_k,
@@ -277,9 +298,15 @@ hipError_t launch_top_p(const Problem& pb, const float* scores, const int32_t* c
   }
   if (pb.R > 0)
     hipLaunchKernelGGL(k_top_p_blocks, dim3((unsigned)pb.R), dim3(kTopPThreads), 0, s, a);
-  hipLaunchKernelGGL(k_top_p_offsets, dim3(1), dim3(1024), 0, s, a.seq_kept, pb.R, new_cu);
-  if (pb.T > 0)
-    hipLaunchKernelGGL(k_top_p_emit, dim3((unsigned)(pb.T / pb.G + pb.R)), dim3(128), 0, s, a);
+  // the sequences' offsets: a launch of their own when there are many sequences, else every
+  // work-group of the expansion adds the few totals before its sequence up itself
+  const bool fold = pb.T > 0 && pb.R <= 128;
+  if (!fold) hipLaunchKernelGGL(k_top_p_offsets, dim3(1), dim3(1024), 0, s, a.seq_kept, pb.R, new_cu);
+  if (pb.T > 0) {
+    const dim3 grid((unsigned)(pb.T / pb.G + pb.R));
+    if (fold) hipLaunchKernelGGL(k_top_p_emit<true>, grid, dim3(128), 0, s, a);
+    else hipLaunchKernelGGL(k_top_p_emit<false>, grid, dim3(128), 0, s, a);
+  }
   return hipGetLastError();
 }
 
