@@ -251,6 +251,23 @@ class Resident:
                 acc[name] += evs[i].elapsed_time(evs[i + 1])
         return {name: acc[name] / steps * 1e3 for name, _ in phases}
 
+    def time_gather_in_select(self, steps):
+        """The variant in which the kernel that selects also copies its kept rows (one launch less):
+        average microseconds per call, measured like the per-kernel loop.  Reported next to the fused
+        call's figure; it is the slower of the two, which is why the fused call gathers in a launch
+        of its own."""
+        torch, up = self.torch, self.up
+        mask = up.UP_PHASE_ALL | up.UP_PHASE_GATHER_IN_SELECT
+        for it in range(2):
+            up.uniprefill_fused_phases(*self.call_args(it), mask, stream=self.stream)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(self.stream)
+        for it in range(steps):
+            up.uniprefill_fused_phases(*self.call_args(it), mask, stream=self.stream)
+        e1.record(self.stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps * 1e3
+
     def kernel_table(self, phase_us):
         """Per-kernel figures: the sweeps against the dense bf16 MFMA peak (flops of one Q.K^T pass) and
         against HBM (K once; pass 2 also scores and kept ids), the gather against HBM."""
@@ -572,6 +589,8 @@ def main():
         row = dict(headline)
         row.update(checks)
         row["kernels_us"] = {n: kernels[n]["avg_us"] for n in kernels}
+        if not args.no_phases:
+            row["gather_in_select_us"] = round(res.time_gather_in_select(args.steps), 2)
         table[w.name] = row
         del res, q, k, hidden, hidden_out, scores, workspace
         torch.cuda.empty_cache()
@@ -588,6 +607,7 @@ def main():
             row = summarise(ri, sec_i)
             if not args.no_phases:
                 row["kernels_us"] = {n: round(v, 2) for n, v in ri.time_phases(max(3, steps_i // 2)).items()}
+                row["gather_in_select_us"] = round(ri.time_gather_in_select(steps_i), 2)
             if not args.no_cpu_baseline:
                 up.uniprefill_fused(*ri.call_args(0), stream=ri.stream)
                 row.update(ri.against_oracle()[0])

@@ -262,7 +262,11 @@ enum {
   UP_PHASE_SWEEP_SELECT = 8,         /* pass 2 (normalised weights summed per token) with the
                                         block-local top-k: scores, kept_idx */
   UP_PHASE_GATHER = 16,              /* gather of the kept rows and position ids */
-  UP_PHASE_ALL = 31
+  UP_PHASE_ALL = 31,
+  UP_PHASE_GATHER_IN_SELECT = 32     /* with UP_PHASE_SWEEP_SELECT: the kernel that selects also copies its
+                                        kept rows (no gather launch).  Measured slower than the launch of
+                                        its own on every workload; not part of UP_PHASE_ALL, kept so that
+                                        the comparison can be repeated */
 };
 
 

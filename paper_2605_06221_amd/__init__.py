@@ -9,5 +9,5 @@ from .binding import (  # noqa: F401
     uniprefill_fused_top_p_chunked, uniprefill_keep_mask, uniprefill_fused_lse, uniprefill_score_lse,
     uniprefill_fused_top_p_lse, uniprefill_score_partial, uniprefill_scores_from_partials, uniprefill_plan_chunked, uniprefill_score_chunked, uniprefill_select_chunked, uniprefill_fused_chunked,
     UP_PHASE_PLAN, UP_PHASE_ROW_STATS, UP_PHASE_MERGE_STATS, UP_PHASE_SWEEP_SELECT, UP_PHASE_GATHER,
-    UP_PHASE_ALL,
+    UP_PHASE_ALL, UP_PHASE_GATHER_IN_SELECT,
 )

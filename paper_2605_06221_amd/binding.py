@@ -32,6 +32,7 @@ EXPORTS = ["uniprefill_plan", "uniprefill_score", "uniprefill_select", "uniprefi
 
 UP_PHASE_PLAN, UP_PHASE_ROW_STATS, UP_PHASE_MERGE_STATS, UP_PHASE_SWEEP_SELECT, UP_PHASE_GATHER = 1, 2, 4, 8, 16
 UP_PHASE_ALL = 31
+UP_PHASE_GATHER_IN_SELECT = 32
 
 
 class up_params(ctypes.Structure):

@@ -49,6 +49,12 @@ Workspace workspace_layout(const Problem& pb) {
   return w;
 }
 
+GatherArgs make_gather_args(const Problem& pb, const void* hidden, const int32_t* pos, void* hidden_out,
+                            int32_t* pos_out) {
+  return GatherArgs{(const char*)hidden, (char*)hidden_out, pos, pos_out, (long long)pb.d * pb.hidden_elem_bytes,
+                    pb.h_stride * pb.hidden_elem_bytes};
+}
+
 SelectArgs make_select_args(const Problem& pb, const float* scores, const int32_t* cu, const int32_t* cu_k,
                             const float* ratio, const int32_t* new_cu, int32_t* kept_idx) {
   SelectArgs a;
@@ -375,7 +381,7 @@ int fused_impl(const up_params* p, const void* q, const void* k, const void* hid
   const Workspace w = workspace_layout(pb);
   if (pb.T > 0 && (workspace == nullptr || workspace_bytes < w.total)) return UP_ERR_WORKSPACE;
   if (pb.T > 0 && (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return UP_ERR_ALIGN;
-  if (phase_mask & ~UP_PHASE_ALL) return UP_ERR_RANGE;
+  if (phase_mask & ~(UP_PHASE_ALL | UP_PHASE_GATHER_IN_SELECT)) return UP_ERR_RANGE;
   hipStream_t s = (hipStream_t)stream;
   if (pb.T == 0) {      // no token: only the offsets (all zero) are written
     if ((phase_mask & UP_PHASE_PLAN) && launch_plan(pb, cu_dev, cu_k_dev, ratio_dev, new_cu_dev, s) != hipSuccess)
@@ -405,11 +411,13 @@ int fused_impl(const up_params* p, const void* q, const void* k, const void* hid
     return UP_ERR_HIP;
   if (phase_mask & UP_PHASE_SWEEP_SELECT) {
     const SelectArgs sa = make_select_args(pb, nullptr, cu_dev, cu_k_dev, ratio_dev, new_cu_dev, kept_idx);
-    if (launch_column_sums(pb, q, k, cu_dev, cu_k_dev, ks.paged, workspace, scores_out, &sa, s, nullptr, skip_forced) !=
-        hipSuccess)
+    // (UP_PHASE_GATHER_IN_SELECT: the kernel that selects also copies its rows -- kept for measurement)
+    const GatherArgs ga = make_gather_args(pb, hidden, pos, hidden_out, pos_out);
+    if (launch_column_sums(pb, q, k, cu_dev, cu_k_dev, ks.paged, workspace, scores_out, &sa, s, nullptr, skip_forced,
+                           (phase_mask & UP_PHASE_GATHER_IN_SELECT) ? &ga : nullptr) != hipSuccess)
       return UP_ERR_HIP;
   }
-  if (phase_mask & UP_PHASE_GATHER) {
+  if ((phase_mask & UP_PHASE_GATHER) && !((phase_mask & UP_PHASE_GATHER_IN_SELECT) && (phase_mask & UP_PHASE_SWEEP_SELECT))) {
     // one wave per kept row: measured faster than gathering inside the scoring kernel, whose
     // work-groups all reach their gather at the same moment
     const long long total_kept = host_total_kept(pb, cu_host, cu_k_host, ratio_host, nullptr);

@@ -46,6 +46,18 @@ struct Workspace {
 Workspace workspace_layout(const Problem& pb);
 
 // --- copies (Eq. 7 / Eq. 8)
+// The gather as a rider of the kernel that selects (hidden == nullptr: it does not ride).  Measured
+// slower than the launch of its own on every workload, so the fused call does not use it; it stays
+// selectable so that the comparison can be repeated.
+struct GatherArgs {
+  const char* hidden;
+  char* hidden_out;
+  const int32_t* pos;      // nullptr: no position ids
+  int32_t* pos_out;
+  long long row_bytes, stride_bytes;
+};
+GatherArgs make_gather_args(const Problem& pb, const void* hidden, const int32_t* pos, void* hidden_out,
+                            int32_t* pos_out);
 hipError_t launch_compact(const Problem& pb, const void* hidden, const int32_t* pos,
                           const int32_t* kept_idx, long long total_kept, void* hidden_out,
                           int32_t* pos_out, hipStream_t s);
@@ -142,7 +154,8 @@ hipError_t launch_lse_stats(const Problem& pb, const int32_t* cu, const int32_t*
 hipError_t launch_column_sums(const Problem& pb, const void* q, const void* k, const int32_t* cu,
                               const int32_t* cu_k, const PagedKeys* paged, void* workspace, float* scores_out,
                               const SelectArgs* sel, hipStream_t s, double* colsum_out = nullptr,
-                              bool skip_forced = false);
+                              bool skip_forced = false, const GatherArgs* gather = nullptr);
+// (gather != nullptr, with sel: the kernel that selects -- pass 2 itself or k_finish -- also copies its kept rows)
 // scores from the tensor-parallel ranks' partial column sums (Eq. 15): parts added in rank order
 hipError_t launch_scores_from_partials(const double* partials, int num_parts, long long part_stride,
                                        const int32_t* cu, int R, int T, int n_obs, int total_q_heads,

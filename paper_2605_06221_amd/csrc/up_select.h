@@ -31,6 +31,7 @@ struct SelectArgs {
 struct SelectSmem {
   unsigned long long keys[128];
   float score[kMaxKeyBlock];
+  int kept_rows[kMaxKeyBlock];   // a kernel that also gathers: the packed rows it has kept, ascending
   int cnt0, base;
 };
 
@@ -87,8 +88,9 @@ __device__ __forceinline__ unsigned phi(float x) {
 // Select block g of sequence r: writes the kept packed row ids, ascending.  Called by all
 // threads of the work-group (at least 128; whole waves); `block_scores` points at the block's scores
 // (LDS or global), indexed by the token's position inside the block.
+// list_base >= 0: the kept rows also go to sm.kept_rows, at their output position minus list_base.
 __device__ __forceinline__ void select_block(const SelectArgs& a, SelectSmem& sm, int r, int c0, int N,
-                                             int g, const float* block_scores) {
+                                             int g, const float* block_scores, int list_base = -1) {
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int n_sink = sinks_of(a.cu_k, a.n_sink, r, N);
@@ -121,7 +123,11 @@ __device__ __forceinline__ void select_block(const SelectArgs& a, SelectSmem& sm
   const int before = __popcll(bal & ((1ull << lane) - 1ull));
   if (wave == 0 && lane == 0) sm.cnt0 = __popcll(bal);
   __syncthreads();
-  if (keep) a.kept_idx[sm.base + before + (wave == 1 ? sm.cnt0 : 0)] = c0 + lo + tid;
+  if (keep) {
+    const int at = sm.base + before + (wave == 1 ? sm.cnt0 : 0);
+    a.kept_idx[at] = c0 + lo + tid;
+    if (list_base >= 0) sm.kept_rows[at - list_base] = c0 + lo + tid;
+  }
   __syncthreads();   // the shared arrays are reused by the next block
 }
 

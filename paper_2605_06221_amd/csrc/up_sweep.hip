@@ -47,6 +47,7 @@
 #include <type_traits>
 
 #include "up_common.h"
+#include "up_copy.h"
 #include "up_kernels.h"
 #include "up_select.h"
 
@@ -87,6 +88,7 @@ struct SweepArgs {
                        // context) are not scored: the caller selects and wants no scores
   int n_sink;
   SelectArgs sel;
+  GatherArgs gather;   // the kernel that selects also copies its kept rows (hidden == nullptr: no)
 };
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
@@ -514,9 +516,27 @@ __global__ __launch_bounds__(64 * NW) void k_sweep(SweepArgs a) {
     __syncthreads();
     // the block-local top-k, one selection block after the other
     const int G = a.sel.G;
+    const int g_first = kblock * (KB / G);
     const int nb = imin(KB / G, ceil_div(N - kblock * KB, G));
+    const bool gather = a.gather.hidden != nullptr;
+    int list_base = -1, list_n = 0;
+    if (gather) {      // where the key block's kept rows start in the output, and how many there are
+      SeqGeom sg{N, G, a.sel.n_obs, sinks_of(a.sel.cu_k, a.sel.n_sink, r, N), (double)a.sel.ratio[r]};
+      const int before = kept_before(sg, g_first);
+      list_base = a.sel.new_cu[r] + before;
+      list_n = kept_before(sg, g_first + nb) - before;
+    }
     for (int b = 0; b < nb; ++b)
-      select_block(a.sel, sm.tail.sel, r, c0, N, kblock * (KB / G) + b, &sm.tail.sel.score[b * G]);
+      select_block(a.sel, sm.tail.sel, r, c0, N, g_first + b, &sm.tail.sel.score[b * G], list_base);
+    if (!gather) return;
+    // the key block's kept rows (Eq. 7), dealt to the waves (select_block ends with a barrier)
+    const int wave = tid >> 6, lane = tid & 63;
+    for (int i = wave; i < list_n; i += NW) {
+      const long long row = sm.tail.sel.kept_rows[i];
+      copy_row_wave(a.gather.hidden + row * a.gather.stride_bytes,
+                    a.gather.hidden_out + (long long)(list_base + i) * a.gather.stride_bytes, a.gather.row_bytes, lane);
+      if (a.gather.pos != nullptr && lane == 0) a.gather.pos_out[list_base + i] = a.gather.pos[row];
+    }
   }
 }
 
@@ -554,7 +574,22 @@ __global__ __launch_bounds__(256) void k_finish(SweepArgs a, int key_block) {   
   }
   if (!a.do_select) return;
   __syncthreads();
-  select_block(a.sel, sm, r, c0, N, g, sm.score);
+  const bool gather = a.gather.hidden != nullptr;
+  int list_base = -1, list_n = 0;
+  if (gather) {      // where the block's kept rows go in the output, and how many there are
+    SeqGeom sg{N, G, a.sel.n_obs, sinks_of(a.sel.cu_k, a.sel.n_sink, r, N), (double)a.sel.ratio[r]};
+    list_base = a.sel.new_cu[r] + kept_before(sg, g);
+    list_n = block_kept(sg, g);
+  }
+  select_block(a.sel, sm, r, c0, N, g, sm.score, list_base);
+  if (!gather) return;
+  const int wave = tid >> 6, lane = tid & 63;      // four waves (select_block ends with a barrier)
+  for (int i = wave; i < list_n; i += 4) {
+    const long long row = sm.kept_rows[i];
+    copy_row_wave(a.gather.hidden + row * a.gather.stride_bytes,
+                  a.gather.hidden_out + (long long)(list_base + i) * a.gather.stride_bytes, a.gather.row_bytes, lane);
+    if (a.gather.pos != nullptr && lane == 0) a.gather.pos_out[list_base + i] = a.gather.pos[row];
+  }
 }
 
 // Merge the per-key-block softmax statistics of every (sequence, window row, head):
@@ -784,7 +819,8 @@ hipError_t launch_merge_stats(const Problem& pb, const int32_t* cu, const int32_
 
 hipError_t launch_column_sums(const Problem& pb, const void* q, const void* k, const int32_t* cu,
                               const int32_t* cu_k, const PagedKeys* paged, void* workspace, float* scores_out,
-                              const SelectArgs* sel, hipStream_t s, double* colsum_out, bool skip_forced) {
+                              const SelectArgs* sel, hipStream_t s, double* colsum_out, bool skip_forced,
+                              const GatherArgs* gather) {
   if (pb.T == 0) return hipSuccess;
   SweepArgs a = make_sweep_args(pb, q, k, cu, cu_k, workspace, paged);
   a.split = pb.split2;
@@ -792,6 +828,7 @@ hipError_t launch_column_sums(const Problem& pb, const void* q, const void* k, c
   a.colsum_out = colsum_out;
   if (colsum_out != nullptr) a.via_finish = 1;
   a.skip_forced = skip_forced && sel != nullptr && scores_out == nullptr && colsum_out == nullptr && !pb.has_ctx;
+  if (gather != nullptr && sel != nullptr) a.gather = *gather;
   if (sel != nullptr) { a.sel = *sel; a.do_select = 1; }
   else { a.sel.G = pb.G; a.sel.cu_k = nullptr; }
   const hipError_t e = launch_sweep<2>(pb, a, s);

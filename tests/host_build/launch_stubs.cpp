@@ -20,7 +20,7 @@ hipError_t launch_compact_counted(const Problem&, const void*, const int32_t*, c
 hipError_t launch_row_stats(const Problem&, const void*, const void*, const int32_t*, const int32_t*, const PagedKeys*, void*, hipStream_t, bool) { return hipSuccess; }
 hipError_t launch_merge_stats(const Problem&, const int32_t*, const int32_t*, void*, const float*, int32_t*, hipStream_t) { return hipSuccess; }
 hipError_t launch_lse_stats(const Problem&, const int32_t*, const int32_t*, const float*, long long, void*, const float*, int32_t*, hipStream_t) { return hipSuccess; }
-hipError_t launch_column_sums(const Problem&, const void*, const void*, const int32_t*, const int32_t*, const PagedKeys*, void*, float*, const SelectArgs*, hipStream_t, double*, bool) { return hipSuccess; }
+hipError_t launch_column_sums(const Problem&, const void*, const void*, const int32_t*, const int32_t*, const PagedKeys*, void*, float*, const SelectArgs*, hipStream_t, double*, bool, const GatherArgs*) { return hipSuccess; }
 hipError_t launch_scores_from_partials(const double*, int, long long, const int32_t*, int, int, int, int, float*, hipStream_t) { return hipSuccess; }
 
 }  // namespace up

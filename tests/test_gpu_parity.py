@@ -837,6 +837,30 @@ def test_fused_phases_one_by_one_equal_the_fused_call(lengths):
     assert up.uniprefill_fused_phases(*args, 64, check=False) == up.UP_ERR_RANGE
 
 
+@pytest.mark.parametrize("lengths", [[3000, 40, 777, 0, 129], [40000]])
+def test_gather_riding_in_the_selecting_kernel_equals_the_fused_call(lengths):
+    """UP_PHASE_GATHER_IN_SELECT (the kernel that selects copies its rows; no gather launch) gives the
+    fused call's outputs exactly, in both launch geometries and with sequences kept whole."""
+    _say("gather in select", lengths)
+    w = workloads.make_custom(name="gis", seed=18, lengths=lengths, keep_ratio=[0.37] * len(lengths), hidden_dim=200,
+                              num_q_heads=4, num_kv_heads=2, block_size=64, n_obs=128, n_sink=4)
+    a = DeviceBatch(w)
+    a.fused()
+    want = a.results()
+    _assert_fused_exact(w, a, oracle_run(w))
+    for with_scores in (True, False):      # (without scores the sequences kept whole are not scored)
+        b = DeviceBatch(w)
+        args = (b.p, b.q, b.k, b.hidden, b.pos, b.cu, b.cu_host, b.ratio, b.ratio_host, b.hidden_out, b.pos_out,
+                b.kept_idx, b.new_cu, b.scores if with_scores else None, b.workspace, b.ws_bytes)
+        up.uniprefill_fused_phases(*args, up.UP_PHASE_ALL | up.UP_PHASE_GATHER_IN_SELECT)
+        got = b.results()
+        for key in want:
+            if key == "scores" and not with_scores:
+                continue
+            np.testing.assert_array_equal(got[key], want[key], err_msg=key)
+        assert b.canaries_intact()
+
+
 def test_slot_mapping_of_a_compacted_stream():
     _say("slot mapping")
     rng = np.random.default_rng(60)

@@ -215,3 +215,30 @@ def test_quantise_floor_and_rounding():
     assert s.dtype == np.float32
     np.testing.assert_array_equal(s, np.array([1.0, 2.0 ** -64, 0.0, 0.0, 0.0, np.float32(1 / 3)], dtype=np.float32))
     assert not np.signbit(s).any()
+
+
+def test_heavy_tailed_workload_offers_no_tiles_to_skip_exactly():
+    """A census on the 131072-token workload with lognormal-scaled keys (one query head; plain numpy on the
+    workload's own tensors): how many 32-row x 32-key tiles of the second scoring pass carry only weights
+    that underflow to exactly zero in fp32 (relative to the row's final maximum, below 2^-127)?  Next to
+    none: the logits are symmetric around zero and the row maxima are 80-280 in log2 units, so about half
+    of all weights are representable and practically every tile holds some.  A cut that would empty most
+    tiles (2^-64) is far above the 2^-90 or so that the selection's margins allow next to the 2^-64 score
+    floor, so skipping tiles cannot be exact on this data."""
+    import workloads
+    w = workloads.make_config(4, hidden_dim=8)
+    N, n = w.total_tokens, w.n_obs
+    q = workloads.bf16_bits_to_f32(w.q[N - n:, 0])                 # [n, D], query head 0
+    k = workloads.bf16_bits_to_f32(w.k[:, 0])                      # [N, D], its kv head
+    c = w.softmax_scale * math.log2(math.e)
+    s = (q.astype(np.float64) @ k.astype(np.float64).T) * c        # logits in log2 units
+    rows = np.arange(N - n, N)[:, None]
+    s = np.where(np.arange(N)[None, :] <= rows, s, -np.inf)
+    x = s - s.max(axis=1, keepdims=True)
+    full = (N // 32) * 32
+    def live_tiles(cut):
+        alive = (x[:, :full] > cut).reshape(n // 32, 32, full // 32, 32)
+        return float(alive.any(axis=(1, 3)).mean())
+    assert float((x > -127).mean()) > 0.4                          # about half of the weights are representable
+    assert live_tiles(-127.0) > 0.99                               # exact skipping: nothing to skip
+    assert live_tiles(-64.0) < 0.5                                 # an (inexact) 2^-64 cut would empty most tiles
