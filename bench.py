@@ -57,6 +57,56 @@ def measured_traffic(workload, kernel):
     return (None if prov["stale"] else int(ent)), prov
 
 
+def record_traffic(idx, fetch_csv, write_csv, profile):
+    """Turn the rocprofv3 counter tables of two runs of `bench.py --config i --calibrate-copy ...` (one
+    with --pmc FETCH_SIZE, one with --pmc WRITE_SIZE; KiB per dispatch) into this workload's entry of
+    profiles/hbm_traffic.json, stamped with the digest of the kernel sources at hand.  The largest
+    k_rows dispatch is the calibration copy, an identity gather of all T hidden rows: it reads the rows,
+    T positions and T indices and writes the rows and T positions, which fixes each counter's scale."""
+    import collections
+    import csv
+    import workloads
+    workload = workloads.CONFIG_NAMES[idx]
+    T = workloads.make_config(idx, hidden_dim=8).total_tokens      # (generated only for its lengths)
+    row = {1: 1024, 2: 4096, 3: 4096, 4: 5120, 5: 4096}[idx] * 2   # bytes of a hidden row (bf16)
+    def table(path):
+        agg = collections.defaultdict(list)
+        for r in csv.DictReader(open(path)):
+            agg[r["Kernel_Name"]].append(float(r["Counter_Value"]) * 1024.0)
+        return agg
+    rd, wr = table(fetch_csv), table(write_csv)
+    rows = next(k for k in rd if "k_rows<false>" in k)
+    scale_r = (T * row + 8 * T) / max(rd[rows])
+    scale_w = (T * row + 4 * T) / max(wr[rows])
+    def mean(agg, key, drop_max=False):
+        v = sorted(x for k in agg if key in k for x in agg[k])
+        if drop_max:
+            v = v[:-1]
+        return sum(v) / len(v) if v else 0.0
+    def both(key, drop_max=False):
+        return mean(rd, key, drop_max) * scale_r + mean(wr, key, drop_max) * scale_w
+    ent = {"row_stats": round(both("k_sweep<1")), "merge_stats": round(both("k_combine")),
+           "sweep_select": round(both("k_sweep<2") + both("k_finish")), "gather": round(both("k_rows<false>", True))}
+    try:
+        rec = json.load(open(TRAFFIC_FILE))
+    except (OSError, ValueError):
+        rec = {}
+    digest = csrc_digest()
+    if rec.get("csrc_sha256") != digest:      # figures taken on other sources do not stay next to new ones
+        rec["bytes"], rec["profiles"], rec["scale"] = {}, {}, {}
+    rec["comment"] = ("HBM bytes per launch (reads + writes) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by "
+                      "what the same counter reads for an identity gather of known size in the same run; written by "
+                      "`bench.py --record-traffic`; the profile summaries named here give the commands and tables")
+    rec["csrc_sha256"] = digest
+    rec.setdefault("bytes", {})[workload] = ent
+    rec.setdefault("profiles", {})[workload] = profile
+    rec.setdefault("scale", {})[workload] = {"FETCH_SIZE": round(scale_r, 4), "WRITE_SIZE": round(scale_w, 4)}
+    with open(TRAFFIC_FILE, "w") as f:
+        json.dump(rec, f, indent=1)
+        f.write("\n")
+    print(json.dumps({workload: ent, "scale": rec["scale"][workload], "csrc_sha256": digest}))
+
+
 def algorithmic_bytes(w, total_kept):
     """Bytes the method must move: K once, a score per token, the kept rows in and out,
     index/position words, and the query window."""
@@ -393,10 +443,17 @@ def main():
                     help="instead of the benchmark line: operator timing over block size x window and over "
                          "context length / batch size, as one JSON object")
     ap.add_argument("--csrc-digest", action="store_true", help="print the digest of the kernel sources and exit")
+    ap.add_argument("--record-traffic", nargs=3, metavar=("FETCH_CSV", "WRITE_CSV", "PROFILE_MD"),
+                    help="no GPU work: read the counter_collection.csv of a --pmc FETCH_SIZE and of a --pmc WRITE_SIZE "
+                         "run of `bench.py --config i --calibrate-copy` and write that workload's entry of "
+                         "profiles/hbm_traffic.json (with the digest of the kernel sources)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one identity gather of the whole hidden tensor (a plain copy of known "
                          "size): the reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
+    if args.record_traffic:
+        record_traffic(args.config, *args.record_traffic)
+        return 0
     if args.csrc_digest:
         print(csrc_digest())
         return
