@@ -9,6 +9,9 @@
 //           with random bf16 operand bits; two orderings of the same work (in-wave software pipeline
 //           over 16x16x32 sub-tiles; half the waves one phase late).
 //   part B  issue cost of single vector instructions, alone and next to a chain of MFMAs.
+//   part C  the tile of part A rebuilt step by step toward the sweep kernel's loop: a barrier per unit of
+//           four tiles; the rows staged global -> registers -> LDS into a double buffer; the key
+//           operands reloaded from global memory every fifth unit; the per-row table staged per unit.
 // The shader clock is read with s_memtime against the 100 MHz s_memrealtime counter.
 #include <hip/hip_runtime.h>
 
@@ -212,6 +215,82 @@ __global__ __launch_bounds__(1024) void k_issue(float* out, long long* clk, int 
   out[blockIdx.x * 1024 + tid] = s + (float)d + __builtin_bit_cast(float, l[0]);
 }
 
+// part C.  LEVEL 0: free-running tiles (one row buffer).  1: + barrier per unit.  2: + rows staged (global ->
+// registers at the top of a unit, registers -> LDS at its end, double buffer).  3: + key operands reloaded
+// every 5 units (a work-group's 128 KB).  4: + the per-row table staged per unit.
+template <int LEVEL>
+__global__ __launch_bounds__(1024) void k_morph(float* out, int units, float c, long long* clk, const u32x4* __restrict__ gq,
+                                                const u32x4* __restrict__ gk, const float2* __restrict__ gc) {
+  __shared__ __align__(16) unsigned char q[2][128 * kQRow];
+  __shared__ __align__(16) float2 cst[2][128];
+  const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
+  for (int b = 0; b < 2; ++b) {
+    for (int i = tid; i < 128 * kQRow / 4; i += 1024) ((unsigned*)q[b])[i] = rnd_bf16x2(i + b * 7777);
+    for (int i = tid; i < 128; i += 1024) cst[b][i] = make_float2(-3.0f - 0.01f * i, 1.0f / (1.0f + i));
+  }
+  __syncthreads();
+  u32x4 kf[8];
+  for (int kk = 0; kk < 8; ++kk)
+    for (int j = 0; j < 4; ++j) kf[kk][j] = rnd_bf16x2(tid * 64 + kk * 4 + j + 12345);
+  double col64 = 0.0;
+  long long c0 = 0, w0 = 0;
+  if (tid == 0) { c0 = clock64(); w0 = wall_clock64(); }
+  f32x16 acc;
+  const int my_row = tid / 16, my_col = tid % 16;      // staging: 128 rows x 16 pieces, rows r and r + 64 per thread
+  u32x4 pre0 = {0, 0, 0, 0}, pre1 = {0, 0, 0, 0};
+  float2 pre_c = make_float2(0.f, 0.f);
+  for (int u = 0; u < units; ++u) {
+    const int buf = LEVEL >= 2 ? (u & 1) : 0;
+    if (LEVEL >= 2) {      // every work-group streams the same 40 units of 32 KB, as the sweeps stream one window
+      const u32x4* src = gq + (size_t)((u + 1) % 40) * 2048;
+      pre0 = src[my_row * 16 + my_col];
+      pre1 = src[(my_row + 64) * 16 + my_col];
+    }
+    if (LEVEL >= 4) pre_c = gc[((u + 1) % 40) * 128 + (tid & 127)];
+#pragma unroll
+    for (int rt = 0; rt < 4; ++rt) {
+      u32x4 qv[8];
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) qv[kk] = *(const u32x4*)(&q[buf][(rt * 32 + l32) * kQRow + half * 16 + kk * 32]);
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf(qv[kk]), bf(kf[kk]), acc, 0, 0, 0);
+      if (LEVEL >= 3 && rt == 3 && (u % 5) == 4) {
+        const u32x4* ks = gk + ((size_t)blockIdx.x * 1024 + tid) * 64 + (size_t)((u / 5) % 8) * 8;
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) kf[kk] = ks[kk];
+      }
+      float a0 = 0.f, a1 = 0.f;
+#pragma unroll
+      for (int e = 0; e < 16; e += 2) {
+        const int row0 = rt * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
+        const f32x4 cv = *(const f32x4*)(&cst[LEVEL >= 4 ? buf : 0][row0]);
+        a0 = fmaf(ex2(fmaf(acc[e], c, cv[0])), cv[1], a0);
+        a1 = fmaf(ex2(fmaf(acc[e + 1], c, cv[2])), cv[3], a1);
+      }
+      col64 += (double)(a0 + a1);
+      asm volatile("" : "+v"(col64) : : "memory");
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (LEVEL >= 2) {
+      *(u32x4*)(&q[buf ^ 1][my_row * kQRow + my_col * 16]) = pre0;
+      *(u32x4*)(&q[buf ^ 1][(my_row + 64) * kQRow + my_col * 16]) = pre1;
+    }
+    if (LEVEL >= 4 && tid < 128) cst[buf ^ 1][tid] = pre_c;
+    if (LEVEL >= 1) __syncthreads();
+  }
+  if (tid == 0 && blockIdx.x == 0) { clk[0] = clock64() - c0; clk[1] = wall_clock64() - w0; }
+  out[blockIdx.x * 1024 + tid] = (float)col64;
+}
+__global__ void k_fill_bits(unsigned* p, size_t n, unsigned salt) {
+  for (size_t i = blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) p[i] = rnd_bf16x2((unsigned)i + salt);
+}
+__global__ void k_fill_table(float2* p, int n) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = make_float2(-3.0f - 0.01f * (i & 127), 1.0f / (1.0f + (i & 127)));
+}
+
 static float* g_out;
 static long long* g_clk;
 template <class F>
@@ -258,6 +337,19 @@ static void run_issue(int iters) {
   fflush(stdout);
 }
 
+static u32x4 *g_rows, *g_keys;
+static float2* g_table;
+template <int LEVEL>
+static void run_morph(const char* name, int units) {
+  const float ms = time_ms([&] {
+    hipLaunchKernelGGL((k_morph<LEVEL>), dim3(256), dim3(1024), 0, 0, g_out, units, 0.1275f, g_clk, g_rows, g_keys, g_table);
+  }, 5);
+  const double ghz = ghz_of_last_run();
+  const double tiles = (double)units * 4 * 4;
+  printf("| %-66s | %7.1f | %6.1f | %5.0f | %4.2f |\n", name, ms * 1e3, ms * 1e6 / tiles, ms * 1e6 / tiles * ghz, ghz);
+  fflush(stdout);
+}
+
 int main() {
   CHECK(hipMalloc(&g_out, 256 * 1024 * 4));
   CHECK(hipMalloc(&g_clk, 64));
@@ -283,5 +375,23 @@ int main() {
   run_issue<OP_EXP, 12>(iters);
   run_issue<OP_FMA64, 6>(iters);
   run_issue<OP_LDS, 6>(iters);
+
+  const size_t n_rows = 40 * 2048, n_keys = (size_t)256 * 1024 * 64;      // 16-byte pieces: 1.25 MB of rows, 256 MB of keys
+  CHECK(hipMalloc(&g_rows, n_rows * 16));
+  CHECK(hipMalloc(&g_keys, n_keys * 16));
+  CHECK(hipMalloc(&g_table, 40 * 128 * sizeof(float2)));
+  hipLaunchKernelGGL(k_fill_bits, dim3(1024), dim3(256), 0, 0, (unsigned*)g_rows, n_rows * 4, 1u);
+  hipLaunchKernelGGL(k_fill_bits, dim3(4096), dim3(256), 0, 0, (unsigned*)g_keys, n_keys * 4, 99u);
+  hipLaunchKernelGGL(k_fill_table, dim3(20), dim3(256), 0, 0, g_table, 40 * 128);
+  CHECK(hipDeviceSynchronize());
+  printf("\npart C: the tile of part A (both pipes) rebuilt toward the sweep kernel's loop, 160 units of 4 tiles per wave\n");
+  printf("| %-66s | us      | ns/tile | cycles/tile | GHz |\n|---|---|---|---|---|\n", "what the loop does besides the tiles");
+  for (int rep = 0; rep < 2; ++rep) {
+    run_morph<0>("nothing (free-running tiles)", units);
+    run_morph<1>("+ a barrier per unit of four tiles", units);
+    run_morph<2>("+ rows staged global -> registers -> LDS, double buffer", units);
+    run_morph<3>("+ key operands reloaded every fifth unit (128 KB per work-group)", units);
+    run_morph<4>("+ per-row table staged per unit", units);
+  }
   return 0;
 }
