@@ -613,7 +613,7 @@ __global__ __launch_bounds__(32 * LPR) void k_combine(const int32_t* __restrict_
                                                       const float2* __restrict__ stat_part,
                                                       float2* __restrict__ stat_fin, int R, int Hq,
                                                       int n_obs, int row_slots, int key_block,
-                                                      PlanInCombine plan) {
+                                                      int heads_per_group, PlanInCombine plan) {
   __shared__ float sh_m[LPR][33];
   __shared__ double sh_l[LPR][33];
   if (plan.ratio != nullptr && blockIdx.x == 0 && blockIdx.y == 0) {
@@ -623,10 +623,9 @@ __global__ __launch_bounds__(32 * LPR) void k_combine(const int32_t* __restrict_
   }
   const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
   const int u = blockIdx.x * 32 + tx;
-  const int h = blockIdx.y;
   bool live = u < row_slots;
   int n_blocks = 0;
-  const float2* p = stat_part;
+  const float2* p_row = stat_part;
   const size_t stride = (size_t)Hq * n_obs;
   if (live) {
     const int r = locate_rowslot(cu, R, n_obs, u);
@@ -637,40 +636,46 @@ __global__ __launch_bounds__(32 * LPR) void k_combine(const int32_t* __restrict_
     if (live) {
       const int ck0 = cu_k[r];
       n_blocks = ceil_div(cu_k[r + 1] - ck0, key_block);
-      p = stat_part + (size_t)slot_base(ck0, r, key_block) * stride + (size_t)h * n_obs + jj;
+      p_row = stat_part + (size_t)slot_base(ck0, r, key_block) * stride + jj;
     }
   }
   if (__syncthreads_or(live) == 0) return;
-  float m = -INFINITY;
-  double L = 0.0;
-  for (int b0 = ty * 16; b0 < n_blocks; b0 += 16 * LPR) {
-    float2 v[16];
-#pragma unroll
-    for (int i = 0; i < 16; ++i)
-      v[i] = b0 + i < n_blocks ? p[(size_t)(b0 + i) * stride] : make_float2(-INFINITY, 0.0f);
-    float mc = v[0].x;
-#pragma unroll
-    for (int i = 1; i < 16; ++i) mc = fmaxf(mc, v[i].x);
-    if (mc != -INFINITY) {
-      double Lc = 0.0;
+  // the work-group's heads one after the other: the look-up of the row's sequence above (a chain of
+  // dependent loads) is paid once for all of them
+  for (int h = blockIdx.y * heads_per_group; h < (blockIdx.y + 1) * heads_per_group; ++h) {
+    const float2* p = p_row + (size_t)h * n_obs;
+    float m = -INFINITY;
+    double L = 0.0;
+    for (int b0 = ty * 16; b0 < n_blocks; b0 += 16 * LPR) {
+      float2 v[16];
 #pragma unroll
       for (int i = 0; i < 16; ++i)
-        if (v[i].x != -INFINITY) Lc += (double)(v[i].y * exp2f(v[i].x - mc));
-      const float mn = fmaxf(m, mc);
-      L = (m == -INFINITY ? 0.0 : L * exp2((double)m - (double)mn)) + Lc * exp2((double)mc - (double)mn);
-      m = mn;
+        v[i] = b0 + i < n_blocks ? p[(size_t)(b0 + i) * stride] : make_float2(-INFINITY, 0.0f);
+      float mc = v[0].x;
+#pragma unroll
+      for (int i = 1; i < 16; ++i) mc = fmaxf(mc, v[i].x);
+      if (mc != -INFINITY) {
+        double Lc = 0.0;
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+          if (v[i].x != -INFINITY) Lc += (double)(v[i].y * exp2f(v[i].x - mc));
+        const float mn = fmaxf(m, mc);
+        L = (m == -INFINITY ? 0.0 : L * exp2((double)m - (double)mn)) + Lc * exp2((double)mc - (double)mn);
+        m = mn;
+      }
     }
-  }
-  sh_m[ty][tx] = m;
-  sh_l[ty][tx] = L;
-  __syncthreads();
-  if (ty == 0 && live) {
-    float mm = -INFINITY;
-    for (int i = 0; i < LPR; ++i) mm = fmaxf(mm, sh_m[i][tx]);
-    double tot = 0.0;
-    for (int i = 0; i < LPR; ++i)
-      if (sh_m[i][tx] != -INFINITY) tot += sh_l[i][tx] * exp2((double)sh_m[i][tx] - (double)mm);
-    stat_fin[(size_t)h * row_slots + u] = make_float2(-mm, (float)(1.0 / tot));
+    sh_m[ty][tx] = m;
+    sh_l[ty][tx] = L;
+    __syncthreads();
+    if (ty == 0 && live) {
+      float mm = -INFINITY;
+      for (int i = 0; i < LPR; ++i) mm = fmaxf(mm, sh_m[i][tx]);
+      double tot = 0.0;
+      for (int i = 0; i < LPR; ++i)
+        if (sh_m[i][tx] != -INFINITY) tot += sh_l[i][tx] * exp2((double)sh_m[i][tx] - (double)mm);
+      stat_fin[(size_t)h * row_slots + u] = make_float2(-mm, (float)(1.0 / tot));
+    }
+    __syncthreads();      // the shared arrays are reused by the next head
   }
 }
 
@@ -807,13 +812,20 @@ hipError_t launch_merge_stats(const Problem& pb, const int32_t* cu, const int32_
   }
   const PlanInCombine plan{plan_ratio, plan_new_cu, cu_k, pb.G, pb.n_sink};
   const SweepArgs a = make_sweep_args(pb, nullptr, nullptr, cu, cu_k, workspace);
-  const dim3 grid((unsigned)((pb.row_slots + 31) / 32), (unsigned)pb.Hq);
+  // a work-group takes 32 row slots x heads_per_group heads: with many (mostly short) sequences the
+  // grid is large and much of a work-group's time is the look-up of its rows' sequence, so up to four
+  // heads share one as long as the grid keeps eight work-groups per CU (more heads per work-group
+  // were slower: the work-groups with live rows then run their heads one after the other)
+  const int row_groups = (pb.row_slots + 31) / 32;
+  int hpg = 1;
+  while (hpg < 4 && pb.Hq % (2 * hpg) == 0 && (long long)row_groups * (pb.Hq / (2 * hpg)) >= 2048) hpg *= 2;
+  const dim3 grid((unsigned)row_groups, (unsigned)(pb.Hq / hpg));
   if (pb.max_key_blocks > 128)
     hipLaunchKernelGGL(k_combine<32>, grid, dim3(1024), 0, s, cu, a.cu_k, a.stat_part, a.stat_fin, pb.R, pb.Hq,
-                       pb.n_obs, pb.row_slots, pb.key_block, plan);
+                       pb.n_obs, pb.row_slots, pb.key_block, hpg, plan);
   else
     hipLaunchKernelGGL(k_combine<8>, grid, dim3(256), 0, s, cu, a.cu_k, a.stat_part, a.stat_fin, pb.R, pb.Hq,
-                       pb.n_obs, pb.row_slots, pb.key_block, plan);
+                       pb.n_obs, pb.row_slots, pb.key_block, hpg, plan);
   return hipGetLastError();
 }
 
