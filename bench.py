@@ -28,15 +28,20 @@ TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.json")
 
 
 def csrc_digest():
-    """SHA-256 over the library's kernel sources: what a counter measurement is valid for (the
-    stand-alone pipe microbenchmark is not part of the library)."""
+    """SHA-256 over the code of the library's kernel sources: what a counter measurement is valid for.
+    Comments and white space are left out (an edit to a comment does not change what was measured), and
+    so is the stand-alone pipe microbenchmark, which is not part of the library."""
     import hashlib
+    import re
     d = os.path.join(ROOT, "paper_2605_06221_amd", "csrc")
     h = hashlib.sha256()
     for name in sorted(os.listdir(d)):
         if name.endswith((".hip", ".h")) and name != "up_pipes_bench.hip":
+            text = open(os.path.join(d, name), encoding="utf-8").read()
+            text = re.sub(r"/\*.*?\*/", " ", text, flags=re.S)      # block comments
+            text = re.sub(r"//[^\n]*", " ", text)                   # line comments (no string in these sources holds "//")
             h.update(name.encode())
-            h.update(open(os.path.join(d, name), "rb").read())
+            h.update(" ".join(text.split()).encode())
     return h.hexdigest()
 
 

@@ -5,14 +5,16 @@
 // attention sinks and the query window always kept.
 //
 // Kept counts depend on the data, so the outputs are sized for the worst case
-// and the totals stay on the device (new_cu_seqlens).  Five launches:
+// and the totals stay on the device (new_cu_seqlens).  Four launches, five for batches of more than
+// 128 sequences:
 //   k_block_mass     one wave per block: its mass
 //   k_top_p_rank     place of every block in the descending order of the keys, by counting the
 //                    larger keys: 256 x 256 pairs per work-group, spread over the chip
 //   k_top_p_blocks   one work-group per sequence: the masses put in that order, their running sum
 //                    (chunks of 64 positions, one wave each), threshold, keep flags and in-sequence
 //                    output offsets of the blocks
-//   k_top_p_offsets  prefix sum of the per-sequence totals
+//   k_top_p_offsets  prefix sum of the per-sequence totals (large batches only: for up to 128
+//                    sequences every work-group of k_top_p_emit forms the few sums it needs itself)
 //   k_top_p_emit     one work-group per block: kept token ids, ascending
 //
 // Arithmetic that decides integers is fixed so that it can be matched bit for
