@@ -395,28 +395,32 @@ def summarise(res, sec_per_step):
 def bench_sweep(args, up, workloads, np, torch):
     """Operator-only timing tables (the shapes of the paper's block-size, window and context/batch
     studies): block size G x observation window n on one 32768-token Llama-3-8B-shaped sequence, and
-    the context-length / batch-size grid.  One JSON object with both tables."""
-    def run(lengths, G, n_obs, ratio=0.3):
-        w = workloads.make_custom(name=f"llama8b_{len(lengths)}x{max(lengths)}_G{G}_n{n_obs}", seed=100, lengths=lengths,
-                                  keep_ratio=[ratio] * len(lengths), hidden_dim=4096, num_q_heads=32, num_kv_heads=8,
-                                  block_size=G, n_obs=n_obs)
+    the context-length / batch-size grid; and the head dimension on one 131072-token sequence.  One JSON
+    object with the three tables."""
+    def run(lengths, G, n_obs, ratio=0.3, head_dim=128):
+        w = workloads.make_custom(name=f"llama8b_{len(lengths)}x{max(lengths)}_G{G}_n{n_obs}_D{head_dim}", seed=100,
+                                  lengths=lengths, keep_ratio=[ratio] * len(lengths), hidden_dim=4096, num_q_heads=32,
+                                  num_kv_heads=8, block_size=G, n_obs=n_obs, head_dim=head_dim)
         res = Resident(w, up, np, torch, 1 if w.total_tokens >= 131072 else 2)
         res.ramp_clocks(args.ramp_ms)
         sec, _ = res.time_fused(args.steps, args.warmup)
         ph = res.time_phases(max(3, args.steps // 4))
         row = summarise(res, sec)
-        row.update(G=G, n_obs=n_obs, lengths=f"{len(lengths)}x{max(lengths)}",
+        row.update(G=G, n_obs=n_obs, head_dim=head_dim, lengths=f"{len(lengths)}x{max(lengths)}",
                    kernels_us={k: round(v, 1) for k, v in ph.items()})
         del res
         torch.cuda.empty_cache()
-        print(f"[bench] sweep {row['lengths']} G={G} n={n_obs}: {row['ms_per_step'] * 1e3:.1f} us", file=sys.stderr, flush=True)
+        print(f"[bench] sweep {row['lengths']} G={G} n={n_obs} D={head_dim}: {row['ms_per_step'] * 1e3:.1f} us", file=sys.stderr,
+              flush=True)
         return row
     block_window = [run([32768], G, n) for G in (32, 64, 128) for n in (32, 128, 512)]
     grid = [run(ls, 128, 128) for ls in ([4096], [8192], [16384], [32768], [65536], [131072], [8192] * 4, [8192] * 16,
                                          [8192] * 64)]
+    head_dims = [run([131072], 128, 128, head_dim=D) for D in (64, 128, 256)]
     print(json.dumps({"metric": "fused score+select+compact operator, microseconds per call", "dtype": "bf16",
                       "data": "synthetic", "steps": args.steps, "warmup": args.warmup,
-                      "block_size_x_window_32k": block_window, "context_and_batch_grid": grid}), flush=True)
+                      "block_size_x_window_32k": block_window, "context_and_batch_grid": grid,
+                      "head_dim_128k": head_dims}), flush=True)
 
 
 def main():
